@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-block fused mixed-precision Adam step on one MI355X.
+
+A "step" is one pass of the whole hot path over one block whose inputs are already resident in
+HBM: lohan_grad_sqnorm (one 2 B/element read of the fp16 gradients giving the overflow flag and
+the squared norm) followed by lohan_adam_block_step with LOHAN_FLAG_PRECHECKED (the 28 B/element
+stream: unscale, Adam/AdamW with bias correction, fp32 write-back, bf16 copy).  The metric is
+Adam-updated elements per second; the roofline object prices the dominant kernel
+(k_adam_block_step, 28 algorithmic bytes per element) against the 8 TB/s HBM peak using HIP events
+recorded on the launch stream inside the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt13b|gpt175b|gpt_h768|stream13b]
+
+Prints ONE JSON line.  There is no multi-GPU path: the step is elementwise and would shard by
+contiguous element ranges, but this build runs on one GPU only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+ADAM_BYTES_PER_ELEM = 28        # read g16 2 + p 4 + m 4 + v 4, write p 4 + m 4 + v 4 + bf16 2
+REDUCE_BYTES_PER_ELEM = 2       # one read of g16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt13b",
+                    choices=["gpt13b", "gpt175b", "gpt_h768", "stream13b"])
+    ap.add_argument("--variant", type=int, default=None, help="kernel launch-shape override")
+    ap.add_argument("--wgs-per-cu", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--blocks", type=int, default=40, help="stream13b: number of blocks")
+    return ap.parse_args()
+
+
+def cpu_baseline(block, wl, sample_elems=1 << 26):
+    """Time the CPU oracle, as it stands, on the first `sample_elems` elements of the same block
+    (copied to the host before the timed GPU region)."""
+    import numpy as np
+    from oracle import reference as oracle
+    from paper_2403_06504_amd import synthetic_inputs as synth
+
+    k = min(sample_elems, wl.n)
+    host = {name: synth.to_numpy_bits(block[name][:k]) for name in ("p", "m", "v", "g", "p16")}
+    hy = wl.hyper()
+    threads = min(oracle.max_threads(), 16 if os.environ.get("OMP_NUM_THREADS") is None
+                  else int(os.environ["OMP_NUM_THREADS"]))
+    threads = max(1, threads)
+
+    def time_step(nthreads, reps):
+        best = float("inf")
+        for r in range(reps):
+            t0 = time.perf_counter()
+            f = oracle.adam_block_step(host["p"], host["m"], host["v"], host["g"], host["p16"],
+                                       nthreads=nthreads, **dict(hy, step=hy["step"] + r))
+            best = min(best, time.perf_counter() - t0)
+            assert f == 0
+        return best
+
+    t_multi = time_step(threads, 5)
+    t_single = time_step(1, 2)
+    t0 = time.perf_counter()
+    oracle.grad_sqnorm(host["g"], wl.loss_scale)
+    t_norm = time.perf_counter() - t0
+    return {
+        "value": k / t_multi, "unit": "elements/s", "cores": threads, "kind": "oracle",
+        "sample": f"first {k} elements of the {wl.name} block; oracle Adam block step (overflow "
+                  f"check + update + bf16 copy), best of 5 on {threads} OpenMP threads",
+        "single_thread_value": k / t_single,
+        "single_thread_with_sqnorm_value": k / (t_single + t_norm),
+        "host_cpus": os.cpu_count(),
+    }
+
+
+def bench_block(args, torch, lohan, synth):
+    wl = synth.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    block = synth.make_block(wl, seed=0, device=dev)
+    n = wl.n
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    sqnorm = torch.zeros(1, dtype=torch.float64, device=dev)
+    ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+    hy = wl.hyper()
+
+    base = None if args.no_cpu_baseline else cpu_baseline(block, wl)
+
+    def one_step(t, ev=None):
+        lohan.lohan_grad_sqnorm(block["g"], n, wl.loss_scale, sqnorm, flag, ws)
+        if ev is not None:
+            ev[0].record()
+        lohan.lohan_adam_block_step(block["p"], block["m"], block["v"], block["g"], block["p16"],
+                                    n, hy["lr"], hy["beta1"], hy["beta2"], hy["eps"],
+                                    hy["weight_decay"], t, hy["loss_scale"], flag,
+                                    lohan.LOHAN_FLAG_PRECHECKED, None)
+        if ev is not None:
+            ev[1].record()
+
+    for w in range(args.warmup):
+        one_step(hy["step"] + w)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
+               torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        events[k][2].record()
+        one_step(hy["step"] + args.warmup + k, events[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    assert int(flag.cpu().item()) == 0, "synthetic gradients must not overflow"
+    adam_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    reduce_ms = sum(e[2].elapsed_time(e[0]) for e in events) / args.steps
+    ms_per_step = elapsed * 1e3 / args.steps
+    achieved = ADAM_BYTES_PER_ELEM * n / (adam_ms * 1e-3) / 1e9
+    out = {
+        "metric": "adam_updated_elements_per_sec",
+        "value": n / (elapsed / args.steps),
+        "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: one GPT block, n={n} elements "
+                               f"(fp32 p/m/v, fp16 grads x loss scale {wl.loss_scale:g}, "
+                               f"bf16 copy), AdamW step {wl.step}",
+                   "elements": n, "bytes_per_element_step": 30,
+                   "launch_config": list(lohan.lohan_get_launch_config())},
+        "step_hbm_gbps": (ADAM_BYTES_PER_ELEM + REDUCE_BYTES_PER_ELEM) * n /
+                         (elapsed / args.steps) / 1e9,
+        "roofline": {"kernel": "k_adam_block_step", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": None, "avg_launch_ms": adam_ms,
+                     "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
+        "reduce_kernel": {"kernel": "k_grad_reduce+k_grad_finalize", "avg_ms": reduce_ms,
+                          "achieved_gbps": REDUCE_BYTES_PER_ELEM * n / (reduce_ms * 1e-3) / 1e9},
+        "cpu_baseline": base,
+    }
+    return out
+
+
+def bench_stream(args, torch, lohan, synth):
+    """13B-shaped model stream: blocks issued one at a time, last block first, alternating two
+    side streams, each behind the event of a synthetic bf16 backward GEMM on the main stream."""
+    wl = synth.WORKLOADS["gpt13b"]
+    dev = "cuda:0"
+    nblocks = args.blocks
+    n = wl.n
+    blocks = [synth.make_block(wl, seed=i, device=dev) for i in range(nblocks)]
+    flags = [torch.zeros(1, dtype=torch.int32, device=dev) for _ in range(nblocks)]
+    norms = [torch.zeros(1, dtype=torch.float64, device=dev) for _ in range(nblocks)]
+    wss = [torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+           for _ in range(2)]
+    side = [torch.cuda.Stream(), torch.cuda.Stream()]
+    a = torch.randn(2048, 5120, device=dev, dtype=torch.bfloat16)
+    b = torch.randn(5120, 20480, device=dev, dtype=torch.bfloat16)
+    hy = wl.hyper()
+    main = torch.cuda.current_stream()
+
+    def gemm_only():
+        for _ in range(nblocks):
+            torch.matmul(a, b)
+
+    def one_pass(t):
+        for i in reversed(range(nblocks)):
+            torch.matmul(a, b)
+            ev = torch.cuda.Event()
+            ev.record(main)
+            s = side[i % 2]
+            s.wait_event(ev)
+            blk = blocks[i]
+            lohan.lohan_grad_sqnorm(blk["g"], n, wl.loss_scale, norms[i], flags[i], wss[i % 2],
+                                    stream=s)
+            lohan.lohan_adam_block_step(blk["p"], blk["m"], blk["v"], blk["g"], blk["p16"], n,
+                                        hy["lr"], hy["beta1"], hy["beta2"], hy["eps"],
+                                        hy["weight_decay"], t, hy["loss_scale"], flags[i],
+                                        lohan.LOHAN_FLAG_PRECHECKED, None, stream=s)
+        for s in side:
+            main.wait_stream(s)
+
+    for w in range(args.warmup):
+        one_pass(hy["step"] + w)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        gemm_only()
+    torch.cuda.synchronize()
+    gemm_s = (time.perf_counter() - t0) / args.steps
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_pass(hy["step"] + args.warmup + k)
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t0) / args.steps
+    assert all(int(f.cpu().item()) == 0 for f in flags)
+    total = n * nblocks
+    return {
+        "metric": "adam_updated_elements_per_sec", "value": total / elapsed,
+        "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"stream13b: {nblocks} blocks of n={n}, 2 side streams, one bf16 "
+                               "GEMM 2048x5120x20480 per block on the main stream",
+                   "elements": total, "blocks": nblocks},
+        "step_hbm_gbps": 30 * total / elapsed / 1e9,
+        "gemm_only_ms": gemm_s * 1e3,
+        "roofline": {"kernel": "k_adam_block_step", "bound": "hbm",
+                     "achieved": 28 * total / elapsed / 1e9, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": 28 * total / elapsed / 1e9 / HBM_PEAK_GBPS,
+                     "traffic": None,
+                     "note": "whole-pass figure (GEMMs and reductions overlapped), not a "
+                             "per-kernel event timing"},
+        "cpu_baseline": None,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); the step is "
+              "elementwise and would shard by contiguous element ranges, but no multi-GPU path "
+              "exists here", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2403_06504_amd as lohan
+    from paper_2403_06504_amd import synthetic_inputs as synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    lohan.load_library()
+    if args.variant is not None:
+        lohan.lohan_set_launch_config(args.variant, args.wgs_per_cu, 0)
+    elif args.wgs_per_cu:
+        v, _, _ = lohan.lohan_get_launch_config()
+        lohan.lohan_set_launch_config(v, args.wgs_per_cu, 0)
+    if args.workload == "stream13b":
+        out = bench_stream(args, torch, lohan, synth)
+    else:
+        out = bench_block(args, torch, lohan, synth)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

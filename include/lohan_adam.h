@@ -1,0 +1,147 @@
+/*
+ * lohan_adam.h -- C ABI of the per-block fused mixed-precision Adam/AdamW step for MI355X (gfx950).
+ *
+ * The operation is the "CPU Compute" step of LoHan's active gradient offloading (arxiv 2403.06504,
+ * Sec. IV-C, "Naive Active Gradient Offloading"): when the gradients of tensor/block i appear
+ * during backward, the model states of that block are updated and a 16-bit parameter copy is
+ * produced.  The tensors are those of Table II: P32 (fp32 parameters, 4 B/param), OS32 (the two
+ * fp32 Adam moments, 8 B/param), G16 (fp16 gradients, 2 B/param) and P16 (16-bit working copy,
+ * 2 B/param, here bfloat16).  The optimizer is Adam (Sec. II, "LLM Training Stages"), run in
+ * mixed precision (Sec. V-A, "Workloads"), synchronously: the P16 copy always equals the rounding
+ * of the P32 written by the same step (Sec. IV-C, footnote on staleness).  Here the step runs on
+ * the GPU out of HBM instead of on the host.
+ *
+ * Conventions common to all entry points
+ *   - Every data pointer is DEVICE memory owned by the caller, valid on `stream`'s device, and
+ *     16-byte aligned.  Buffers of one call must not overlap each other.
+ *   - The library allocates nothing, keeps no per-call state, and never synchronises: kernels are
+ *     enqueued on `stream` and the call returns.  Results (state, flag, squared norm) are valid
+ *     once the work enqueued on `stream` has completed.
+ *   - `workspace` is device scratch of at least lohan_workspace_bytes() bytes, 16-byte aligned,
+ *     private to the call until its kernels complete (calls that may run concurrently on different
+ *     streams need different workspaces).
+ *   - n is the element count of the flat block; any n >= 0 is accepted (n == 0: flag = 0,
+ *     squared norm = 0, nothing else is touched).
+ *   - Errors are reported by return code only.  For codes LOHAN_ERR_NULL .. LOHAN_ERR_WORKSPACE no
+ *     kernel was launched and no memory was modified.  After LOHAN_ERR_HIP (a launch failed)
+ *     buffer contents are unspecified.
+ */
+#ifndef LOHAN_ADAM_H
+#define LOHAN_ADAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include <hip/hip_runtime_api.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOHAN_OK = 0,
+    LOHAN_ERR_NULL = 1,       /* a required pointer is NULL */
+    LOHAN_ERR_ALIGN = 2,      /* a data pointer or the workspace is not 16-byte aligned */
+    LOHAN_ERR_ARG = 3,        /* a scalar argument is out of its domain (see each call) */
+    LOHAN_ERR_WORKSPACE = 4,  /* workspace_bytes < lohan_workspace_bytes() */
+    LOHAN_ERR_HIP = 5         /* the HIP runtime reported an error at launch */
+} lohan_status_t;
+
+enum {
+    /* Adam with L2 regularisation (g += wd * p) instead of decoupled decay (AdamW, the default). */
+    LOHAN_FLAG_L2_MODE = 1u,
+    /* *overflow_flag already holds this block's flag on `stream` (from lohan_grad_overflow_check
+     * or lohan_grad_sqnorm): lohan_adam_block_step then skips its own 2 B/element check pass. */
+    LOHAN_FLAG_PRECHECKED = 2u
+};
+
+/* Device scratch bytes one call needs (a constant of the build; a few tens of KiB). */
+size_t lohan_workspace_bytes(void);
+
+/* Static text for a status code (host memory owned by the library). */
+const char *lohan_status_string(lohan_status_t status);
+
+/*
+ * Overflow flag of one block's fp16 gradients (G16 of Table II): *overflow_flag = 1 if any of the
+ * n stored values is +-inf or NaN (fp16 exponent field all ones, tested on the raw bits before
+ * any unscaling), else 0.  The flag is always written (never left stale).
+ *   grad_fp16      device, in : n IEEE binary16 values, contiguous
+ *   overflow_flag  device, out: one uint32, 4-byte aligned
+ */
+lohan_status_t lohan_grad_overflow_check(const void *grad_fp16, uint64_t n,
+                                         uint32_t *overflow_flag,
+                                         void *workspace, size_t workspace_bytes,
+                                         hipStream_t stream);
+
+/*
+ * Squared l2 norm of one block's unscaled gradients, *sqnorm = sum_i (g16_i / loss_scale)^2,
+ * accumulated in float64 in a fixed order (same input -> same bits), for per-block gradient
+ * clipping; the same single read of G16 also yields the overflow flag when overflow_flag is not
+ * NULL.  When the flag is 1 the value of *sqnorm is unspecified (it may be inf or NaN).
+ *   sqnorm         device, out: one double, 8-byte aligned
+ *   overflow_flag  device, out: one uint32 or NULL
+ *   loss_scale     finite and > 0, else LOHAN_ERR_ARG
+ */
+lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_scale,
+                                 double *sqnorm, uint32_t *overflow_flag,
+                                 void *workspace, size_t workspace_bytes, hipStream_t stream);
+
+/*
+ * One block step (Sec. IV-C "CPU Compute": update the model states of block i and emit its 16-bit
+ * parameter copy; tensors of Table II; Adam per Sec. II with bias correction).
+ *
+ * Unless LOHAN_FLAG_PRECHECKED is given, pass 1 computes *overflow_flag as
+ * lohan_grad_overflow_check does.  Pass 2 reads the flag on the device; if it is non-zero the
+ * step is skipped and param_fp32, exp_avg, exp_avg_sq and param_bf16_out stay bit-identical.
+ * Otherwise, per element, in fp32 with every operation rounded to nearest-even and none fused:
+ *     g   = float(g16) * (1 / loss_scale)              [L2 mode: g = g + wd * p]
+ *     m'  = beta1 * m + (1 - beta1) * g
+ *     v'  = beta2 * v + (1 - beta2) * (g * g)
+ *     den = sqrt(v') / sqrt(1 - beta2^step) + eps
+ *     p'  = p * (1 - lr * wd) - (lr / (1 - beta1^step)) * (m' / den)     [L2 mode: no p factor]
+ *     p16 = bfloat16 round-to-nearest-even of p'
+ * and p', m', v' overwrite p, m, v (1 - beta^step is evaluated in float64 and rounded once).
+ *
+ *   param_fp32, exp_avg, exp_avg_sq   device, in/out: n floats each
+ *   grad_fp16                          device, in    : n binary16 values
+ *   param_bf16_out                     device, out   : n bfloat16 values
+ *   step        1-based index of the step being taken; the caller advances it only when the
+ *               flag came back 0.  step < 1 -> LOHAN_ERR_ARG
+ *   loss_scale  finite and > 0.  Gradient clipping is folded in by the caller passing
+ *               loss_scale / coef (see lohan_clip_loss_scale)
+ *   lr, eps, weight_decay  finite and >= 0; beta1, beta2 in [0, 1); else LOHAN_ERR_ARG
+ *   overflow_flag  device, in/out: one uint32 (written by pass 1, or read-only when prechecked)
+ *   flags       OR of LOHAN_FLAG_*; unknown bits -> LOHAN_ERR_ARG
+ * Moves 28 bytes per element (14 read, 14 written), plus 2 read by pass 1 when it runs.
+ */
+lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *exp_avg_sq,
+                                     const void *grad_fp16, void *param_bf16_out, uint64_t n,
+                                     float lr, float beta1, float beta2, float eps,
+                                     float weight_decay, int64_t step, float loss_scale,
+                                     uint32_t *overflow_flag, uint32_t flags,
+                                     void *workspace, size_t workspace_bytes, hipStream_t stream);
+
+/*
+ * Host-only helper for per-block gradient-norm clipping: returns the loss scale to hand to
+ * lohan_adam_block_step so that unscaling and clipping are one multiply,
+ *     coef = min(1, max_norm / (sqrt(sqnorm) + 1e-6)),   result = (float)(loss_scale / coef),
+ * evaluated in float64.  sqnorm is the host copy of lohan_grad_sqnorm's result.  Returns NaN when
+ * an argument is out of domain (sqnorm negative or not finite, loss_scale or max_norm not > 0).
+ */
+float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm);
+
+/*
+ * Launch-shape override for benchmarking and tuning sweeps (process-wide, not thread-safe against
+ * concurrent calls).  variant selects one of the compiled kernel shapes (0 = default); a value
+ * <= 0 for workgroups_per_cu keeps the built-in choice.  Unknown variants -> LOHAN_ERR_ARG.
+ */
+lohan_status_t lohan_set_launch_config(int adam_variant, int adam_workgroups_per_cu,
+                                       int reduce_workgroups_per_cu);
+void lohan_get_launch_config(int *adam_variant, int *adam_workgroups_per_cu,
+                             int *reduce_workgroups_per_cu);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* LOHAN_ADAM_H */

@@ -1,0 +1,22 @@
+"""MI355X-native per-block fused mixed-precision Adam/AdamW step (LoHan's active gradient
+offloading hot path, arxiv 2403.06504 Sec. IV-C).
+
+The product is the C-ABI library declared in include/lohan_adam.h (HIP kernels for gfx950);
+`binding` is a thin ctypes layer over it with the same entry-point names.  There is no CPU
+fallback: calling an entry point without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    LOHAN_FLAG_L2_MODE,
+    LOHAN_FLAG_PRECHECKED,
+    LohanError,
+    library_path,
+    load_library,
+    lohan_adam_block_step,
+    lohan_clip_loss_scale,
+    lohan_get_launch_config,
+    lohan_grad_overflow_check,
+    lohan_grad_sqnorm,
+    lohan_set_launch_config,
+    lohan_status_string,
+    lohan_workspace_bytes,
+)

@@ -1,0 +1,176 @@
+"""ctypes binding of liblohan_adam.so -- argument marshalling only.
+
+Each function has the name and argument order of the C entry point it calls
+(include/lohan_adam.h).  Device buffers may be given as torch tensors (their data_ptr() is taken;
+dtype, contiguity and length are checked against n) or as raw integer device addresses; `stream`
+may be a torch.cuda.Stream, a raw hipStream_t integer, or None for torch's current stream.
+Nothing is computed here, and nothing falls back to the host: without the built library every
+call raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblohan_adam.so")
+_LIB = None
+
+LOHAN_OK = 0
+LOHAN_FLAG_L2_MODE = 1
+LOHAN_FLAG_PRECHECKED = 2
+
+EXPORTS = (
+    "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
+    "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_clip_loss_scale",
+    "lohan_set_launch_config", "lohan_get_launch_config",
+)
+
+
+class LohanError(RuntimeError):
+    """A C entry point returned a status other than LOHAN_OK."""
+
+    def __init__(self, status: int, message: str):
+        super().__init__(f"lohan status {status}: {message}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the in-tree shared library (built by paper_2403_06504_amd/build.py)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it first (python -m paper_2403_06504_amd.build, or "
+            "__graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, u64, f32, sz = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_float, ctypes.c_size_t
+    lib.lohan_workspace_bytes.argtypes = []
+    lib.lohan_workspace_bytes.restype = sz
+    lib.lohan_status_string.argtypes = [ctypes.c_int]
+    lib.lohan_status_string.restype = ctypes.c_char_p
+    lib.lohan_grad_overflow_check.argtypes = [vp, u64, vp, vp, sz, vp]
+    lib.lohan_grad_overflow_check.restype = ctypes.c_int
+    lib.lohan_grad_sqnorm.argtypes = [vp, u64, f32, vp, vp, vp, sz, vp]
+    lib.lohan_grad_sqnorm.restype = ctypes.c_int
+    lib.lohan_adam_block_step.argtypes = [vp, vp, vp, vp, vp, u64, f32, f32, f32, f32, f32,
+                                          ctypes.c_int64, f32, vp, ctypes.c_uint32, vp, sz, vp]
+    lib.lohan_adam_block_step.restype = ctypes.c_int
+    lib.lohan_clip_loss_scale.argtypes = [ctypes.c_double, f32, f32]
+    lib.lohan_clip_loss_scale.restype = f32
+    lib.lohan_set_launch_config.argtypes = [ctypes.c_int] * 3
+    lib.lohan_set_launch_config.restype = ctypes.c_int
+    lib.lohan_get_launch_config.argtypes = [ctypes.POINTER(ctypes.c_int)] * 3
+    lib.lohan_get_launch_config.restype = None
+    _LIB = lib
+    return lib
+
+
+def _check(status: int):
+    if status != LOHAN_OK:
+        raise LohanError(status, lohan_status_string(status))
+
+
+def _addr(buf, n=None, dtype_name=None, what="buffer"):
+    """Device address of a torch tensor or pass-through of an integer address / None."""
+    if buf is None:
+        return None
+    if isinstance(buf, int):
+        return buf
+    if hasattr(buf, "data_ptr"):
+        if not buf.is_contiguous():
+            raise TypeError(f"{what}: tensor must be contiguous")
+        if dtype_name is not None and str(buf.dtype) not in dtype_name:
+            raise TypeError(f"{what}: expected dtype in {dtype_name}, got {buf.dtype}")
+        if n is not None and buf.numel() < n:
+            raise ValueError(f"{what}: tensor holds {buf.numel()} elements, need {n}")
+        return buf.data_ptr()
+    raise TypeError(f"{what}: expected a torch tensor, an integer device address or None")
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    if hasattr(stream, "cuda_stream"):
+        return stream.cuda_stream
+    raise TypeError("stream: expected torch.cuda.Stream, an integer hipStream_t or None")
+
+
+def _workspace(workspace, workspace_bytes):
+    if workspace is None:
+        return None, 0
+    if isinstance(workspace, int):
+        if workspace_bytes is None:
+            raise ValueError("workspace_bytes is required with a raw workspace address")
+        return workspace, int(workspace_bytes)
+    nbytes = workspace.numel() * workspace.element_size()
+    return _addr(workspace, what="workspace"), nbytes if workspace_bytes is None else int(
+        workspace_bytes)
+
+
+_F16 = ("torch.float16", "torch.int16", "torch.uint16")
+_BF16 = ("torch.bfloat16", "torch.int16", "torch.uint16")
+_F32 = ("torch.float32",)
+_U32 = ("torch.int32", "torch.uint32")
+_F64 = ("torch.float64",)
+
+
+def lohan_workspace_bytes() -> int:
+    return int(load_library().lohan_workspace_bytes())
+
+
+def lohan_status_string(status: int) -> str:
+    return load_library().lohan_status_string(int(status)).decode()
+
+
+def lohan_grad_overflow_check(grad_fp16, n, overflow_flag, workspace, workspace_bytes=None,
+                              stream=None):
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_grad_overflow_check(
+        _addr(grad_fp16, n, _F16, "grad_fp16"), int(n),
+        _addr(overflow_flag, 1, _U32, "overflow_flag"), ws, ws_bytes, _stream(stream)))
+
+
+def lohan_grad_sqnorm(grad_fp16, n, loss_scale, sqnorm, overflow_flag, workspace,
+                      workspace_bytes=None, stream=None):
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_grad_sqnorm(
+        _addr(grad_fp16, n, _F16, "grad_fp16"), int(n), float(loss_scale),
+        _addr(sqnorm, 1, _F64, "sqnorm"), _addr(overflow_flag, 1, _U32, "overflow_flag"),
+        ws, ws_bytes, _stream(stream)))
+
+
+def lohan_adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n,
+                          lr, beta1, beta2, eps, weight_decay, step, loss_scale,
+                          overflow_flag, flags, workspace, workspace_bytes=None, stream=None):
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_adam_block_step(
+        _addr(param_fp32, n, _F32, "param_fp32"), _addr(exp_avg, n, _F32, "exp_avg"),
+        _addr(exp_avg_sq, n, _F32, "exp_avg_sq"), _addr(grad_fp16, n, _F16, "grad_fp16"),
+        _addr(param_bf16_out, n, _BF16, "param_bf16_out"), int(n),
+        float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
+        float(loss_scale), _addr(overflow_flag, 1, _U32, "overflow_flag"), int(flags),
+        ws, ws_bytes, _stream(stream)))
+
+
+def lohan_clip_loss_scale(sqnorm, loss_scale, max_norm) -> float:
+    return float(load_library().lohan_clip_loss_scale(float(sqnorm), float(loss_scale),
+                                                      float(max_norm)))
+
+
+def lohan_set_launch_config(adam_variant=1, adam_workgroups_per_cu=0,
+                            reduce_workgroups_per_cu=0):
+    _check(load_library().lohan_set_launch_config(int(adam_variant), int(adam_workgroups_per_cu),
+                                                  int(reduce_workgroups_per_cu)))
+
+
+def lohan_get_launch_config():
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    load_library().lohan_get_launch_config(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    return a.value, b.value, c.value

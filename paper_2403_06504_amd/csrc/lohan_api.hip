@@ -1,0 +1,205 @@
+// C ABI of the per-block fused Adam step: argument validation, host-side scalar precompute,
+// launch sizing.  See include/lohan_adam.h for the contract of every entry point.
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstdint>
+#include <limits>
+
+#include "lohan_adam.h"
+#include "lohan_kernels.h"
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_cu_count[kMaxDevices];
+
+// Launch shape (overridable through lohan_set_launch_config for tuning sweeps).
+constexpr int kDefaultAdamVariant = 1;        // 2 vectors per lane per trip, plain loads/stores
+constexpr int kDefaultAdamWgsPerCu = 8;
+constexpr int kDefaultReduceWgsPerCu = 8;
+std::atomic<int> g_adam_variant{kDefaultAdamVariant};
+std::atomic<int> g_adam_wgs_per_cu{kDefaultAdamWgsPerCu};
+std::atomic<int> g_reduce_wgs_per_cu{kDefaultReduceWgsPerCu};
+
+// Compute units of the current device (the device `stream` must belong to).  Returns 0 on error.
+int current_cu_count()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (dev >= 0 && dev < kMaxDevices) {
+        int cached = g_cu_count[dev].load(std::memory_order_relaxed);
+        if (cached > 0) return cached;
+    }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus <= 0)
+        return 0;
+    if (dev >= 0 && dev < kMaxDevices) g_cu_count[dev].store(cus, std::memory_order_relaxed);
+    return cus;
+}
+
+inline bool misaligned(const void *ptr, uintptr_t align)
+{
+    return (reinterpret_cast<uintptr_t>(ptr) & (align - 1)) != 0;
+}
+
+inline bool finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
+inline bool finite_pos(float x) { return std::isfinite(x) && x > 0.0f; }
+inline bool unit_interval(float x) { return std::isfinite(x) && x >= 0.0f && x < 1.0f; }
+
+lohan_status_t check_workspace(const void *workspace, size_t workspace_bytes)
+{
+    if (workspace == nullptr) return LOHAN_ERR_NULL;
+    if (misaligned(workspace, 16)) return LOHAN_ERR_ALIGN;
+    if (workspace_bytes < lohan::kWorkspaceBytes) return LOHAN_ERR_WORKSPACE;
+    return LOHAN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lohan_workspace_bytes(void) { return lohan::kWorkspaceBytes; }
+
+const char *lohan_status_string(lohan_status_t status)
+{
+    switch (status) {
+    case LOHAN_OK: return "ok";
+    case LOHAN_ERR_NULL: return "a required pointer is NULL";
+    case LOHAN_ERR_ALIGN: return "a pointer is not sufficiently aligned";
+    case LOHAN_ERR_ARG: return "a scalar argument is out of its domain";
+    case LOHAN_ERR_WORKSPACE: return "workspace is smaller than lohan_workspace_bytes()";
+    case LOHAN_ERR_HIP: return "the HIP runtime reported an error at launch";
+    default: return "unknown status";
+    }
+}
+
+lohan_status_t lohan_grad_overflow_check(const void *grad_fp16, uint64_t n,
+                                         uint32_t *overflow_flag, void *workspace,
+                                         size_t workspace_bytes, hipStream_t stream)
+{
+    if (overflow_flag == nullptr || (grad_fp16 == nullptr && n != 0)) return LOHAN_ERR_NULL;
+    if (misaligned(grad_fp16, 16) || misaligned(overflow_flag, 4)) return LOHAN_ERR_ALIGN;
+    lohan_status_t ws = check_workspace(workspace, workspace_bytes);
+    if (ws != LOHAN_OK) return ws;
+    const int cus = current_cu_count();
+    if (cus <= 0) return LOHAN_ERR_HIP;
+    const uint32_t max_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
+    hipError_t e = lohan::launch_grad_reduce(grad_fp16, n, false, 0.0, nullptr, overflow_flag,
+                                             workspace, max_wgs, stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
+lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_scale,
+                                 double *sqnorm, uint32_t *overflow_flag, void *workspace,
+                                 size_t workspace_bytes, hipStream_t stream)
+{
+    if (sqnorm == nullptr || (grad_fp16 == nullptr && n != 0)) return LOHAN_ERR_NULL;
+    if (misaligned(grad_fp16, 16) || misaligned(sqnorm, 8) || misaligned(overflow_flag, 4))
+        return LOHAN_ERR_ALIGN;
+    if (!finite_pos(loss_scale)) return LOHAN_ERR_ARG;
+    lohan_status_t ws = check_workspace(workspace, workspace_bytes);
+    if (ws != LOHAN_OK) return ws;
+    const int cus = current_cu_count();
+    if (cus <= 0) return LOHAN_ERR_HIP;
+    const uint32_t max_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
+    const double inv = 1.0 / (double)loss_scale;
+    hipError_t e = lohan::launch_grad_reduce(grad_fp16, n, true, inv * inv, sqnorm, overflow_flag,
+                                             workspace, max_wgs, stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
+lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *exp_avg_sq,
+                                     const void *grad_fp16, void *param_bf16_out, uint64_t n,
+                                     float lr, float beta1, float beta2, float eps,
+                                     float weight_decay, int64_t step, float loss_scale,
+                                     uint32_t *overflow_flag, uint32_t flags, void *workspace,
+                                     size_t workspace_bytes, hipStream_t stream)
+{
+    if (overflow_flag == nullptr) return LOHAN_ERR_NULL;
+    if (n != 0 && (param_fp32 == nullptr || exp_avg == nullptr || exp_avg_sq == nullptr ||
+                   grad_fp16 == nullptr || param_bf16_out == nullptr))
+        return LOHAN_ERR_NULL;
+    if (misaligned(param_fp32, 16) || misaligned(exp_avg, 16) || misaligned(exp_avg_sq, 16) ||
+        misaligned(grad_fp16, 16) || misaligned(param_bf16_out, 16) ||
+        misaligned(overflow_flag, 4))
+        return LOHAN_ERR_ALIGN;
+    if ((flags & ~(uint32_t)(LOHAN_FLAG_L2_MODE | LOHAN_FLAG_PRECHECKED)) != 0)
+        return LOHAN_ERR_ARG;
+    if (step < 1 || !finite_pos(loss_scale) || !finite_nonneg(lr) || !finite_nonneg(eps) ||
+        !finite_nonneg(weight_decay) || !unit_interval(beta1) || !unit_interval(beta2))
+        return LOHAN_ERR_ARG;
+    const bool prechecked = (flags & LOHAN_FLAG_PRECHECKED) != 0;
+    if (!prechecked) {
+        lohan_status_t ws = check_workspace(workspace, workspace_bytes);
+        if (ws != LOHAN_OK) return ws;
+    }
+    const int cus = current_cu_count();
+    if (cus <= 0) return LOHAN_ERR_HIP;
+
+    // Element-independent scalars, each an individually rounded fp32 operation; the bias
+    // corrections go through float64 and are rounded once.
+    lohan::StepScalars s;
+    s.inv = 1.0f / loss_scale;
+    s.beta1 = beta1;
+    s.beta2 = beta2;
+    s.omb1 = 1.0f - beta1;
+    s.omb2 = 1.0f - beta2;
+    const float bc1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    const float bc2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    s.sbc2 = std::sqrt(bc2);
+    s.ss = lr / bc1;
+    const float lr_wd = lr * weight_decay;
+    s.decay = 1.0f - lr_wd;
+    s.eps = eps;
+    s.wd = weight_decay;
+
+    if (!prechecked) {
+        const uint32_t red_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
+        hipError_t e = lohan::launch_grad_reduce(grad_fp16, n, false, 0.0, nullptr, overflow_flag,
+                                                 workspace, red_wgs, stream);
+        if (e != hipSuccess) return LOHAN_ERR_HIP;
+    }
+    const uint32_t max_wgs = (uint32_t)cus * (uint32_t)g_adam_wgs_per_cu.load();
+    hipError_t e = lohan::launch_adam_block_step(
+        param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n, s,
+        (flags & LOHAN_FLAG_L2_MODE) != 0, overflow_flag, g_adam_variant.load(), max_wgs, stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
+float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm)
+{
+    if (!(sqnorm >= 0.0) || !std::isfinite(sqnorm) || !finite_pos(loss_scale) ||
+        !finite_pos(max_norm))
+        return std::numeric_limits<float>::quiet_NaN();
+    const double norm = std::sqrt(sqnorm);
+    double coef = (double)max_norm / (norm + 1e-6);
+    if (coef > 1.0) coef = 1.0;
+    return (float)((double)loss_scale / coef);
+}
+
+lohan_status_t lohan_set_launch_config(int adam_variant, int adam_workgroups_per_cu,
+                                       int reduce_workgroups_per_cu)
+{
+    if (!lohan::adam_variant_valid(adam_variant)) return LOHAN_ERR_ARG;
+    if (adam_workgroups_per_cu > 1024 || reduce_workgroups_per_cu > 16) return LOHAN_ERR_ARG;
+    g_adam_variant.store(adam_variant);
+    g_adam_wgs_per_cu.store(adam_workgroups_per_cu > 0 ? adam_workgroups_per_cu
+                                                       : kDefaultAdamWgsPerCu);
+    g_reduce_wgs_per_cu.store(reduce_workgroups_per_cu > 0 ? reduce_workgroups_per_cu
+                                                           : kDefaultReduceWgsPerCu);
+    return LOHAN_OK;
+}
+
+void lohan_get_launch_config(int *adam_variant, int *adam_workgroups_per_cu,
+                             int *reduce_workgroups_per_cu)
+{
+    if (adam_variant) *adam_variant = g_adam_variant.load();
+    if (adam_workgroups_per_cu) *adam_workgroups_per_cu = g_adam_wgs_per_cu.load();
+    if (reduce_workgroups_per_cu) *reduce_workgroups_per_cu = g_reduce_wgs_per_cu.load();
+}
+
+}  // extern "C"

@@ -1,0 +1,42 @@
+// Internal interface between the C ABI layer (lohan_api.hip) and the kernels (lohan_kernels.hip).
+#ifndef LOHAN_KERNELS_H
+#define LOHAN_KERNELS_H
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lohan {
+
+// Per-call fp32 scalars, computed once on the host and passed by value (they live in SGPRs).
+struct StepScalars {
+    float inv;    // fl(1 / loss_scale)
+    float beta1;
+    float omb1;   // fl(1 - beta1)
+    float beta2;
+    float omb2;   // fl(1 - beta2)
+    float sbc2;   // fl(sqrt(bc2)), bc2 = fp32 rounding of the float64 value 1 - beta2^step
+    float eps;
+    float ss;     // fl(lr / bc1),  bc1 = fp32 rounding of the float64 value 1 - beta1^step
+    float decay;  // fl(1 - fl(lr * wd))
+    float wd;
+};
+
+// Workspace layout: kMaxPartials doubles, then kMaxPartials uint32 flags.
+constexpr uint32_t kMaxPartials = 4096;
+constexpr size_t kWorkspaceBytes = (size_t)kMaxPartials * (sizeof(double) + sizeof(uint32_t));
+
+hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm, double inv2,
+                              double *sqnorm, uint32_t *flag, void *workspace, uint32_t max_wgs,
+                              hipStream_t stream);
+
+bool adam_variant_valid(int variant);
+
+hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
+                                  void *p16, uint64_t n, const StepScalars &s, bool l2,
+                                  const uint32_t *flag, int variant, uint32_t max_wgs,
+                                  hipStream_t stream);
+
+}  // namespace lohan
+
+#endif

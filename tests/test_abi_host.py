@@ -1,0 +1,158 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
+its host-side logic (validation order, status strings, clipping helper, launch-config knob)
+behaves as documented.  No kernel is launched: every call here returns from validation, which
+runs before the library touches the HIP runtime."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2403_06504_amd as lohan
+from paper_2403_06504_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lohan_adam.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(lohan.library_path()):
+        from paper_2403_06504_amd import build
+        build.build(force=True)
+    return lohan.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lohan_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_named_entry_points():
+    names = declared_functions()
+    for must in ("lohan_adam_block_step", "lohan_grad_overflow_check", "lohan_grad_sqnorm"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert len(names) >= 8
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in the header but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_workspace_bytes_and_status_strings(lib):
+    ws = lohan.lohan_workspace_bytes()
+    assert 0 < ws <= (1 << 20) and ws % 16 == 0
+    seen = set()
+    for code in range(0, 6):
+        s = lohan.lohan_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert lohan.lohan_status_string(0) == "ok"
+    assert "unknown" in lohan.lohan_status_string(99)
+
+
+GOOD = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, step=1,
+            loss_scale=1024.0)
+A = 0x1000   # a fake, aligned, never dereferenced device address
+
+
+def step_status(lib, *, p=A, m=A * 2, v=A * 3, g=A * 4, h=A * 5, n=16, flag=A * 6, flags=0,
+                ws=A * 7, ws_bytes=None, **hy):
+    args = dict(GOOD, **hy)
+    if ws_bytes is None:
+        ws_bytes = lib.lohan_workspace_bytes()
+    return lib.lohan_adam_block_step(p, m, v, g, h, n, args["lr"], args["beta1"], args["beta2"],
+                                     args["eps"], args["weight_decay"], args["step"],
+                                     args["loss_scale"], flag, flags, ws, ws_bytes, None)
+
+
+def test_step_validation_returns_before_any_launch(lib):
+    assert step_status(lib, flag=None) == 1                       # LOHAN_ERR_NULL
+    for name in ("p", "m", "v", "g", "h"):
+        assert step_status(lib, **{name: None}) == 1
+    for name in ("p", "m", "v", "g", "h"):
+        assert step_status(lib, **{name: A + 4}) == 2             # LOHAN_ERR_ALIGN
+    assert step_status(lib, flag=A + 2) == 2
+    assert step_status(lib, step=0) == 3                          # LOHAN_ERR_ARG
+    assert step_status(lib, step=-5) == 3
+    for bad in (0.0, -1.0, math.inf, math.nan):
+        assert step_status(lib, loss_scale=bad) == 3
+    for name in ("lr", "eps", "weight_decay"):
+        for bad in (-1e-3, math.inf, math.nan):
+            assert step_status(lib, **{name: bad}) == 3
+    for name in ("beta1", "beta2"):
+        for bad in (1.0, 1.5, -0.1, math.nan):
+            assert step_status(lib, **{name: bad}) == 3
+    assert step_status(lib, flags=4) == 3                         # unknown flag bit
+    assert step_status(lib, ws=None) == 1
+    assert step_status(lib, ws=A + 8) == 2
+    assert step_status(lib, ws_bytes=16) == 4                     # LOHAN_ERR_WORKSPACE
+
+
+def test_reduction_validation_returns_before_any_launch(lib):
+    ws_bytes = lib.lohan_workspace_bytes()
+    assert lib.lohan_grad_overflow_check(A, 8, None, A * 2, ws_bytes, None) == 1
+    assert lib.lohan_grad_overflow_check(None, 8, A, A * 2, ws_bytes, None) == 1
+    assert lib.lohan_grad_overflow_check(A + 2, 8, A, A * 2, ws_bytes, None) == 2
+    assert lib.lohan_grad_overflow_check(A, 8, A * 3, None, ws_bytes, None) == 1
+    assert lib.lohan_grad_overflow_check(A, 8, A * 3, A * 2, ws_bytes - 1, None) == 4
+    f = ctypes.c_float
+    assert lib.lohan_grad_sqnorm(A, 8, f(1.0), None, A * 3, A * 2, ws_bytes, None) == 1
+    assert lib.lohan_grad_sqnorm(A, 8, f(1.0), A * 4 + 4, A * 3, A * 2, ws_bytes, None) == 2
+    for bad in (0.0, -2.0, math.inf, math.nan):
+        assert lib.lohan_grad_sqnorm(A, 8, f(bad), A * 4, A * 3, A * 2, ws_bytes, None) == 3
+    assert lib.lohan_grad_sqnorm(A, 8, f(1.0), A * 4, None, A * 2, 8, None) == 4
+
+
+def test_binding_raises_with_status(lib):
+    with pytest.raises(lohan.LohanError) as e:
+        lohan.lohan_adam_block_step(A, A * 2, A * 3, A * 4, A * 5, 16, 1e-4, 0.9, 0.999, 1e-8,
+                                    0.01, 0, 1024.0, A * 6, 0, A * 7,
+                                    lohan.lohan_workspace_bytes(), stream=0)
+    assert e.value.status == 3
+
+
+def test_clip_loss_scale_matches_oracle(lib, oracle):
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        sq = float(10 ** rng.uniform(-8, 6))
+        S = float(np.float32(2.0 ** rng.integers(0, 17)))
+        mx = float(np.float32(10 ** rng.uniform(-2, 1)))
+        got = np.float32(lohan.lohan_clip_loss_scale(sq, S, mx))
+        want = oracle.clip_loss_scale(sq, S, mx)
+        assert got == want, (sq, S, mx)
+    assert lohan.lohan_clip_loss_scale(0.0, 1024.0, 1.0) == 1024.0
+    assert abs(lohan.lohan_clip_loss_scale(5.25, 1024.0, 1.0) - 2346.2798) < 2e-3
+    for bad in ((-1.0, 1.0, 1.0), (math.nan, 1.0, 1.0), (math.inf, 1.0, 1.0), (1.0, 0.0, 1.0),
+                (1.0, 1.0, 0.0), (1.0, 1.0, -1.0)):
+        assert math.isnan(lohan.lohan_clip_loss_scale(*bad))
+
+
+def test_launch_config_knob(lib):
+    before = lohan.lohan_get_launch_config()
+    try:
+        lohan.lohan_set_launch_config(2, 16, 4)
+        assert lohan.lohan_get_launch_config() == (2, 16, 4)
+        lohan.lohan_set_launch_config(0, 0, 0)
+        v, a, r = lohan.lohan_get_launch_config()
+        assert v == 0 and a > 0 and r > 0
+        for bad in (-1, 3, 5 << 2, 1 << 6):
+            with pytest.raises(lohan.LohanError):
+                lohan.lohan_set_launch_config(bad, 0, 0)
+        with pytest.raises(lohan.LohanError):
+            lohan.lohan_set_launch_config(0, 100000, 0)
+    finally:
+        lohan.lohan_set_launch_config(*before)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.lohan_workspace_bytes()

@@ -1,0 +1,397 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+bits.  Every test needs an MI355X and the built in-tree library (no fallback exists)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2403_06504_amd as lohan
+from paper_2403_06504_amd import synthetic_inputs as synth
+
+from gpu_util import (RTOL_SQNORM, DeviceBlock, assert_state_parity, gpu_steps, oracle_steps)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _library_is_native():
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    lohan.load_library()            # raises if the HIP library was not built
+    lohan.lohan_set_launch_config(1, 0, 0)
+    yield
+
+
+def small_workload(n, step=100, S=65536.0, zero=False):
+    return synth.Workload(name=f"n{n}", n=n, step=step, loss_scale=S, zero_moments=zero)
+
+
+SMALL_N = list(range(0, 18)) + [255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096,
+                                4097, 8191, 8193, 65537, 1_000_003]
+
+
+@pytest.mark.parametrize("l2_mode", [False, True])
+def test_ten_chained_steps_small_sizes(oracle, l2_mode):
+    """All tail residues of the 4-wide vectors and of the workgroup tiles, 10 chained steps."""
+    worst_all = {"p": 0, "m": 0, "v": 0, "p16": 0}
+    for n in SMALL_N:
+        wl = small_workload(n)
+        say(f"[small] n={n} l2={l2_mode}")
+        blk = DeviceBlock(synth.make_block(wl, seed=n, device=DEV))
+        host = blk.host()
+        hy = wl.hyper()
+        gflags = gpu_steps(blk, hy, 10, l2_mode=l2_mode)
+        oflags = oracle_steps(oracle, host, hy, 10, l2_mode=l2_mode, nthreads=4)
+        assert gflags == oflags == [0] * 10
+        worst = assert_state_parity(blk.host(), host, what=f"n={n}")
+        for k in worst:
+            worst_all[k] = max(worst_all[k], worst[k])
+    say(f"[small] worst ulp over all sizes: {worst_all}")
+
+
+def all_variants():
+    return [u | (nt << 2) | (b << 5) for b in (0, 1) for nt in range(5) for u in range(3)]
+
+
+def test_every_kernel_variant_matches(oracle):
+    """Every compiled launch shape (unroll x nontemporal set x tile mapping) at a ragged size."""
+    n = 1_000_003
+    wl = small_workload(n)
+    ref_blk = synth.make_block(wl, seed=1, device=DEV)
+    host = DeviceBlock({k: t.clone() for k, t in ref_blk.items()}).host()
+    hy = wl.hyper()
+    oracle_steps(oracle, host, hy, 2, nthreads=16)
+    try:
+        for variant in all_variants():
+            for wgs in (1, 8):
+                say(f"[variant] variant={variant} wgs_per_cu={wgs}")
+                lohan.lohan_set_launch_config(variant, wgs, 0)
+                blk = DeviceBlock({k: t.clone() for k, t in ref_blk.items()})
+                assert gpu_steps(blk, hy, 2) == [0, 0]
+                assert_state_parity(blk.host(), host, what=f"variant={variant}")
+    finally:
+        lohan.lohan_set_launch_config(1, 0, 0)
+
+
+def test_config1_h768_block_ten_steps(oracle):
+    wl = synth.WORKLOADS["gpt_h768"]
+    say(f"[cfg1] n={wl.n}")
+    blk = DeviceBlock(synth.make_block(wl, seed=0, device=DEV))
+    host = blk.host()
+    hy = wl.hyper()
+    assert gpu_steps(blk, hy, 10) == [0] * 10
+    assert oracle_steps(oracle, host, hy, 10) == [0] * 10
+    worst = assert_state_parity(blk.host(), host, what="config 1")
+    say(f"[cfg1] worst ulp {worst}")
+    # first step closed form also holds on the GPU result after step 1 (fresh block)
+    blk1 = DeviceBlock(synth.make_block(wl, seed=0, device=DEV))
+    p0 = blk1.p.clone()
+    gpu_steps(blk1, hy, 1)
+    g = blk1.g.float() / wl.loss_scale
+    dp = (blk1.p.double() - p0.double() * (1.0 - wl.lr * wl.weight_decay))
+    big = g.abs() > 1e-5
+    assert torch.all((dp[big].abs() - wl.lr).abs() <= 2e-3 * wl.lr + 1e-8)
+    assert torch.all(torch.sign(dp[big]) == -torch.sign(g[big].double()))
+
+
+def test_config2_13b_block_full_size(oracle):
+    """The benchmark's workload at full size and in its launch configuration: one step compared
+    over all 314,572,800 elements, then ten chained steps."""
+    wl = synth.WORKLOADS["gpt13b"]
+    say(f"[cfg2] n={wl.n} generating")
+    blk = DeviceBlock(synth.make_block(wl, seed=0, device=DEV))
+    host = blk.host()
+    hy = wl.hyper()
+    say("[cfg2] step 1 gpu")
+    assert gpu_steps(blk, hy, 1) == [0]
+    say("[cfg2] step 1 oracle")
+    assert oracle_steps(oracle, host, hy, 1) == [0]
+    worst = assert_state_parity(blk.host(), host, what="config 2, 1 step")
+    say(f"[cfg2] 1 step worst ulp {worst}")
+    hy2 = dict(hy, step=hy["step"] + 1)
+    assert gpu_steps(blk, hy2, 9) == [0] * 9
+    say("[cfg2] 9 more oracle steps")
+    assert oracle_steps(oracle, host, hy2, 9) == [0] * 9
+    worst = assert_state_parity(blk.host(), host, what="config 2, 10 steps")
+    say(f"[cfg2] 10 steps worst ulp {worst}")
+
+
+def test_config4_175b_block_sampled(oracle):
+    """n = 12*12288^2 (29 GB resident, byte offsets beyond 2^32): the elements are independent, so
+    the oracle is run on sampled ranges -- the head, the end, and seeded unaligned interior
+    ranges -- of the same buffers."""
+    wl = synth.WORKLOADS["gpt175b"]
+    say(f"[cfg4] n={wl.n} generating")
+    blk = DeviceBlock(synth.make_block(wl, seed=0, device=DEV))
+    span = 1 << 21
+    rng = np.random.default_rng(4)
+    starts = [0, wl.n - span] + [int(x) for x in rng.integers(span, wl.n - 2 * span, size=6)]
+    starts += [(1 << 30) - 3, (1 << 30) + (1 << 29) + 1, wl.n // 2 + 1]   # fp32 byte offsets cross 2^32
+    before = {s: blk.host(s, s + span) for s in starts}
+    hy = wl.hyper()
+    say("[cfg4] 3 gpu steps")
+    assert gpu_steps(blk, hy, 3) == [0, 0, 0]
+    for s in starts:
+        host = before[s]
+        assert oracle_steps(oracle, host, hy, 3, nthreads=8) == [0, 0, 0]
+        worst = assert_state_parity(blk.host(s, s + span), host, what=f"config 4 range {s}")
+        say(f"[cfg4] range start {s}: worst ulp {worst}")
+    # sampled check and whole-buffer properties
+    blk.check()
+    torch.cuda.synchronize()
+    assert blk.flag_value() == 0
+    assert bool(torch.all(blk.v >= 0))
+    assert torch.equal(blk.p16.view(torch.int16), blk.p.to(torch.bfloat16).view(torch.int16))
+
+
+def test_config5_ragged_overflow_skip_and_clipping(oracle):
+    """Ragged 13B block (n = 12*5120^2 + 1).  With 0.01 % of the gradients set to inf/NaN the
+    flag is 1 and p, m, v, p16 stay bit-identical; without them a clipping run (max-norm 1.0)
+    goes through lohan_grad_sqnorm and matches the oracle."""
+    wl = synth.WORKLOADS["gpt13b_ragged"]
+    hy = wl.hyper()
+    for seed in (0, 1):
+        say(f"[cfg5] overflow run seed={seed}")
+        blk = DeviceBlock(synth.make_block(wl, seed=seed, device=DEV))
+        pos = synth.plant_nonfinite(blk.g, 1e-4, seed, always=(0, wl.n - 1) if seed == 0 else ())
+        assert pos.numel() > 30000
+        keep = {k: getattr(blk, k).clone() for k in ("p", "m", "v", "p16")}
+        assert gpu_steps(blk, hy, 1) == [1]
+        for k, t in keep.items():
+            a, b = getattr(blk, k), t
+            if a.dtype == torch.bfloat16:
+                a, b = a.view(torch.int16), b.view(torch.int16)
+            else:
+                a, b = a.view(torch.int32), b.view(torch.int32)
+            assert torch.equal(a, b), f"{k} changed on a skipped step"
+        assert oracle.grad_overflow_check(synth.to_numpy_bits(blk.g)) == 1
+        blk.norm(wl.loss_scale)
+        torch.cuda.synchronize()
+        assert blk.flag_value() == 1
+        del blk, keep
+    # a single non-finite value in the ragged last element is enough
+    say("[cfg5] single nan at n-1")
+    blk = DeviceBlock(synth.make_block(wl, seed=2, device=DEV))
+    blk.g.view(torch.int16)[wl.n - 1] = 0x7E00
+    p_before = blk.p.clone()
+    assert gpu_steps(blk, hy, 1) == [1]
+    assert torch.equal(blk.p.view(torch.int32), p_before.view(torch.int32))
+    blk.g.view(torch.int16)[wl.n - 1] = 0x7BFF                # largest finite value: no overflow
+    del p_before
+
+    say("[cfg5] clipping run")
+    host = blk.host()
+    blk.norm(wl.loss_scale)
+    torch.cuda.synchronize()
+    assert blk.flag_value() == 0
+    sq_gpu = float(blk.sqnorm.cpu().item())
+    sq_orc = oracle.grad_sqnorm(host["g"], wl.loss_scale)
+    assert abs(sq_gpu - sq_orc) <= RTOL_SQNORM * sq_orc
+    assert 0.9 * wl.n * 1e-6 < sq_gpu < 1.1 * wl.n * 1e-6     # ||g||^2 ~ n * std^2, norm ~ 17.7
+    s_eff_gpu = lohan.lohan_clip_loss_scale(sq_gpu, wl.loss_scale, 1.0)
+    s_eff_orc = float(oracle.clip_loss_scale(sq_orc, wl.loss_scale, 1.0))
+    assert abs(s_eff_gpu - s_eff_orc) <= 1e-5 * s_eff_orc
+    # the step itself is compared with both sides using the oracle's effective scale, so that a
+    # last-digit difference of the two norms does not leak into a bit-level comparison
+    hy_clip = dict(hy, loss_scale=s_eff_orc)
+    blk.step(hy_clip, flags=lohan.LOHAN_FLAG_PRECHECKED)
+    torch.cuda.synchronize()
+    assert oracle_steps(oracle, host, hy_clip, 1) == [0]
+    worst = assert_state_parity(blk.host(), host, what="config 5 clipping run")
+    say(f"[cfg5] clipping run worst ulp {worst}, sqnorm rel err {abs(sq_gpu - sq_orc) / sq_orc:.2e}")
+
+
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 4099, 1_000_003])
+def test_overflow_patterns_and_positions(oracle, n):
+    wl = small_workload(n)
+    hy = wl.hyper()
+    base = synth.make_block(wl, seed=3, device=DEV)
+    positions = sorted({0, n - 1, n // 2, max(0, n - 2), (n // 8) * 8 % n})
+    for pat in synth.NONFINITE_FP16 + (0x7BFF, 0xFBFF):
+        for pos in positions:
+            blk = DeviceBlock({k: t.clone() for k, t in base.items()})
+            blk.g.view(torch.int16)[pos] = pat if pat < 0x8000 else pat - 0x10000
+            host = blk.host()
+            want = oracle.grad_overflow_check(host["g"])
+            assert want == (0 if pat in (0x7BFF, 0xFBFF) else 1)
+            blk.check()
+            torch.cuda.synchronize()
+            assert blk.flag_value() == want
+            blk.flag.fill_(5)
+            blk.norm(wl.loss_scale)
+            torch.cuda.synchronize()
+            assert blk.flag_value() == want
+            blk.flag.fill_(5)
+            assert gpu_steps(blk, hy, 1) == [want]
+            oracle_steps(oracle, host, hy, 1, nthreads=1)
+            after = blk.host()
+            for k in ("p", "m", "v", "p16"):
+                assert np.array_equal(after[k].view(np.uint8), host[k].view(np.uint8)), (k, pat, pos)
+
+
+def test_prechecked_flag_is_honoured(oracle):
+    n = 70_001
+    wl = small_workload(n)
+    hy = wl.hyper()
+    blk = DeviceBlock(synth.make_block(wl, seed=5, device=DEV))
+    host = blk.host()
+    before = blk.host()
+    blk.flag.fill_(1)                     # caller says: overflow
+    blk.step(hy, flags=lohan.LOHAN_FLAG_PRECHECKED)
+    torch.cuda.synchronize()
+    after = blk.host()
+    for k in ("p", "m", "v", "p16"):
+        assert np.array_equal(after[k], before[k])
+    assert blk.flag_value() == 1          # read-only in this mode
+    blk.flag.fill_(0)
+    blk.step(hy, flags=lohan.LOHAN_FLAG_PRECHECKED, stream=None)
+    torch.cuda.synchronize()
+    oracle_steps(oracle, host, hy, 1)
+    assert_state_parity(blk.host(), host, what="prechecked")
+    # prechecked calls need no workspace at all
+    lohan.lohan_adam_block_step(blk.p, blk.m, blk.v, blk.g, blk.p16, n, hy["lr"], hy["beta1"],
+                                hy["beta2"], hy["eps"], hy["weight_decay"], hy["step"] + 1,
+                                hy["loss_scale"], blk.flag, lohan.LOHAN_FLAG_PRECHECKED, None)
+    torch.cuda.synchronize()
+    oracle_steps(oracle, host, dict(hy, step=hy["step"] + 1), 1)
+    assert_state_parity(blk.host(), host, what="prechecked, no workspace")
+
+
+@pytest.mark.parametrize("S", [65536.0, 1024.0, 3000.0, 1.0])
+def test_sqnorm_parity_and_determinism(oracle, S):
+    for n in (0, 1, 5, 8, 2047, 8192, 8193, 65537, 3_000_001, 40_000_003):
+        wl = small_workload(n, S=S)
+        blk = DeviceBlock(synth.make_block(wl, seed=n % 97, device=DEV))
+        blk.norm(S)
+        torch.cuda.synchronize()
+        got = float(blk.sqnorm.cpu().item())
+        want = oracle.grad_sqnorm(synth.to_numpy_bits(blk.g), S)
+        assert abs(got - want) <= RTOL_SQNORM * want, (n, got, want)
+        assert blk.flag_value() == 0
+        blk.sqnorm.fill_(-1.0)
+        blk.norm(S, want_flag=False)
+        torch.cuda.synchronize()
+        assert float(blk.sqnorm.cpu().item()) == got          # fixed-order reduction
+    # all-subnormal gradients are not flushed: n * (2^-24)^2 / S^2
+    n = 10_000
+    blk = DeviceBlock(synth.make_block(small_workload(n, S=S), seed=0, device=DEV))
+    blk.g.view(torch.int16).fill_(1)
+    blk.norm(S)
+    torch.cuda.synchronize()
+    want = oracle.grad_sqnorm(synth.to_numpy_bits(blk.g), S)
+    assert want > 0 and abs(float(blk.sqnorm.cpu().item()) - want) <= RTOL_SQNORM * want
+
+
+def test_denormals_and_extremes_bit_exact(oracle):
+    """Hand-placed extreme values: subnormal gradients, moments and parameters, the largest fp16
+    value, signed zeros -- the regions where flush-to-zero or an approximate divide would show."""
+    n = 4096 + 3
+    wl = small_workload(n)
+    t = synth.make_block(wl, seed=9, device=DEV)
+    edge32 = torch.tensor([0.0, -0.0, 1e-38, -1e-38, 1.4e-45, 3e-39, 1e-30, 1e-20, 1.0, -1.0,
+                           123.456, -7.5e3, 2.0 ** -126, 2.0 ** -127, 1e10, 3e-41],
+                          dtype=torch.float32, device=DEV)
+    edge16 = torch.tensor([0x0000, 0x0001, -0x7FFF, 0x03FF, 0x0400, 0x7BFF, -0x0401, 0x3C00,
+                           -0x4400, 0x3555, 0x0200, 0x6400, -0x8000, 0x0002, 0x7BFE, 0x1234],
+                          dtype=torch.int16, device=DEV)
+    k = edge32.numel()
+    for rep in range(0, n - 4 * k, 4 * k):
+        t["p"][rep:rep + k] = edge32
+        t["m"][rep + k:rep + 2 * k] = edge32 * 1e-3
+        t["v"][rep + 2 * k:rep + 3 * k] = edge32.abs()
+        t["g"].view(torch.int16)[rep + (rep // 7) % k:rep + (rep // 7) % k + k] = edge16
+    for l2_mode in (False, True):
+        blk = DeviceBlock({kk: x.clone() for kk, x in t.items()})
+        host = blk.host()
+        hy = wl.hyper()
+        assert gpu_steps(blk, hy, 10, l2_mode=l2_mode) == [0] * 10
+        oracle_steps(oracle, host, hy, 10, l2_mode=l2_mode, nthreads=1)
+        got = blk.host()
+        for kk in ("p", "m", "v", "p16"):
+            assert np.array_equal(got[kk].view(np.uint8), host[kk].view(np.uint8)), (kk, l2_mode)
+
+
+def test_other_hyperparameters(oracle):
+    n = 300_007
+    cases = [
+        dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, step=1, loss_scale=1024.0),
+        dict(lr=3e-3, beta1=0.8, beta2=0.95, eps=1e-6, weight_decay=0.1, step=7, loss_scale=3000.0),
+        dict(lr=1e-4, beta1=0.0, beta2=0.5, eps=1e-3, weight_decay=0.01, step=3, loss_scale=1.0),
+        dict(lr=0.0, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.5, step=12345678,
+             loss_scale=2346.2798),
+    ]
+    for i, hy in enumerate(cases):
+        hy = {k: (float(np.float32(v)) if k != "step" else v) for k, v in hy.items()}
+        for l2_mode in (False, True):
+            wl = small_workload(n, S=hy["loss_scale"])
+            blk = DeviceBlock(synth.make_block(wl, seed=i, device=DEV))
+            host = blk.host()
+            assert gpu_steps(blk, hy, 3, l2_mode=l2_mode) == [0, 0, 0]
+            oracle_steps(oracle, host, hy, 3, l2_mode=l2_mode)
+            assert_state_parity(blk.host(), host, what=f"hyper case {i} l2={l2_mode}")
+
+
+def test_empty_block_defines_outputs():
+    blk = DeviceBlock(synth.make_block(small_workload(0), seed=0, device=DEV))
+    blk.check()
+    torch.cuda.synchronize()
+    assert blk.flag_value() == 0
+    blk.flag.fill_(9)
+    blk.norm(1024.0)
+    torch.cuda.synchronize()
+    assert blk.flag_value() == 0 and float(blk.sqnorm.cpu().item()) == 0.0
+    blk.flag.fill_(9)
+    blk.step(small_workload(0).hyper())
+    torch.cuda.synchronize()
+    assert blk.flag_value() == 0
+
+
+def test_blocks_on_two_side_streams_behind_gemms(oracle):
+    """The streaming pattern of active gradient offloading: blocks arrive with decreasing index
+    while backward GEMMs run on the main stream; each block step is issued on one of two side
+    streams behind the event of its GEMM.  Every block must match the oracle."""
+    nblocks, n = 12, 2_000_003
+    wl = small_workload(n)
+    hy = wl.hyper()
+    blocks = [DeviceBlock(synth.make_block(wl, seed=100 + i, device=DEV)) for i in range(nblocks)]
+    hosts = [b.host() for b in blocks]
+    side = [torch.cuda.Stream(), torch.cuda.Stream()]
+    a = torch.randn(1024, 2048, device=DEV, dtype=torch.bfloat16)
+    b = torch.randn(2048, 4096, device=DEV, dtype=torch.bfloat16)
+    main = torch.cuda.current_stream()
+    for i in reversed(range(nblocks)):
+        torch.matmul(a, b)
+        ev = torch.cuda.Event()
+        ev.record(main)
+        s = side[i % 2]
+        s.wait_event(ev)
+        blocks[i].step(hy, stream=s)
+    for s in side:
+        s.synchronize()
+    torch.cuda.synchronize()
+    for i in range(nblocks):
+        assert blocks[i].flag_value() == 0
+        oracle_steps(oracle, hosts[i], hy, 1)
+        assert_state_parity(blocks[i].host(), hosts[i], what=f"block {i}")
+
+
+def test_same_input_same_bits():
+    n = 5_000_011
+    wl = small_workload(n)
+    outs = []
+    for _ in range(2):
+        blk = DeviceBlock(synth.make_block(wl, seed=42, device=DEV))
+        gpu_steps(blk, wl.hyper(), 2)
+        blk.norm(wl.loss_scale)
+        torch.cuda.synchronize()
+        outs.append((blk.host(), float(blk.sqnorm.cpu().item())))
+    for k in ("p", "m", "v", "p16"):
+        assert np.array_equal(outs[0][0][k], outs[1][0][k])
+    assert outs[0][1] == outs[1][1]
