@@ -131,14 +131,23 @@ lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *e
 float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm);
 
 /*
- * Launch-shape override for benchmarking and tuning sweeps (process-wide, not thread-safe against
- * concurrent calls).  variant selects one of the compiled kernel shapes (0 = default); a value
- * <= 0 for workgroups_per_cu keeps the built-in choice.  Unknown variants -> LOHAN_ERR_ARG.
+ * Launch-shape override for benchmarking and tuning sweeps (process-wide; do not change it while
+ * calls are in flight on other threads).
+ *   adam_variant            bits [1:0] workgroup size (64, 128, 256, 512 lanes), bits [3:2]
+ *                           vectors per lane per tile (1, 2, 4), bits [5:4] cache policy (0 default,
+ *                           1 nontemporal, 2 nontemporal loads + write-through streaming stores);
+ *                           negative = built-in default; other values -> LOHAN_ERR_ARG
+ *   adam_workgroups_per_cu  0 = one tile per workgroup (grid = number of tiles); > 0 caps the
+ *                           grid at that many workgroups per compute unit; negative = default
+ *   adam_waves_per_cu       occupancy throttle: at most this many wavefronts of the Adam kernel
+ *                           resident per compute unit (0 or 32 = no throttle); negative = default
+ *   reduce_workgroups_per_cu  grid of the gradient reduction per compute unit (<= 16);
+ *                           <= 0 = default
  */
 lohan_status_t lohan_set_launch_config(int adam_variant, int adam_workgroups_per_cu,
-                                       int reduce_workgroups_per_cu);
+                                       int adam_waves_per_cu, int reduce_workgroups_per_cu);
 void lohan_get_launch_config(int *adam_variant, int *adam_workgroups_per_cu,
-                             int *reduce_workgroups_per_cu);
+                             int *adam_waves_per_cu, int *reduce_workgroups_per_cu);
 
 #ifdef __cplusplus
 }

@@ -61,9 +61,9 @@ def load_library():
     lib.lohan_adam_block_step.restype = ctypes.c_int
     lib.lohan_clip_loss_scale.argtypes = [ctypes.c_double, f32, f32]
     lib.lohan_clip_loss_scale.restype = f32
-    lib.lohan_set_launch_config.argtypes = [ctypes.c_int] * 3
+    lib.lohan_set_launch_config.argtypes = [ctypes.c_int] * 4
     lib.lohan_set_launch_config.restype = ctypes.c_int
-    lib.lohan_get_launch_config.argtypes = [ctypes.POINTER(ctypes.c_int)] * 3
+    lib.lohan_get_launch_config.argtypes = [ctypes.POINTER(ctypes.c_int)] * 4
     lib.lohan_get_launch_config.restype = None
     _LIB = lib
     return lib
@@ -164,13 +164,16 @@ def lohan_clip_loss_scale(sqnorm, loss_scale, max_norm) -> float:
                                                       float(max_norm)))
 
 
-def lohan_set_launch_config(adam_variant=1, adam_workgroups_per_cu=0,
+def lohan_set_launch_config(adam_variant=-1, adam_workgroups_per_cu=-1, adam_waves_per_cu=-1,
                             reduce_workgroups_per_cu=0):
+    """Negative (or, for the last, non-positive) arguments select the built-in defaults."""
     _check(load_library().lohan_set_launch_config(int(adam_variant), int(adam_workgroups_per_cu),
+                                                  int(adam_waves_per_cu),
                                                   int(reduce_workgroups_per_cu)))
 
 
 def lohan_get_launch_config():
-    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    load_library().lohan_get_launch_config(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
-    return a.value, b.value, c.value
+    a, b, c, d = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    load_library().lohan_get_launch_config(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                           ctypes.byref(d))
+    return a.value, b.value, c.value, d.value

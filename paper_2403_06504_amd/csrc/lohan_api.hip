@@ -17,11 +17,13 @@ constexpr int kMaxDevices = 64;
 std::atomic<int> g_cu_count[kMaxDevices];
 
 // Launch shape (overridable through lohan_set_launch_config for tuning sweeps).
-constexpr int kDefaultAdamVariant = 1;        // 2 vectors per lane per trip, plain loads/stores
-constexpr int kDefaultAdamWgsPerCu = 8;
-constexpr int kDefaultReduceWgsPerCu = 8;
+constexpr int kDefaultAdamVariant = 0 | (0 << 2) | (2 << 4);  // 64 lanes, 1 vector, streaming
+constexpr int kDefaultAdamWgsPerCu = 0;                       // one tile per workgroup
+constexpr int kDefaultAdamWavesPerCu = 10;                    // occupancy throttle
+constexpr int kDefaultReduceWgsPerCu = 2;
 std::atomic<int> g_adam_variant{kDefaultAdamVariant};
 std::atomic<int> g_adam_wgs_per_cu{kDefaultAdamWgsPerCu};
+std::atomic<int> g_adam_waves_per_cu{kDefaultAdamWavesPerCu};
 std::atomic<int> g_reduce_wgs_per_cu{kDefaultReduceWgsPerCu};
 
 // Compute units of the current device (the device `stream` must belong to).  Returns 0 on error.
@@ -163,10 +165,11 @@ lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *e
                                                  workspace, red_wgs, stream);
         if (e != hipSuccess) return LOHAN_ERR_HIP;
     }
-    const uint32_t max_wgs = (uint32_t)cus * (uint32_t)g_adam_wgs_per_cu.load();
+    const lohan::AdamLaunch cfg{g_adam_variant.load(), g_adam_wgs_per_cu.load(),
+                                g_adam_waves_per_cu.load()};
     hipError_t e = lohan::launch_adam_block_step(
         param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n, s,
-        (flags & LOHAN_FLAG_L2_MODE) != 0, overflow_flag, g_adam_variant.load(), max_wgs, stream);
+        (flags & LOHAN_FLAG_L2_MODE) != 0, overflow_flag, cfg, cus, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -182,23 +185,27 @@ float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm)
 }
 
 lohan_status_t lohan_set_launch_config(int adam_variant, int adam_workgroups_per_cu,
-                                       int reduce_workgroups_per_cu)
+                                       int adam_waves_per_cu, int reduce_workgroups_per_cu)
 {
+    if (adam_variant < 0) adam_variant = kDefaultAdamVariant;
     if (!lohan::adam_variant_valid(adam_variant)) return LOHAN_ERR_ARG;
-    if (adam_workgroups_per_cu > 1024 || reduce_workgroups_per_cu > 16) return LOHAN_ERR_ARG;
+    if (adam_workgroups_per_cu > 4096 || adam_waves_per_cu > 32 || reduce_workgroups_per_cu > 16)
+        return LOHAN_ERR_ARG;
     g_adam_variant.store(adam_variant);
-    g_adam_wgs_per_cu.store(adam_workgroups_per_cu > 0 ? adam_workgroups_per_cu
-                                                       : kDefaultAdamWgsPerCu);
-    g_reduce_wgs_per_cu.store(reduce_workgroups_per_cu > 0 ? reduce_workgroups_per_cu
-                                                           : kDefaultReduceWgsPerCu);
+    g_adam_wgs_per_cu.store(adam_workgroups_per_cu < 0 ? kDefaultAdamWgsPerCu
+                                                       : adam_workgroups_per_cu);
+    g_adam_waves_per_cu.store(adam_waves_per_cu < 0 ? kDefaultAdamWavesPerCu : adam_waves_per_cu);
+    g_reduce_wgs_per_cu.store(reduce_workgroups_per_cu <= 0 ? kDefaultReduceWgsPerCu
+                                                            : reduce_workgroups_per_cu);
     return LOHAN_OK;
 }
 
 void lohan_get_launch_config(int *adam_variant, int *adam_workgroups_per_cu,
-                             int *reduce_workgroups_per_cu)
+                             int *adam_waves_per_cu, int *reduce_workgroups_per_cu)
 {
     if (adam_variant) *adam_variant = g_adam_variant.load();
     if (adam_workgroups_per_cu) *adam_workgroups_per_cu = g_adam_wgs_per_cu.load();
+    if (adam_waves_per_cu) *adam_waves_per_cu = g_adam_waves_per_cu.load();
     if (reduce_workgroups_per_cu) *reduce_workgroups_per_cu = g_reduce_wgs_per_cu.load();
 }
 

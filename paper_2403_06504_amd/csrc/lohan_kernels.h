@@ -30,11 +30,21 @@ hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm,
                               double *sqnorm, uint32_t *flag, void *workspace, uint32_t max_wgs,
                               hipStream_t stream);
 
+// LDS per compute unit on gfx950; used only to size the occupancy throttle.
+constexpr size_t kLdsBytesPerCu = 160 * 1024;
+
+// Launch shape of the Adam kernel.
+struct AdamLaunch {
+    int variant;         // see adam_variant_valid
+    int max_wgs_per_cu;  // <= 0: one tile per workgroup (grid = number of tiles)
+    int waves_per_cu;    // <= 0 or >= 32: no occupancy throttle
+};
+
 bool adam_variant_valid(int variant);
 
 hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
                                   void *p16, uint64_t n, const StepScalars &s, bool l2,
-                                  const uint32_t *flag, int variant, uint32_t max_wgs,
+                                  const uint32_t *flag, const AdamLaunch &cfg, int cus,
                                   hipStream_t stream);
 
 }  // namespace lohan

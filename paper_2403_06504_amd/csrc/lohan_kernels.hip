@@ -206,17 +206,20 @@ __global__ void k_grad_empty(double *sqnorm, uint32_t *flag)
 // The 28 B/element stream.
 // ------------------------------------------------------------------------------------------------
 
-__device__ __forceinline__ uint32_t bf16_rne_bits(float x)
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// fp32 -> bfloat16, round to nearest even; gfx950 converts a pair in one instruction
+// (v_cvt_pk_bf16_f32).  lo goes to bits [15:0], hi to bits [31:16].  A NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi)
 {
-    uint32_t b = __builtin_bit_cast(uint32_t, x);
-    uint32_t r = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
-    if ((b & 0x7FFFFFFFu) > 0x7F800000u) r = (b >> 16) | 0x0040u;   // NaN stays a quiet NaN
-    return r;
+    f32x2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
 template <bool L2>
 __device__ __forceinline__ void adam_elem(float &p, float &m, float &v, float g_scaled,
-                                          const StepScalars &s, uint32_t &p16)
+                                          const StepScalars &s)
 {
     float g = g_scaled * s.inv;
     if constexpr (L2) {
@@ -240,83 +243,102 @@ __device__ __forceinline__ void adam_elem(float &p, float &m, float &v, float g_
     p = p_new;
     m = m_new;
     v = v_new;
-    p16 = bf16_rne_bits(p_new);
 }
 
 template <bool L2>
 __device__ __forceinline__ void adam_vec4(f32x4 &p, f32x4 &m, f32x4 &v, f16x4 g,
                                           const StepScalars &s, u32x2 &out16)
 {
-    uint32_t h[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float pe = p[k], me = m[k], ve = v[k];
-        adam_elem<L2>(pe, me, ve, (float)g[k], s, h[k]);
+        adam_elem<L2>(pe, me, ve, (float)g[k], s);
         p[k] = pe;
         m[k] = me;
         v[k] = ve;
     }
-    out16.x = h[0] | (h[1] << 16);
-    out16.y = h[2] | (h[3] << 16);
+    out16.x = bf16_pack_rne(p[0], p[1]);
+    out16.y = bf16_pack_rne(p[2], p[3]);
 }
 
-// NT is a bit set: 1 = nontemporal G16 loads, 2 = nontemporal P32/OS32 loads,
-// 4 = nontemporal P32/OS32 stores, 8 = nontemporal P16 stores.
-template <int UNROLL, int NT, bool L2>
-__global__ __launch_bounds__(kThreads) void k_adam_block_step(float *__restrict__ p,
-                                                              float *__restrict__ m,
-                                                              float *__restrict__ v,
-                                                              const uint16_t *__restrict__ g,
-                                                              uint16_t *__restrict__ p16,
-                                                              uint64_t n, StepScalars s,
-                                                              const uint32_t *__restrict__ flag,
-                                                              uint32_t tiles_per_wg)
+// Streaming stores with the write-through-to-memory cache policy (sc0 sc1 nt).  The compiler has
+// no builtin for this policy on 128-bit vectors, hence the two one-instruction asm wrappers; they
+// are ordinary vector stores.  They are issued after all arithmetic of a tile, so that no later
+// load of the same wavefront has to wait behind them.  The trailing s_nop covers the two wait
+// states gfx940-class hardware needs between a store of more than 64 bits and a VALU write to
+// the registers that held its data (the compiler cannot see into the asm to insert them).
+__device__ __forceinline__ void st_through(f32x4 *ptr, f32x4 val)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(ptr), "v"(val)
+                 : "memory");
+}
+__device__ __forceinline__ void st_through(u32x2 *ptr, u32x2 val)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(ptr), "v"(val)
+                 : "memory");
+}
+
+// POLICY: 0 = default cache policy, 1 = nontemporal loads and stores, 2 = nontemporal loads and
+// write-through streaming stores.  Nothing is re-read, so nothing should linger in L2 or in the
+// memory-side cache.
+template <int POLICY, typename T>
+__device__ __forceinline__ T ld_stream(const T *ptr)
+{
+    return ld<(POLICY != 0)>(ptr);
+}
+template <int POLICY, typename T>
+__device__ __forceinline__ void st_stream(T *ptr, T val)
+{
+    if constexpr (POLICY == 2) st_through(ptr, val);
+    else st<(POLICY == 1)>(ptr, val);
+}
+
+// One workgroup handles tiles of WG * 4 * UNROLL elements; within a tile every global access of a
+// wavefront is one contiguous run (lane l touches elements 4l..4l+3 of its wavefront's row).
+// The grid is normally one tile per workgroup, so that the set of tiles in flight is a compact
+// window sliding through the buffers in address order (measured: this keeps HBM far busier than
+// a persistent grid-stride loop whose workgroups drift apart); the loop only runs more than once
+// when the host caps the grid.
+template <int WG, int UNROLL, int POLICY, bool L2>
+__global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
+                                                        float *__restrict__ m,
+                                                        float *__restrict__ v,
+                                                        const uint16_t *__restrict__ g,
+                                                        uint16_t *__restrict__ p16, uint64_t n,
+                                                        StepScalars s,
+                                                        const uint32_t *__restrict__ flag)
 {
     // Skip rule: a set overflow flag means nothing at all is written by this kernel.
     if (*flag != 0u) return;
 
-    constexpr bool kNtG = (NT & 1) != 0, kNtLd = (NT & 2) != 0, kNtSt = (NT & 4) != 0,
-                   kNtH = (NT & 8) != 0;
     constexpr uint64_t kVec = 4;                                  // elements per lane per access
-    constexpr uint64_t kRow = (uint64_t)kThreads * kVec;          // elements per wg-wide access
+    constexpr uint64_t kRow = (uint64_t)WG * kVec;                // elements per wg-wide access
     constexpr uint64_t kTile = kRow * UNROLL;
     const uint32_t tid = threadIdx.x;
     const uint64_t ntiles = n / kTile;
 
-    // tiles_per_wg == 0: tiles are dealt round-robin to workgroups (neighbouring workgroups
-    // stream neighbouring tiles).  Otherwise each workgroup owns a contiguous run of tiles.
-    uint64_t tile, tile_end, tile_step;
-    if (tiles_per_wg == 0u) {
-        tile = blockIdx.x;
-        tile_end = ntiles;
-        tile_step = gridDim.x;
-    } else {
-        tile = (uint64_t)blockIdx.x * tiles_per_wg;
-        tile_end = tile + tiles_per_wg < ntiles ? tile + tiles_per_wg : ntiles;
-        tile_step = 1;
-    }
-
-    for (; tile < tile_end; tile += tile_step) {
+    for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const uint64_t base = tile * kTile + (uint64_t)tid * kVec;
         f16x4 gv[UNROLL];
         f32x4 pv[UNROLL], mv[UNROLL], vv[UNROLL];
+        u32x2 hv[UNROLL];
 #pragma unroll
         for (int j = 0; j < UNROLL; ++j) {
             const uint64_t off = base + j * kRow;
-            gv[j] = ld<kNtG>(reinterpret_cast<const f16x4 *>(g + off));
-            pv[j] = ld<kNtLd>(reinterpret_cast<const f32x4 *>(p + off));
-            mv[j] = ld<kNtLd>(reinterpret_cast<const f32x4 *>(m + off));
-            vv[j] = ld<kNtLd>(reinterpret_cast<const f32x4 *>(v + off));
+            gv[j] = ld_stream<POLICY>(reinterpret_cast<const f16x4 *>(g + off));
+            pv[j] = ld_stream<POLICY>(reinterpret_cast<const f32x4 *>(p + off));
+            mv[j] = ld_stream<POLICY>(reinterpret_cast<const f32x4 *>(m + off));
+            vv[j] = ld_stream<POLICY>(reinterpret_cast<const f32x4 *>(v + off));
         }
 #pragma unroll
+        for (int j = 0; j < UNROLL; ++j) adam_vec4<L2>(pv[j], mv[j], vv[j], gv[j], s, hv[j]);
+#pragma unroll
         for (int j = 0; j < UNROLL; ++j) {
             const uint64_t off = base + j * kRow;
-            u32x2 h;
-            adam_vec4<L2>(pv[j], mv[j], vv[j], gv[j], s, h);
-            st<kNtSt>(reinterpret_cast<f32x4 *>(p + off), pv[j]);
-            st<kNtSt>(reinterpret_cast<f32x4 *>(m + off), mv[j]);
-            st<kNtSt>(reinterpret_cast<f32x4 *>(v + off), vv[j]);
-            st<kNtH>(reinterpret_cast<u32x2 *>(p16 + off), h);
+            st_stream<POLICY>(reinterpret_cast<f32x4 *>(p + off), pv[j]);
+            st_stream<POLICY>(reinterpret_cast<f32x4 *>(m + off), mv[j]);
+            st_stream<POLICY>(reinterpret_cast<f32x4 *>(v + off), vv[j]);
+            st_stream<POLICY>(reinterpret_cast<u32x2 *>(p16 + off), hv[j]);
         }
     }
 
@@ -324,8 +346,8 @@ __global__ __launch_bounds__(kThreads) void k_adam_block_step(float *__restrict_
     // up to 3 single elements in workgroup 0.
     const uint64_t rem_start = ntiles * kTile;
     const uint64_t rem_vecs = (n - rem_start) / kVec;
-    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + tid; i < rem_vecs;
-         i += (uint64_t)gridDim.x * kThreads) {
+    for (uint64_t i = (uint64_t)blockIdx.x * WG + tid; i < rem_vecs;
+         i += (uint64_t)gridDim.x * WG) {
         const uint64_t off = rem_start + i * kVec;
         f16x4 gq = *reinterpret_cast<const f16x4 *>(g + off);
         f32x4 pq = *reinterpret_cast<const f32x4 *>(p + off);
@@ -342,12 +364,11 @@ __global__ __launch_bounds__(kThreads) void k_adam_block_step(float *__restrict_
     if (blockIdx.x == 0 && tail < n) {
         _Float16 gh = __builtin_bit_cast(_Float16, g[tail]);
         float pe = p[tail], me = m[tail], ve = v[tail];
-        uint32_t h;
-        adam_elem<L2>(pe, me, ve, (float)gh, s, h);
+        adam_elem<L2>(pe, me, ve, (float)gh, s);
         p[tail] = pe;
         m[tail] = me;
         v[tail] = ve;
-        p16[tail] = (uint16_t)h;
+        p16[tail] = (uint16_t)bf16_pack_rne(pe, 0.0f);
     }
 }
 
@@ -392,66 +413,88 @@ hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm,
 }
 
 typedef void (*adam_kernel_t)(float *, float *, float *, const uint16_t *, uint16_t *, uint64_t,
-                              StepScalars, const uint32_t *, uint32_t);
+                              StepScalars, const uint32_t *);
 
-template <int UNROLL, int NT>
-static adam_kernel_t pick_l2(bool l2)
+template <int WG, int UNROLL>
+static adam_kernel_t pick_flags(int policy, bool l2)
 {
-    return l2 ? k_adam_block_step<UNROLL, NT, true> : k_adam_block_step<UNROLL, NT, false>;
-}
-
-template <int UNROLL>
-static adam_kernel_t pick_nt(int nt_index, bool l2)
-{
-    switch (nt_index) {
-    case 0: return pick_l2<UNROLL, 0>(l2);
-    case 1: return pick_l2<UNROLL, 9>(l2);
-    case 2: return pick_l2<UNROLL, 12>(l2);
-    case 3: return pick_l2<UNROLL, 13>(l2);
-    case 4: return pick_l2<UNROLL, 15>(l2);
+    switch (policy) {
+    case 0: return l2 ? k_adam_block_step<WG, UNROLL, 0, true>
+                      : k_adam_block_step<WG, UNROLL, 0, false>;
+    case 1: return l2 ? k_adam_block_step<WG, UNROLL, 1, true>
+                      : k_adam_block_step<WG, UNROLL, 1, false>;
+    case 2: return l2 ? k_adam_block_step<WG, UNROLL, 2, true>
+                      : k_adam_block_step<WG, UNROLL, 2, false>;
     default: return nullptr;
     }
 }
 
+template <int WG>
+static adam_kernel_t pick_unroll(int unroll_index, int policy, bool l2)
+{
+    switch (unroll_index) {
+    case 0: return pick_flags<WG, 1>(policy, l2);
+    case 1: return pick_flags<WG, 2>(policy, l2);
+    case 2: return pick_flags<WG, 4>(policy, l2);
+    default: return nullptr;
+    }
+}
+
+// variant bits: [1:0] workgroup size index (64, 128, 256, 512 lanes), [3:2] unroll index (1, 2, 4
+// vectors per lane per tile), [5:4] cache policy (0 default, 1 nontemporal, 2 nontemporal loads
+// with write-through streaming stores).
 bool adam_variant_valid(int variant)
 {
-    if (variant < 0) return false;
-    const int unroll_index = variant & 3, nt_index = (variant >> 2) & 7, rest = variant >> 6;
-    return unroll_index < 3 && nt_index < 5 && rest == 0;
+    return variant >= 0 && variant < 64 && ((variant >> 2) & 3) < 3 && ((variant >> 4) & 3) < 3;
 }
 
 hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
                                   void *p16, uint64_t n, const StepScalars &s, bool l2,
-                                  const uint32_t *flag, int variant, uint32_t max_wgs,
+                                  const uint32_t *flag, const AdamLaunch &cfg, int cus,
                                   hipStream_t stream)
 {
     if (n == 0) return hipSuccess;
-    // variant bits: [1:0] unroll index (1, 2, 4 vectors per lane per trip), [4:2] nontemporal
-    // set index, [5] contiguous tile runs per workgroup instead of round-robin.
-    const int unroll_index = variant & 3, nt_index = (variant >> 2) & 7;
-    const bool blocked = ((variant >> 5) & 1) != 0;
+    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    const int wg_index = cfg.variant & 3, unroll_index = (cfg.variant >> 2) & 3;
+    const int policy = (cfg.variant >> 4) & 3;
+    const int wg = 64 << wg_index, unroll = 1 << unroll_index;
     adam_kernel_t kernel = nullptr;
-    int unroll = 1;
-    switch (unroll_index) {
-    case 0: kernel = pick_nt<1>(nt_index, l2); unroll = 1; break;
-    case 1: kernel = pick_nt<2>(nt_index, l2); unroll = 2; break;
-    case 2: kernel = pick_nt<4>(nt_index, l2); unroll = 4; break;
-    default: break;
+    switch (wg_index) {
+    case 0: kernel = pick_unroll<64>(unroll_index, policy, l2); break;
+    case 1: kernel = pick_unroll<128>(unroll_index, policy, l2); break;
+    case 2: kernel = pick_unroll<256>(unroll_index, policy, l2); break;
+    default: kernel = pick_unroll<512>(unroll_index, policy, l2); break;
     }
     if (kernel == nullptr) return hipErrorInvalidValue;
-    const uint64_t tile = (uint64_t)kThreads * 4 * unroll;
-    uint64_t ntiles = n / tile;
-    uint64_t want = ntiles > 0 ? ntiles : 1;
-    uint32_t grid = (uint32_t)(want < max_wgs ? want : max_wgs);
-    uint32_t tiles_per_wg = 0;
-    if (blocked && ntiles > 0) {
-        uint64_t per = (ntiles + grid - 1) / grid;
-        if (per > 0xFFFFFFFFull) return hipErrorInvalidValue;
-        tiles_per_wg = (uint32_t)per;
+
+    const uint64_t tile = (uint64_t)wg * 4 * unroll;
+    uint64_t want = n / tile;
+    if (want < 1) want = 1;
+    if (cfg.max_wgs_per_cu > 0) {
+        const uint64_t cap = (uint64_t)cus * (uint64_t)cfg.max_wgs_per_cu;
+        if (want > cap) want = cap;
     }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, stream, p, m, v,
+    if (want > 0x7FFFFFFFull) want = 0x7FFFFFFFull;      // grid-stride loop covers the rest
+
+    // Occupancy throttle: the kernel uses no LDS, so a dynamic LDS request per workgroup sized
+    // as a fraction of the CU's 160 KB bounds how many workgroups (hence wavefronts, hence bytes
+    // in flight) a CU holds at once.
+    size_t lds = 0;
+    const int waves_per_wg = wg / 64;
+    if (cfg.waves_per_cu > 0 && cfg.waves_per_cu < 32) {
+        int wgs = cfg.waves_per_cu / waves_per_wg;
+        if (wgs < 1) wgs = 1;
+        lds = (size_t)(kLdsBytesPerCu / wgs) / 256 * 256;
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)lds);
+            if (e != hipSuccess) return e;
+        }
+    }
+    hipLaunchKernelGGL(kernel, dim3((uint32_t)want), dim3(wg), lds, stream, p, m, v,
                        reinterpret_cast<const uint16_t *>(grad_fp16),
-                       reinterpret_cast<uint16_t *>(p16), n, s, flag, tiles_per_wg);
+                       reinterpret_cast<uint16_t *>(p16), n, s, flag);
     return hipGetLastError();
 }
 

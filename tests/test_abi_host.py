@@ -137,16 +137,19 @@ def test_clip_loss_scale_matches_oracle(lib, oracle):
 def test_launch_config_knob(lib):
     before = lohan.lohan_get_launch_config()
     try:
-        lohan.lohan_set_launch_config(2, 16, 4)
-        assert lohan.lohan_get_launch_config() == (2, 16, 4)
-        lohan.lohan_set_launch_config(0, 0, 0)
-        v, a, r = lohan.lohan_get_launch_config()
-        assert v == 0 and a > 0 and r > 0
-        for bad in (-1, 3, 5 << 2, 1 << 6):
+        lohan.lohan_set_launch_config(2 | (1 << 2) | (1 << 4), 16, 12, 4)
+        assert lohan.lohan_get_launch_config() == (2 | (1 << 2) | (1 << 4), 16, 12, 4)
+        lohan.lohan_set_launch_config()                       # all defaults
+        v, a, w, r = lohan.lohan_get_launch_config()
+        assert v >= 0 and a >= 0 and w >= 0 and r > 0
+        lohan.lohan_set_launch_config(0, 0, 0, 0)
+        assert lohan.lohan_get_launch_config()[:3] == (0, 0, 0)
+        for bad in (3 << 2, 3 << 4, 1 << 6, 1000):
             with pytest.raises(lohan.LohanError):
-                lohan.lohan_set_launch_config(bad, 0, 0)
-        with pytest.raises(lohan.LohanError):
-            lohan.lohan_set_launch_config(0, 100000, 0)
+                lohan.lohan_set_launch_config(bad, 0, 0, 0)
+        for bad in ((0, 100000, 0, 0), (0, 0, 33, 0), (0, 0, 0, 17)):
+            with pytest.raises(lohan.LohanError):
+                lohan.lohan_set_launch_config(*bad)
     finally:
         lohan.lohan_set_launch_config(*before)
 

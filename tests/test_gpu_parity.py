@@ -25,7 +25,7 @@ def say(msg):
 def _library_is_native():
     assert torch.cuda.is_available(), "these tests need a GPU"
     lohan.load_library()            # raises if the HIP library was not built
-    lohan.lohan_set_launch_config(1, 0, 0)
+    lohan.lohan_set_launch_config()         # built-in defaults, the shape bench.py times
     yield
 
 
@@ -57,11 +57,12 @@ def test_ten_chained_steps_small_sizes(oracle, l2_mode):
 
 
 def all_variants():
-    return [u | (nt << 2) | (b << 5) for b in (0, 1) for nt in range(5) for u in range(3)]
+    return [wg | (u << 2) | (pol << 4) for pol in range(3) for u in range(3) for wg in range(4)]
 
 
 def test_every_kernel_variant_matches(oracle):
-    """Every compiled launch shape (unroll x nontemporal set x tile mapping) at a ragged size."""
+    """Every compiled launch shape (workgroup size x unroll x cache policy), with and without a
+    grid cap and an occupancy throttle, at a ragged size."""
     n = 1_000_003
     wl = small_workload(n)
     ref_blk = synth.make_block(wl, seed=1, device=DEV)
@@ -70,14 +71,39 @@ def test_every_kernel_variant_matches(oracle):
     oracle_steps(oracle, host, hy, 2, nthreads=16)
     try:
         for variant in all_variants():
-            for wgs in (1, 8):
-                say(f"[variant] variant={variant} wgs_per_cu={wgs}")
-                lohan.lohan_set_launch_config(variant, wgs, 0)
+            for wgs, waves in ((0, 0), (1, 8), (8, 4), (0, 2)):
+                say(f"[variant] variant={variant} wgs_per_cu={wgs} waves_per_cu={waves}")
+                lohan.lohan_set_launch_config(variant, wgs, waves, 0)
                 blk = DeviceBlock({k: t.clone() for k, t in ref_blk.items()})
                 assert gpu_steps(blk, hy, 2) == [0, 0]
                 assert_state_parity(blk.host(), host, what=f"variant={variant}")
     finally:
-        lohan.lohan_set_launch_config(1, 0, 0)
+        lohan.lohan_set_launch_config()
+
+
+def test_bf16_copy_rounding_all_upper_halves(oracle):
+    """The hardware fp32->bf16 conversion against the oracle's round-to-nearest-even on crafted
+    parameters: every bf16 value's tie, just-below-tie and just-above-tie neighbour (lr = 0 and
+    wd = 0 make the step leave p unchanged, so p16 is the rounding of the crafted p)."""
+    hi = torch.arange(0, 1 << 16, dtype=torch.int64)
+    hi = hi[((hi >> 7) & 0xFF) != 0xFF]                       # finite bf16 values only
+    lows = torch.tensor([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=torch.int64)
+    bits = ((hi[:, None] << 16) | lows[None, :]).reshape(-1)
+    bits = bits[((bits >> 23) & 0xFF) != 0xFF]                # keep fp32 finite
+    n = bits.numel()
+    p = (bits.to(torch.int64) - ((bits >> 31) << 32)).to(torch.int32).view(torch.float32).to(DEV)
+    wl = small_workload(n)
+    t = synth.make_block(wl, seed=0, device=DEV)
+    t["p"] = p.contiguous()
+    t["g"].zero_()
+    blk = DeviceBlock(t)
+    host = blk.host()
+    hy = dict(wl.hyper(), lr=0.0, weight_decay=0.0)
+    assert gpu_steps(blk, hy, 1) == [0]
+    oracle_steps(oracle, host, hy, 1, nthreads=4)
+    got = blk.host()
+    assert np.array_equal(got["p"].view(np.uint32), host["p"].view(np.uint32))
+    assert np.array_equal(got["p16"], host["p16"])
 
 
 def test_config1_h768_block_ten_steps(oracle):
