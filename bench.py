@@ -28,6 +28,11 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 ADAM_BYTES_PER_ELEM = 28        # read g16 2 + p 4 + m 4 + v 4, write p 4 + m 4 + v 4 + bf16 2
 REDUCE_BYTES_PER_ELEM = 2       # one read of g16
 
+# HBM bytes per k_adam_block_step launch measured with two rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy:
+# factor 2.000 and 1.000 on gfx950).  Summary: profiles/k_adam_block_step_gpt13b_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {"gpt13b": 8601651 * 1024}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -40,6 +45,9 @@ def parse_args():
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks", type=int, default=40, help="stream13b: number of blocks")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy before the steps, so that a "
+                         "rocprofv3 --pmc run of this command holds a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -94,6 +102,13 @@ def bench_block(args, torch, lohan, synth):
 
     base = None if args.no_cpu_baseline else cpu_baseline(block, wl)
 
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)        # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     def one_step(t, ev=None):
         lohan.lohan_grad_sqnorm(block["g"], n, wl.loss_scale, sqnorm, flag, ws)
         if ev is not None:
@@ -140,7 +155,7 @@ def bench_block(args, torch, lohan, synth):
                          (elapsed / args.steps) / 1e9,
         "roofline": {"kernel": "k_adam_block_step", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None, "avg_launch_ms": adam_ms,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "avg_launch_ms": adam_ms,
                      "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
         "reduce_kernel": {"kernel": "k_grad_reduce+k_grad_finalize", "avg_ms": reduce_ms,
                           "achieved_gbps": REDUCE_BYTES_PER_ELEM * n / (reduce_ms * 1e-3) / 1e9},

@@ -19,7 +19,7 @@ std::atomic<int> g_cu_count[kMaxDevices];
 // Launch shape (overridable through lohan_set_launch_config for tuning sweeps).
 constexpr int kDefaultAdamVariant = 0 | (0 << 2) | (2 << 4);  // 64 lanes, 1 vector, streaming
 constexpr int kDefaultAdamWgsPerCu = 0;                       // one tile per workgroup
-constexpr int kDefaultAdamWavesPerCu = 10;                    // occupancy throttle
+constexpr int kDefaultAdamWavesPerCu = 11;                    // occupancy throttle
 constexpr int kDefaultReduceWgsPerCu = 2;
 std::atomic<int> g_adam_variant{kDefaultAdamVariant};
 std::atomic<int> g_adam_wgs_per_cu{kDefaultAdamWgsPerCu};
