@@ -122,6 +122,29 @@ lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *e
                                      void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 /*
+ * The same block step with per-block gradient-norm clipping resolved on the device, so that a
+ * clipping run needs no host round trip between lohan_grad_sqnorm and the update: the unscale
+ * factor is 1 / fp32(loss_scale / coef) with coef = min(1, max_norm / (sqrt(*sqnorm) + 1e-6)),
+ * evaluated in float64 by a one-lane kernel ahead of the update (same formula as
+ * lohan_clip_loss_scale).  *sqnorm and *overflow_flag must already hold this block's results of
+ * lohan_grad_sqnorm on `stream` (the flag is read-only here, as with LOHAN_FLAG_PRECHECKED; a set
+ * flag skips the step whatever *sqnorm holds).
+ *   sqnorm      device, in: one double, 8-byte aligned
+ *   max_norm    finite and > 0, else LOHAN_ERR_ARG
+ *   flags       LOHAN_FLAG_L2_MODE or 0 (LOHAN_FLAG_PRECHECKED is implied and may be given)
+ *   workspace   required (holds the device-side scalar); may be the one lohan_grad_sqnorm used
+ * Everything else as lohan_adam_block_step.
+ */
+lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, float *exp_avg_sq,
+                                             const void *grad_fp16, void *param_bf16_out,
+                                             uint64_t n, float lr, float beta1, float beta2,
+                                             float eps, float weight_decay, int64_t step,
+                                             float loss_scale, const double *sqnorm,
+                                             float max_norm, const uint32_t *overflow_flag,
+                                             uint32_t flags, void *workspace,
+                                             size_t workspace_bytes, hipStream_t stream);
+
+/*
  * Host-only helper for per-block gradient-norm clipping: returns the loss scale to hand to
  * lohan_adam_block_step so that unscaling and clipping are one multiply,
  *     coef = min(1, max_norm / (sqrt(sqnorm) + 1e-6)),   result = (float)(loss_scale / coef),
@@ -136,7 +159,9 @@ float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm);
  *   adam_variant            bits [1:0] workgroup size (64, 128, 256, 512 lanes), bits [3:2]
  *                           vectors per lane per tile (1, 2, 4), bits [5:4] cache policy (0 default,
  *                           1 nontemporal, 2 nontemporal loads + write-through streaming stores);
- *                           negative = built-in default; other values -> LOHAN_ERR_ARG
+ *                           negative = automatic (64 lanes, 1 vector; default policy for blocks
+ *                           that fit the 256 MiB memory-side cache, policy 2 above that; reported
+ *                           as -1 by lohan_get_launch_config); other values -> LOHAN_ERR_ARG
  *   adam_workgroups_per_cu  0 = one tile per workgroup (grid = number of tiles); > 0 caps the
  *                           grid at that many workgroups per compute unit; negative = default
  *   adam_waves_per_cu       occupancy throttle: at most this many wavefronts of the Adam kernel

@@ -20,7 +20,8 @@ LOHAN_FLAG_PRECHECKED = 2
 
 EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
-    "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_clip_loss_scale",
+    "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
+    "lohan_clip_loss_scale",
     "lohan_set_launch_config", "lohan_get_launch_config",
 )
 
@@ -59,6 +60,10 @@ def load_library():
     lib.lohan_adam_block_step.argtypes = [vp, vp, vp, vp, vp, u64, f32, f32, f32, f32, f32,
                                           ctypes.c_int64, f32, vp, ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_block_step.restype = ctypes.c_int
+    lib.lohan_adam_block_step_clipped.argtypes = [vp, vp, vp, vp, vp, u64, f32, f32, f32, f32,
+                                                  f32, ctypes.c_int64, f32, vp, f32, vp,
+                                                  ctypes.c_uint32, vp, sz, vp]
+    lib.lohan_adam_block_step_clipped.restype = ctypes.c_int
     lib.lohan_clip_loss_scale.argtypes = [ctypes.c_double, f32, f32]
     lib.lohan_clip_loss_scale.restype = f32
     lib.lohan_set_launch_config.argtypes = [ctypes.c_int] * 4
@@ -157,6 +162,21 @@ def lohan_adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16
         float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
         float(loss_scale), _addr(overflow_flag, 1, _U32, "overflow_flag"), int(flags),
         ws, ws_bytes, _stream(stream)))
+
+
+def lohan_adam_block_step_clipped(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n,
+                                  lr, beta1, beta2, eps, weight_decay, step, loss_scale,
+                                  sqnorm, max_norm, overflow_flag, flags, workspace,
+                                  workspace_bytes=None, stream=None):
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_adam_block_step_clipped(
+        _addr(param_fp32, n, _F32, "param_fp32"), _addr(exp_avg, n, _F32, "exp_avg"),
+        _addr(exp_avg_sq, n, _F32, "exp_avg_sq"), _addr(grad_fp16, n, _F16, "grad_fp16"),
+        _addr(param_bf16_out, n, _BF16, "param_bf16_out"), int(n),
+        float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
+        float(loss_scale), _addr(sqnorm, 1, _F64, "sqnorm"), float(max_norm),
+        _addr(overflow_flag, 1, _U32, "overflow_flag"), int(flags), ws, ws_bytes,
+        _stream(stream)))
 
 
 def lohan_clip_loss_scale(sqnorm, loss_scale, max_norm) -> float:

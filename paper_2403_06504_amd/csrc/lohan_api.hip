@@ -17,11 +17,17 @@ constexpr int kMaxDevices = 64;
 std::atomic<int> g_cu_count[kMaxDevices];
 
 // Launch shape (overridable through lohan_set_launch_config for tuning sweeps).
-constexpr int kDefaultAdamVariant = 0 | (0 << 2) | (2 << 4);  // 64 lanes, 1 vector, streaming
+// Automatic variant (-1): 64-lane workgroups, 1 vector per lane; the cache policy follows the
+// block's resident size (16 B/element): blocks that fit the 256 MiB memory-side cache keep the
+// default policy (measured +5 % there), everything larger streams past the caches.
+constexpr int kAutoAdamVariant = -1;
+constexpr int kStreamingVariant = 0 | (0 << 2) | (2 << 4);
+constexpr int kCacheResidentVariant = 0 | (0 << 2) | (0 << 4);
+constexpr uint64_t kCacheResidentBytes = 256ull << 20;
 constexpr int kDefaultAdamWgsPerCu = 0;                       // one tile per workgroup
 constexpr int kDefaultAdamWavesPerCu = 11;                    // occupancy throttle
 constexpr int kDefaultReduceWgsPerCu = 2;
-std::atomic<int> g_adam_variant{kDefaultAdamVariant};
+std::atomic<int> g_adam_variant{kAutoAdamVariant};
 std::atomic<int> g_adam_wgs_per_cu{kDefaultAdamWgsPerCu};
 std::atomic<int> g_adam_waves_per_cu{kDefaultAdamWavesPerCu};
 std::atomic<int> g_reduce_wgs_per_cu{kDefaultReduceWgsPerCu};
@@ -114,12 +120,13 @@ lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_s
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
-lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *exp_avg_sq,
-                                     const void *grad_fp16, void *param_bf16_out, uint64_t n,
-                                     float lr, float beta1, float beta2, float eps,
-                                     float weight_decay, int64_t step, float loss_scale,
-                                     uint32_t *overflow_flag, uint32_t flags, void *workspace,
-                                     size_t workspace_bytes, hipStream_t stream)
+namespace {
+
+lohan_status_t validate_step_args(const float *param_fp32, const float *exp_avg,
+                                  const float *exp_avg_sq, const void *grad_fp16,
+                                  const void *param_bf16_out, uint64_t n, float lr, float beta1,
+                                  float beta2, float eps, float weight_decay, int64_t step,
+                                  float loss_scale, const uint32_t *overflow_flag, uint32_t flags)
 {
     if (overflow_flag == nullptr) return LOHAN_ERR_NULL;
     if (n != 0 && (param_fp32 == nullptr || exp_avg == nullptr || exp_avg_sq == nullptr ||
@@ -134,16 +141,14 @@ lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *e
     if (step < 1 || !finite_pos(loss_scale) || !finite_nonneg(lr) || !finite_nonneg(eps) ||
         !finite_nonneg(weight_decay) || !unit_interval(beta1) || !unit_interval(beta2))
         return LOHAN_ERR_ARG;
-    const bool prechecked = (flags & LOHAN_FLAG_PRECHECKED) != 0;
-    if (!prechecked) {
-        lohan_status_t ws = check_workspace(workspace, workspace_bytes);
-        if (ws != LOHAN_OK) return ws;
-    }
-    const int cus = current_cu_count();
-    if (cus <= 0) return LOHAN_ERR_HIP;
+    return LOHAN_OK;
+}
 
-    // Element-independent scalars, each an individually rounded fp32 operation; the bias
-    // corrections go through float64 and are rounded once.
+// Element-independent scalars, each an individually rounded fp32 operation; the bias corrections
+// go through float64 and are rounded once.
+lohan::StepScalars make_step_scalars(float lr, float beta1, float beta2, float eps,
+                                     float weight_decay, int64_t step, float loss_scale)
+{
     lohan::StepScalars s;
     s.inv = 1.0f / loss_scale;
     s.beta1 = beta1;
@@ -158,18 +163,81 @@ lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *e
     s.decay = 1.0f - lr_wd;
     s.eps = eps;
     s.wd = weight_decay;
+    return s;
+}
 
+lohan::AdamLaunch adam_launch_for(uint64_t n)
+{
+    int variant = g_adam_variant.load();
+    if (variant < 0)
+        variant = n * 16 <= kCacheResidentBytes ? kCacheResidentVariant : kStreamingVariant;
+    return lohan::AdamLaunch{variant, g_adam_wgs_per_cu.load(), g_adam_waves_per_cu.load()};
+}
+
+}  // namespace
+
+lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *exp_avg_sq,
+                                     const void *grad_fp16, void *param_bf16_out, uint64_t n,
+                                     float lr, float beta1, float beta2, float eps,
+                                     float weight_decay, int64_t step, float loss_scale,
+                                     uint32_t *overflow_flag, uint32_t flags, void *workspace,
+                                     size_t workspace_bytes, hipStream_t stream)
+{
+    lohan_status_t st = validate_step_args(param_fp32, exp_avg, exp_avg_sq, grad_fp16,
+                                           param_bf16_out, n, lr, beta1, beta2, eps, weight_decay,
+                                           step, loss_scale, overflow_flag, flags);
+    if (st != LOHAN_OK) return st;
+    const bool prechecked = (flags & LOHAN_FLAG_PRECHECKED) != 0;
+    if (!prechecked) {
+        st = check_workspace(workspace, workspace_bytes);
+        if (st != LOHAN_OK) return st;
+    }
+    const int cus = current_cu_count();
+    if (cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::StepScalars s =
+        make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
     if (!prechecked) {
         const uint32_t red_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
         hipError_t e = lohan::launch_grad_reduce(grad_fp16, n, false, 0.0, nullptr, overflow_flag,
                                                  workspace, red_wgs, stream);
         if (e != hipSuccess) return LOHAN_ERR_HIP;
     }
-    const lohan::AdamLaunch cfg{g_adam_variant.load(), g_adam_wgs_per_cu.load(),
-                                g_adam_waves_per_cu.load()};
     hipError_t e = lohan::launch_adam_block_step(
         param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n, s,
-        (flags & LOHAN_FLAG_L2_MODE) != 0, overflow_flag, cfg, cus, stream);
+        (flags & LOHAN_FLAG_L2_MODE) != 0, overflow_flag, nullptr, adam_launch_for(n), cus, stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
+lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, float *exp_avg_sq,
+                                             const void *grad_fp16, void *param_bf16_out,
+                                             uint64_t n, float lr, float beta1, float beta2,
+                                             float eps, float weight_decay, int64_t step,
+                                             float loss_scale, const double *sqnorm,
+                                             float max_norm, const uint32_t *overflow_flag,
+                                             uint32_t flags, void *workspace,
+                                             size_t workspace_bytes, hipStream_t stream)
+{
+    lohan_status_t st = validate_step_args(param_fp32, exp_avg, exp_avg_sq, grad_fp16,
+                                           param_bf16_out, n, lr, beta1, beta2, eps, weight_decay,
+                                           step, loss_scale, overflow_flag, flags);
+    if (st != LOHAN_OK) return st;
+    if (sqnorm == nullptr) return LOHAN_ERR_NULL;
+    if (misaligned(sqnorm, 8)) return LOHAN_ERR_ALIGN;
+    if (!finite_pos(max_norm)) return LOHAN_ERR_ARG;
+    st = check_workspace(workspace, workspace_bytes);
+    if (st != LOHAN_OK) return st;
+    const int cus = current_cu_count();
+    if (cus <= 0) return LOHAN_ERR_HIP;
+    if (n == 0) return LOHAN_OK;
+    const lohan::StepScalars s =
+        make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
+    float *inv_dev = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
+                                               lohan::kScalarsOffset);
+    hipError_t e = lohan::launch_clip_scale(sqnorm, loss_scale, max_norm, inv_dev, stream);
+    if (e != hipSuccess) return LOHAN_ERR_HIP;
+    e = lohan::launch_adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out,
+                                      n, s, (flags & LOHAN_FLAG_L2_MODE) != 0, overflow_flag,
+                                      inv_dev, adam_launch_for(n), cus, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -187,8 +255,8 @@ float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm)
 lohan_status_t lohan_set_launch_config(int adam_variant, int adam_workgroups_per_cu,
                                        int adam_waves_per_cu, int reduce_workgroups_per_cu)
 {
-    if (adam_variant < 0) adam_variant = kDefaultAdamVariant;
-    if (!lohan::adam_variant_valid(adam_variant)) return LOHAN_ERR_ARG;
+    if (adam_variant < 0) adam_variant = kAutoAdamVariant;
+    else if (!lohan::adam_variant_valid(adam_variant)) return LOHAN_ERR_ARG;
     if (adam_workgroups_per_cu > 4096 || adam_waves_per_cu > 32 || reduce_workgroups_per_cu > 16)
         return LOHAN_ERR_ARG;
     g_adam_variant.store(adam_variant);

@@ -22,9 +22,11 @@ struct StepScalars {
     float wd;
 };
 
-// Workspace layout: kMaxPartials doubles, then kMaxPartials uint32 flags.
+// Workspace layout: kMaxPartials doubles, then kMaxPartials uint32 flags, then 256 bytes of
+// per-call scalars (the clipped step's unscale factor).
 constexpr uint32_t kMaxPartials = 4096;
-constexpr size_t kWorkspaceBytes = (size_t)kMaxPartials * (sizeof(double) + sizeof(uint32_t));
+constexpr size_t kScalarsOffset = (size_t)kMaxPartials * (sizeof(double) + sizeof(uint32_t));
+constexpr size_t kWorkspaceBytes = kScalarsOffset + 256;
 
 hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm, double inv2,
                               double *sqnorm, uint32_t *flag, void *workspace, uint32_t max_wgs,
@@ -44,8 +46,11 @@ bool adam_variant_valid(int variant);
 
 hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
                                   void *p16, uint64_t n, const StepScalars &s, bool l2,
-                                  const uint32_t *flag, const AdamLaunch &cfg, int cus,
-                                  hipStream_t stream);
+                                  const uint32_t *flag, const float *inv_override,
+                                  const AdamLaunch &cfg, int cus, hipStream_t stream);
+
+hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,
+                             float *inv_out, hipStream_t stream);
 
 }  // namespace lohan
 

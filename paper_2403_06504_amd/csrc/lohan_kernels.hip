@@ -306,10 +306,13 @@ __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
                                                         const uint16_t *__restrict__ g,
                                                         uint16_t *__restrict__ p16, uint64_t n,
                                                         StepScalars s,
-                                                        const uint32_t *__restrict__ flag)
+                                                        const uint32_t *__restrict__ flag,
+                                                        const float *__restrict__ inv_override)
 {
     // Skip rule: a set overflow flag means nothing at all is written by this kernel.
     if (*flag != 0u) return;
+    // Device-side clipping: the unscale factor then comes from k_clip_scale's output.
+    if (inv_override != nullptr) s.inv = *inv_override;
 
     constexpr uint64_t kVec = 4;                                  // elements per lane per access
     constexpr uint64_t kRow = (uint64_t)WG * kVec;                // elements per wg-wide access
@@ -372,6 +375,22 @@ __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
     }
 }
 
+// Per-block norm clipping without a host round trip: from the squared norm that
+// lohan_grad_sqnorm left in device memory, compute the unscale factor of the clipped step,
+//     coef = min(1, max_norm / (sqrt(sqnorm) + 1e-6)),  S_eff = fp32(S / coef),  inv = fl(1 / S_eff),
+// in float64 until the two roundings shown -- the same formula as lohan_clip_loss_scale on the
+// host.  One lane; the result is read by every wavefront of the following k_adam_block_step.
+__global__ void k_clip_scale(const double *__restrict__ sqnorm, float loss_scale, float max_norm,
+                             float *__restrict__ inv_out)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const double norm = __builtin_sqrt(*sqnorm);
+    double coef = (double)max_norm / (norm + 1e-6);
+    if (coef > 1.0) coef = 1.0;
+    const float s_eff = (float)((double)loss_scale / coef);
+    *inv_out = 1.0f / s_eff;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Host-side launchers (no validation here: the C ABI layer has done it).
 // ------------------------------------------------------------------------------------------------
@@ -412,8 +431,16 @@ hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm,
     return hipGetLastError();
 }
 
+hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,
+                             float *inv_out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_clip_scale, dim3(1), dim3(64), 0, stream, sqnorm, loss_scale, max_norm,
+                       inv_out);
+    return hipGetLastError();
+}
+
 typedef void (*adam_kernel_t)(float *, float *, float *, const uint16_t *, uint16_t *, uint64_t,
-                              StepScalars, const uint32_t *);
+                              StepScalars, const uint32_t *, const float *);
 
 template <int WG, int UNROLL>
 static adam_kernel_t pick_flags(int policy, bool l2)
@@ -450,8 +477,8 @@ bool adam_variant_valid(int variant)
 
 hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
                                   void *p16, uint64_t n, const StepScalars &s, bool l2,
-                                  const uint32_t *flag, const AdamLaunch &cfg, int cus,
-                                  hipStream_t stream)
+                                  const uint32_t *flag, const float *inv_override,
+                                  const AdamLaunch &cfg, int cus, hipStream_t stream)
 {
     if (n == 0) return hipSuccess;
     if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
@@ -494,7 +521,7 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
     }
     hipLaunchKernelGGL(kernel, dim3((uint32_t)want), dim3(wg), lds, stream, p, m, v,
                        reinterpret_cast<const uint16_t *>(grad_fp16),
-                       reinterpret_cast<uint16_t *>(p16), n, s, flag);
+                       reinterpret_cast<uint16_t *>(p16), n, s, flag, inv_override);
     return hipGetLastError();
 }
 

@@ -39,7 +39,7 @@ def test_header_declares_the_three_named_entry_points():
 
 def test_library_exports_every_declared_symbol(lib):
     names = declared_functions()
-    assert len(names) >= 8
+    assert len(names) >= 9
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in the header but not exported"
     assert sorted(binding.EXPORTS) == names
@@ -110,6 +110,26 @@ def test_reduction_validation_returns_before_any_launch(lib):
     assert lib.lohan_grad_sqnorm(A, 8, f(1.0), A * 4, None, A * 2, 8, None) == 4
 
 
+def test_clipped_step_validation_returns_before_any_launch(lib):
+    ws_bytes = lib.lohan_workspace_bytes()
+
+    def status(sqnorm=A * 8, max_norm=1.0, flag=A * 6, ws=A * 7, wsb=ws_bytes, flags=0, step=1):
+        return lib.lohan_adam_block_step_clipped(
+            A, A * 2, A * 3, A * 4, A * 5, 16, GOOD["lr"], GOOD["beta1"], GOOD["beta2"],
+            GOOD["eps"], GOOD["weight_decay"], step, GOOD["loss_scale"], sqnorm, max_norm, flag,
+            flags, ws, wsb, None)
+
+    assert status(sqnorm=None) == 1
+    assert status(flag=None) == 1
+    assert status(sqnorm=A * 8 + 4) == 2
+    for bad in (0.0, -1.0, math.inf, math.nan):
+        assert status(max_norm=bad) == 3
+    assert status(step=0) == 3
+    assert status(flags=8) == 3
+    assert status(ws=None) == 1
+    assert status(wsb=ws_bytes - 1) == 4
+
+
 def test_binding_raises_with_status(lib):
     with pytest.raises(lohan.LohanError) as e:
         lohan.lohan_adam_block_step(A, A * 2, A * 3, A * 4, A * 5, 16, 1e-4, 0.9, 0.999, 1e-8,
@@ -141,7 +161,7 @@ def test_launch_config_knob(lib):
         assert lohan.lohan_get_launch_config() == (2 | (1 << 2) | (1 << 4), 16, 12, 4)
         lohan.lohan_set_launch_config()                       # all defaults
         v, a, w, r = lohan.lohan_get_launch_config()
-        assert v >= 0 and a >= 0 and w >= 0 and r > 0
+        assert v == -1 and a >= 0 and w >= 0 and r > 0        # -1: variant chosen per call
         lohan.lohan_set_launch_config(0, 0, 0, 0)
         assert lohan.lohan_get_launch_config()[:3] == (0, 0, 0)
         for bad in (3 << 2, 3 << 4, 1 << 6, 1000):

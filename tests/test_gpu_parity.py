@@ -290,6 +290,87 @@ def test_prechecked_flag_is_honoured(oracle):
     assert_state_parity(blk.host(), host, what="prechecked, no workspace")
 
 
+@pytest.mark.parametrize("n,S,max_norm", [(1_000_003, 65536.0, 1.0), (300_007, 1024.0, 0.05),
+                                          (70_001, 3000.0, 0.1), (5_000, 65536.0, 100.0),
+                                          (257, 1.0, 1e-3)])
+def test_device_side_clipping(oracle, n, S, max_norm):
+    """lohan_adam_block_step_clipped resolves the clip coefficient on the device.  It must be
+    bit-identical to the host route through lohan_clip_loss_scale (same formula, same norm), and
+    match the oracle, which clips with its own norm: bit-exact when both effective scales round
+    to the same fp32 value, within the 2-ulp bar otherwise."""
+    wl = small_workload(n, S=S)
+    hy = wl.hyper()
+    base = synth.make_block(wl, seed=11, device=DEV)
+    dev_route = DeviceBlock({k: t.clone() for k, t in base.items()})
+    host_route = DeviceBlock({k: t.clone() for k, t in base.items()})
+    host = dev_route.host()
+
+    dev_route.norm(S)
+    lohan.lohan_adam_block_step_clipped(
+        dev_route.p, dev_route.m, dev_route.v, dev_route.g, dev_route.p16, n, hy["lr"],
+        hy["beta1"], hy["beta2"], hy["eps"], hy["weight_decay"], hy["step"], S, dev_route.sqnorm,
+        max_norm, dev_route.flag, 0, dev_route.ws)
+    torch.cuda.synchronize()
+    assert dev_route.flag_value() == 0
+
+    host_route.norm(S)
+    torch.cuda.synchronize()
+    sq_gpu = float(host_route.sqnorm.cpu().item())
+    s_eff_gpu = lohan.lohan_clip_loss_scale(sq_gpu, S, max_norm)
+    host_route.step(dict(hy, loss_scale=s_eff_gpu), flags=lohan.LOHAN_FLAG_PRECHECKED)
+    torch.cuda.synchronize()
+    a, b = dev_route.host(), host_route.host()
+    for k in ("p", "m", "v", "p16"):
+        assert np.array_equal(a[k].view(np.uint8), b[k].view(np.uint8)), k
+
+    sq_orc = oracle.grad_sqnorm(host["g"], S)
+    assert abs(sq_gpu - sq_orc) <= RTOL_SQNORM * sq_orc
+    s_eff_orc = float(oracle.clip_loss_scale(sq_orc, S, max_norm))
+    if max_norm >= 100.0:
+        assert s_eff_orc == S                                  # norm below the threshold
+    else:
+        assert s_eff_orc > S                                   # really clipped
+    old = {k: host[k].copy() for k in ("p", "m", "v")}
+    oracle_steps(oracle, host, dict(hy, loss_scale=s_eff_orc), 1, nthreads=4)
+    if np.float32(s_eff_orc) == np.float32(s_eff_gpu):
+        worst = assert_state_parity(a, host, what="device-side clipping")
+        assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
+    else:
+        # The two norms agree to ~1e-8 but their effective scales rounded to neighbouring fp32
+        # values, so every unscaled gradient differs by one ulp between the two sides.  Outputs
+        # can then differ by a few ulp *of the operands that were summed* (sums may cancel), so
+        # the bound is taken at the operands' magnitude rather than at the result's.
+        assert abs(np.float32(s_eff_orc).view(np.uint32).astype(np.int64)
+                   - np.float32(s_eff_gpu).view(np.uint32).astype(np.int64)) == 1
+        gval = np.abs(host["g"].view(np.float16).astype(np.float32)) / np.float32(s_eff_orc)
+        mag = {"p": np.maximum(np.maximum(np.abs(old["p"]), np.abs(host["p"])),
+                               np.float32(hy["lr"])),
+               "m": np.maximum(np.maximum(np.abs(old["m"]), np.abs(host["m"])), gval),
+               "v": np.maximum(np.maximum(old["v"], host["v"]), gval * gval)}
+        for k in ("p", "m", "v"):
+            err = np.abs(a[k].astype(np.float64) - host[k].astype(np.float64))
+            bound = 4 * np.spacing(mag[k]).astype(np.float64)
+            i = int(np.argmax(err - bound))
+            assert np.all(err <= bound), (k, i, float(err[i]), float(bound[i]),
+                                          {q: float(old[q][i]) for q in old},
+                                          float(a[k][i]), float(host[k][i]), float(gval[i]))
+
+    # an overflowing block is skipped whatever the norm holds
+    skip = DeviceBlock({k: t.clone() for k, t in base.items()})
+    skip.g.view(torch.int16)[n // 2] = 0x7C00
+    before = skip.host()
+    skip.norm(S)
+    lohan.lohan_adam_block_step_clipped(
+        skip.p, skip.m, skip.v, skip.g, skip.p16, n, hy["lr"], hy["beta1"], hy["beta2"],
+        hy["eps"], hy["weight_decay"], hy["step"], S, skip.sqnorm, max_norm, skip.flag,
+        lohan.LOHAN_FLAG_L2_MODE, skip.ws)
+    torch.cuda.synchronize()
+    assert skip.flag_value() == 1
+    after = skip.host()
+    for k in ("p", "m", "v", "p16"):
+        assert np.array_equal(after[k].view(np.uint8), before[k].view(np.uint8)), k
+
+
 @pytest.mark.parametrize("S", [65536.0, 1024.0, 3000.0, 1.0])
 def test_sqnorm_parity_and_determinism(oracle, S):
     for n in (0, 1, 5, 8, 2047, 8192, 8193, 65537, 3_000_001, 40_000_003):
