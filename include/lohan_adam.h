@@ -153,6 +153,75 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
  */
 float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm);
 
+/* ---------------------------------------------------------------------------------------------
+ * Active gradient offloading pipeline (Sec. IV-C, Fig. 3) for model states kept outside HBM.
+ *
+ * The paper's handler for gradient tensor i has three steps: bring the model states of block i
+ * in from the far tier, run the step, push the updated states back; "naive" active gradient
+ * offloading serialises them (Fig. 3a), the "optimized" schedule overlaps the transfers of
+ * neighbouring blocks with the compute (Fig. 3b).  Here the far tier is PINNED HOST memory and
+ * the compute is the block step above, run in place in a device staging slot:
+ *     H2D p,m,v (12 B/element)  ->  flag/norm pass + lohan_adam_block_step  ->  D2H p,m,v
+ * on three internal streams chained by events.  Gradients and the bf16 copy stay in HBM.
+ * With LOHAN_OFFLOAD_OVERLAPPED and >= 3 slots, H2D(i+1), step(i) and D2H(i-1) run concurrently
+ * (PCIe is full duplex); LOHAN_OFFLOAD_SERIALIZED reproduces the naive schedule for comparison.
+ * A skipped (overflowing) block is copied back bit-identical.
+ *
+ * The handle owns three streams and 4 events per slot, nothing else: the staging memory
+ * (`device_slab`, lohan_offload_slab_bytes() bytes, 256-byte aligned) is the caller's and must
+ * outlive the handle.  A handle is bound to the device that was current at creation and is not
+ * thread-safe.  Host state arrays must be pinned (hipHostMalloc or equivalent), otherwise the
+ * copies are not asynchronous.
+ */
+typedef struct lohan_offload lohan_offload_t;
+
+enum { LOHAN_OFFLOAD_SERIALIZED = 0, LOHAN_OFFLOAD_OVERLAPPED = 1 };
+
+typedef struct {
+    float *host_param_fp32;   /* pinned host, in/out: n floats */
+    float *host_exp_avg;      /* pinned host, in/out: n floats */
+    float *host_exp_avg_sq;   /* pinned host, in/out: n floats */
+    const void *grad_fp16;    /* device, in : n binary16 values, 16-byte aligned */
+    void *param_bf16_out;     /* device, out: n bfloat16 values, 16-byte aligned */
+    uint64_t n;               /* 1 <= n <= max_block_elems of the handle */
+    uint32_t *overflow_flag;  /* device, out: this block's flag (one uint32 per block) */
+    double *sqnorm;           /* device, out: this block's squared norm, or NULL (then only the
+                                 flag is computed); required when max_norm > 0 */
+} lohan_offload_block_t;
+
+/* Bytes of device staging memory a handle with these parameters needs. 0 if num_slots < 1. */
+size_t lohan_offload_slab_bytes(uint64_t max_block_elems, int num_slots);
+
+/* num_slots in [1, 16] (3 gives full overlap); mode is LOHAN_OFFLOAD_*.  LOHAN_ERR_WORKSPACE if
+ * the slab is too small, LOHAN_ERR_HIP if streams or events cannot be created. */
+lohan_status_t lohan_offload_create(lohan_offload_t **handle, void *device_slab,
+                                    size_t device_slab_bytes, uint64_t max_block_elems,
+                                    int num_slots, int mode);
+
+/*
+ * Enqueue stage-in, step and stage-out of one block and return.  The step waits for the work
+ * that `producer_stream` (the stream that writes the gradients) holds at the time of the call.
+ * Hyper-parameters as lohan_adam_block_step; max_norm > 0 turns on device-side per-block
+ * clipping (lohan_adam_block_step_clipped), 0 turns it off; flags: LOHAN_FLAG_L2_MODE or 0.
+ * The block's host arrays must not be touched until lohan_offload_drain (or a later
+ * synchronisation of the caller's own with the copy-out) and *blk itself is read only during
+ * the call.  Validation errors enqueue nothing.
+ */
+lohan_status_t lohan_offload_submit(lohan_offload_t *handle, const lohan_offload_block_t *blk,
+                                    float lr, float beta1, float beta2, float eps,
+                                    float weight_decay, int64_t step, float loss_scale,
+                                    float max_norm, uint32_t flags, hipStream_t producer_stream);
+
+/* Make `stream` wait (asynchronously) for the step of the most recently submitted block, i.e.
+ * until its bf16 copy, flag and norm are valid.  No-op before the first submit. */
+lohan_status_t lohan_offload_wait_last_step(lohan_offload_t *handle, hipStream_t stream);
+
+/* Block the host until everything submitted so far, copy-outs included, has completed. */
+lohan_status_t lohan_offload_drain(lohan_offload_t *handle);
+
+/* Drain, then release the streams, events and the handle. */
+lohan_status_t lohan_offload_destroy(lohan_offload_t *handle);
+
 /*
  * Launch-shape override for benchmarking and tuning sweeps (process-wide; do not change it while
  * calls are in flight on other threads).

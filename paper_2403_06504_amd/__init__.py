@@ -6,6 +6,14 @@ The product is the C-ABI library declared in include/lohan_adam.h (HIP kernels f
 fallback: calling an entry point without the built library raises.
 """
 from .binding import (  # noqa: F401
+    LOHAN_OFFLOAD_OVERLAPPED,
+    LOHAN_OFFLOAD_SERIALIZED,
+    lohan_offload_create,
+    lohan_offload_destroy,
+    lohan_offload_drain,
+    lohan_offload_slab_bytes,
+    lohan_offload_submit,
+    lohan_offload_wait_last_step,
     LOHAN_FLAG_L2_MODE,
     LOHAN_FLAG_PRECHECKED,
     LohanError,

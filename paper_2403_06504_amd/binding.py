@@ -23,7 +23,20 @@ EXPORTS = (
     "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
     "lohan_clip_loss_scale",
     "lohan_set_launch_config", "lohan_get_launch_config",
+    "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
+    "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
 )
+
+LOHAN_OFFLOAD_SERIALIZED = 0
+LOHAN_OFFLOAD_OVERLAPPED = 1
+
+
+class LohanOffloadBlock(ctypes.Structure):
+    """Mirror of lohan_offload_block_t."""
+    _fields_ = [("host_param_fp32", ctypes.c_void_p), ("host_exp_avg", ctypes.c_void_p),
+                ("host_exp_avg_sq", ctypes.c_void_p), ("grad_fp16", ctypes.c_void_p),
+                ("param_bf16_out", ctypes.c_void_p), ("n", ctypes.c_uint64),
+                ("overflow_flag", ctypes.c_void_p), ("sqnorm", ctypes.c_void_p)]
 
 
 class LohanError(RuntimeError):
@@ -70,6 +83,20 @@ def load_library():
     lib.lohan_set_launch_config.restype = ctypes.c_int
     lib.lohan_get_launch_config.argtypes = [ctypes.POINTER(ctypes.c_int)] * 4
     lib.lohan_get_launch_config.restype = None
+    lib.lohan_offload_slab_bytes.argtypes = [u64, ctypes.c_int]
+    lib.lohan_offload_slab_bytes.restype = sz
+    lib.lohan_offload_create.argtypes = [ctypes.POINTER(vp), vp, sz, u64, ctypes.c_int,
+                                         ctypes.c_int]
+    lib.lohan_offload_create.restype = ctypes.c_int
+    lib.lohan_offload_submit.argtypes = [vp, ctypes.POINTER(LohanOffloadBlock), f32, f32, f32,
+                                         f32, f32, ctypes.c_int64, f32, f32, ctypes.c_uint32, vp]
+    lib.lohan_offload_submit.restype = ctypes.c_int
+    lib.lohan_offload_wait_last_step.argtypes = [vp, vp]
+    lib.lohan_offload_wait_last_step.restype = ctypes.c_int
+    lib.lohan_offload_drain.argtypes = [vp]
+    lib.lohan_offload_drain.restype = ctypes.c_int
+    lib.lohan_offload_destroy.argtypes = [vp]
+    lib.lohan_offload_destroy.restype = ctypes.c_int
     _LIB = lib
     return lib
 
@@ -197,3 +224,45 @@ def lohan_get_launch_config():
     load_library().lohan_get_launch_config(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
                                            ctypes.byref(d))
     return a.value, b.value, c.value, d.value
+
+
+def lohan_offload_slab_bytes(max_block_elems, num_slots) -> int:
+    return int(load_library().lohan_offload_slab_bytes(int(max_block_elems), int(num_slots)))
+
+
+def lohan_offload_create(device_slab, max_block_elems, num_slots, mode, device_slab_bytes=None):
+    """Returns the opaque handle (an integer address) of a new pipeline."""
+    slab, nbytes = _workspace(device_slab, device_slab_bytes)
+    handle = ctypes.c_void_p()
+    _check(load_library().lohan_offload_create(ctypes.byref(handle), slab, nbytes,
+                                               int(max_block_elems), int(num_slots), int(mode)))
+    return handle.value
+
+
+def lohan_offload_submit(handle, host_param_fp32, host_exp_avg, host_exp_avg_sq, grad_fp16,
+                         param_bf16_out, n, overflow_flag, sqnorm, lr, beta1, beta2, eps,
+                         weight_decay, step, loss_scale, max_norm, flags, producer_stream=None):
+    """Host arrays: pinned CPU torch tensors (or raw addresses); the rest device tensors."""
+    blk = LohanOffloadBlock(
+        _addr(host_param_fp32, n, _F32, "host_param_fp32"),
+        _addr(host_exp_avg, n, _F32, "host_exp_avg"),
+        _addr(host_exp_avg_sq, n, _F32, "host_exp_avg_sq"),
+        _addr(grad_fp16, n, _F16, "grad_fp16"),
+        _addr(param_bf16_out, n, _BF16, "param_bf16_out"), int(n),
+        _addr(overflow_flag, 1, _U32, "overflow_flag"), _addr(sqnorm, 1, _F64, "sqnorm"))
+    _check(load_library().lohan_offload_submit(
+        handle, ctypes.byref(blk), float(lr), float(beta1), float(beta2), float(eps),
+        float(weight_decay), int(step), float(loss_scale), float(max_norm), int(flags),
+        _stream(producer_stream)))
+
+
+def lohan_offload_wait_last_step(handle, stream=None):
+    _check(load_library().lohan_offload_wait_last_step(handle, _stream(stream)))
+
+
+def lohan_offload_drain(handle):
+    _check(load_library().lohan_offload_drain(handle))
+
+
+def lohan_offload_destroy(handle):
+    _check(load_library().lohan_offload_destroy(handle))

@@ -12,7 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblohan_adam.so")
-SOURCES = [os.path.join(CSRC, "lohan_kernels.hip"), os.path.join(CSRC, "lohan_api.hip")]
+SOURCES = [os.path.join(CSRC, "lohan_kernels.hip"), os.path.join(CSRC, "lohan_api.hip"),
+           os.path.join(CSRC, "lohan_offload.hip")]
 HEADERS = [os.path.join(CSRC, "lohan_kernels.h"), os.path.join(ROOT, "include", "lohan_adam.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -96,3 +96,27 @@ def assert_state_parity(got: dict, want: dict, what=""):
         assert worst[k] <= ULP_F32, f"{what}: {k} differs by {worst[k]} ulp (bar {ULP_F32})"
     assert worst["p16"] <= ULP_BF16, f"{what}: p16 differs by {worst['p16']} ulp (bar {ULP_BF16})"
     return worst
+
+
+def assert_parity_given_scales(got: dict, want: dict, old: dict, g_bits, s_eff_gpu, s_eff_orc, lr,
+                               what=""):
+    """Compare a clipped step.  `want` is the oracle's result with ITS effective loss scale,
+    `old` the state before the step.  Equal effective scales (as fp32) demand bit equality; scales
+    one ulp apart make every unscaled gradient differ by one ulp between the two sides, so the
+    outputs may differ by a few ulp of the operands that were summed (sums can cancel): the bound
+    is then taken at the operands' magnitude."""
+    a32, b32 = np.float32(s_eff_gpu), np.float32(s_eff_orc)
+    if a32 == b32:
+        worst = assert_state_parity(got, want, what=what)
+        assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}, (what, worst)
+        return
+    assert abs(int(a32.view(np.uint32)) - int(b32.view(np.uint32))) == 1, (what, a32, b32)
+    gval = np.abs(g_bits.view(np.float16).astype(np.float32)) / b32
+    mag = {"p": np.maximum(np.maximum(np.abs(old["p"]), np.abs(want["p"])), np.float32(lr)),
+           "m": np.maximum(np.maximum(np.abs(old["m"]), np.abs(want["m"])), gval),
+           "v": np.maximum(np.maximum(old["v"], want["v"]), gval * gval)}
+    for k in ("p", "m", "v"):
+        err = np.abs(got[k].astype(np.float64) - want[k].astype(np.float64))
+        bound = 4 * np.spacing(mag[k]).astype(np.float64)
+        i = int(np.argmax(err - bound))
+        assert np.all(err <= bound), (what, k, i, float(err[i]), float(bound[i]))

@@ -130,6 +130,23 @@ def test_clipped_step_validation_returns_before_any_launch(lib):
     assert status(wsb=ws_bytes - 1) == 4
 
 
+def test_offload_create_validation_touches_no_device(lib):
+    handle = ctypes.c_void_p()
+    need = lib.lohan_offload_slab_bytes(1000, 3)
+    assert need >= 3 * (3 * 4000 + lib.lohan_workspace_bytes()) and need % 256 == 0
+    assert lib.lohan_offload_slab_bytes(1000, 0) == 0
+    assert lib.lohan_offload_create(None, A * 16, need, 1000, 3, 1) == 1
+    assert lib.lohan_offload_create(ctypes.byref(handle), None, need, 1000, 3, 1) == 1
+    assert lib.lohan_offload_create(ctypes.byref(handle), A * 16 + 64, need, 1000, 3, 1) == 2
+    for bad in ((0, 3, 1), (1000, 0, 1), (1000, 17, 1), (1000, 3, 2), (1000, 3, -1)):
+        assert lib.lohan_offload_create(ctypes.byref(handle), A * 16, need, *bad) == 3
+    assert lib.lohan_offload_create(ctypes.byref(handle), A * 16, need - 1, 1000, 3, 1) == 4
+    assert handle.value is None
+    assert lib.lohan_offload_drain(None) == 1 and lib.lohan_offload_destroy(None) == 1
+    assert lib.lohan_offload_wait_last_step(None, None) == 1
+    assert lib.lohan_offload_submit(None, None, 0, 0, 0, 0, 0, 1, 1, 0, 0, None) == 1
+
+
 def test_binding_raises_with_status(lib):
     with pytest.raises(lohan.LohanError) as e:
         lohan.lohan_adam_block_step(A, A * 2, A * 3, A * 4, A * 5, 16, 1e-4, 0.9, 0.999, 1e-8,
