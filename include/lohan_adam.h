@@ -52,7 +52,10 @@ enum {
     LOHAN_FLAG_L2_MODE = 1u,
     /* *overflow_flag already holds this block's flag on `stream` (from lohan_grad_overflow_check
      * or lohan_grad_sqnorm): lohan_adam_block_step then skips its own 2 B/element check pass. */
-    LOHAN_FLAG_PRECHECKED = 2u
+    LOHAN_FLAG_PRECHECKED = 2u,
+    /* Emit the 16-bit working copy as IEEE binary16 (round to nearest even, overflow to infinity)
+     * instead of bfloat16; param_bf16_out then receives n binary16 values. */
+    LOHAN_FLAG_P16_FP16 = 4u
 };
 
 /* Device scratch bytes one call needs (a constant of the build; a few tens of KiB). */
@@ -99,7 +102,7 @@ lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_s
  *     v'  = beta2 * v + (1 - beta2) * (g * g)
  *     den = sqrt(v') / sqrt(1 - beta2^step) + eps
  *     p'  = p * (1 - lr * wd) - (lr / (1 - beta1^step)) * (m' / den)     [L2 mode: no p factor]
- *     p16 = bfloat16 round-to-nearest-even of p'
+ *     p16 = bfloat16 round-to-nearest-even of p'        [LOHAN_FLAG_P16_FP16: binary16 instead]
  * and p', m', v' overwrite p, m, v (1 - beta^step is evaluated in float64 and rounded once).
  *
  *   param_fp32, exp_avg, exp_avg_sq   device, in/out: n floats each
@@ -131,7 +134,8 @@ lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *e
  * flag skips the step whatever *sqnorm holds).
  *   sqnorm      device, in: one double, 8-byte aligned
  *   max_norm    finite and > 0, else LOHAN_ERR_ARG
- *   flags       LOHAN_FLAG_L2_MODE or 0 (LOHAN_FLAG_PRECHECKED is implied and may be given)
+ *   flags       LOHAN_FLAG_L2_MODE and/or LOHAN_FLAG_P16_FP16 (LOHAN_FLAG_PRECHECKED is implied
+ *               and may be given)
  *   workspace   required (holds the device-side scalar); may be the one lohan_grad_sqnorm used
  * Everything else as lohan_adam_block_step.
  */
@@ -202,7 +206,8 @@ lohan_status_t lohan_offload_create(lohan_offload_t **handle, void *device_slab,
  * Enqueue stage-in, step and stage-out of one block and return.  The step waits for the work
  * that `producer_stream` (the stream that writes the gradients) holds at the time of the call.
  * Hyper-parameters as lohan_adam_block_step; max_norm > 0 turns on device-side per-block
- * clipping (lohan_adam_block_step_clipped), 0 turns it off; flags: LOHAN_FLAG_L2_MODE or 0.
+ * clipping (lohan_adam_block_step_clipped), 0 turns it off; flags: LOHAN_FLAG_L2_MODE and/or
+ * LOHAN_FLAG_P16_FP16.
  * The block's host arrays must not be touched until lohan_offload_drain (or a later
  * synchronisation of the caller's own with the copy-out) and *blk itself is read only during
  * the call.  Validation errors enqueue nothing.
@@ -225,8 +230,8 @@ lohan_status_t lohan_offload_destroy(lohan_offload_t *handle);
 /*
  * Launch-shape override for benchmarking and tuning sweeps (process-wide; do not change it while
  * calls are in flight on other threads).
- *   adam_variant            bits [1:0] workgroup size (64, 128, 256, 512 lanes), bits [3:2]
- *                           vectors per lane per tile (1, 2, 4), bits [5:4] cache policy (0 default,
+ *   adam_variant            bits [1:0] workgroup size (64, 128, 256 lanes), bits [3:2]
+ *                           vectors per lane per tile (1, 2), bits [5:4] cache policy (0 default,
  *                           1 nontemporal, 2 nontemporal loads + write-through streaming stores);
  *                           negative = automatic (64 lanes, 1 vector; default policy for blocks
  *                           that fit the 256 MiB memory-side cache, policy 2 above that; reported

@@ -117,6 +117,26 @@ def bf16_bits_rne(x: Fraction) -> int:
     return sign | (bits32 >> 16)
 
 
+def half_bits_rne(x: Fraction) -> int:
+    """binary16 bit pattern nearest to x (ties to even): 11 significant bits, smallest normal
+    2^-14, quantum 2^-24 below it, 65520 and above round to infinity."""
+    if x == 0:
+        return 0
+    sign = 0x8000 if x < 0 else 0
+    a = abs(x)
+    e = max(_floor_log2(a), -14)
+    quantum = Fraction(2) ** (e - 10)
+    r = _round_int_ties_even(a / quantum) * quantum
+    if r >= 65536:
+        return sign | 0x7C00
+    if r == 0:
+        return sign
+    er = _floor_log2(r)
+    if er < -14:
+        return sign | int(r / Fraction(2) ** -24)
+    return sign | ((er + 15) << 10) | (int(r / Fraction(2) ** (er - 10)) - 1024)
+
+
 def scalars(lr, beta1, beta2, wd, step, loss_scale):
     """Per-call scalars as Fractions (each an exact binary32 value)."""
     lr, beta1, beta2, wd, S = map(float_to_frac, (lr, beta1, beta2, wd, loss_scale))
@@ -135,7 +155,7 @@ def scalars(lr, beta1, beta2, wd, step, loss_scale):
 
 
 def adam_block_step_exact(p_bits, m_bits, v_bits, g16_bits, *, lr, beta1, beta2, eps,
-                          weight_decay, step, loss_scale, l2_mode=False):
+                          weight_decay, step, loss_scale, l2_mode=False, half_out=False):
     """Lists of binary32 bit patterns in, (p', m', v', bf16) lists of bit patterns out."""
     s = scalars(lr, beta1, beta2, weight_decay, step, loss_scale)
     eps = float_to_frac(eps)
@@ -157,5 +177,5 @@ def adam_block_step_exact(p_bits, m_bits, v_bits, g16_bits, *, lr, beta1, beta2,
         out_p.append(frac_to_f32_bits(p_new))
         out_m.append(frac_to_f32_bits(m_new))
         out_v.append(frac_to_f32_bits(v_new))
-        out_h.append(bf16_bits_rne(p_new))
+        out_h.append(half_bits_rne(p_new) if half_out else bf16_bits_rne(p_new))
     return out_p, out_m, out_v, out_h

@@ -70,6 +70,34 @@ static uint16_t float_to_bf16_bits_rne(float x)
     return (uint16_t)(b >> 16);
 }
 
+/* fp32 -> IEEE binary16 bit pattern, round to nearest, ties to even, overflow to infinity,
+ * gradual underflow.  Used when the caller asks for an fp16 (instead of bf16) working copy: the
+ * paper only says "16-bit parameter copy" (Sec. IV-C; P16 in Table II). */
+static uint16_t float_to_half_bits_rne(float x)
+{
+    uint32_t b;
+    memcpy(&b, &x, sizeof b);
+    uint16_t sign = (uint16_t)((b >> 16) & 0x8000u);
+    uint32_t a = b & 0x7FFFFFFFu;
+    if (a > 0x7F800000u) return (uint16_t)(sign | 0x7E00u);          /* NaN -> quiet NaN */
+    if (a >= 0x47800000u) return (uint16_t)(sign | 0x7C00u);         /* >= 65536 (and inf) */
+    if (a >= 0x38800000u) {                                          /* >= 2^-14: normal half */
+        uint32_t mant = a & 0x7FFFFFu;
+        uint32_t h = (((a >> 23) - 112u) << 10) | (mant >> 13);      /* rebias 127 -> 15 */
+        uint32_t rest = mant & 0x1FFFu;
+        if (rest > 0x1000u || (rest == 0x1000u && (h & 1u))) h += 1u; /* may carry up to inf */
+        return (uint16_t)(sign | h);
+    }
+    if (a <= 0x33000000u) return sign;                               /* <= 2^-25 rounds to zero */
+    uint32_t mant = (a & 0x7FFFFFu) | 0x800000u;                     /* subnormal half: units of */
+    uint32_t shift = 126u - (a >> 23);                               /* 2^-24                    */
+    uint32_t h = mant >> shift;
+    uint32_t rest = mant & ((1u << shift) - 1u);
+    uint32_t halfway = 1u << (shift - 1u);
+    if (rest > halfway || (rest == halfway && (h & 1u))) h += 1u;
+    return (uint16_t)(sign | h);
+}
+
 /* ---- gradient overflow test ------------------------------------------------------------- */
 
 /* 1 if any fp16 gradient of the block is +-inf or NaN (exponent field all ones), else 0.
@@ -141,7 +169,7 @@ void lohan_oracle_step_scalars(float lr, float beta1, float beta2, float wd, int
  * into the gradient (l2_mode != 0). */
 static inline void step_one(float *p, float *m, float *v, uint16_t g16, uint16_t *p16,
                             const step_scalars *s, float beta1, float beta2, float eps, float wd,
-                            int l2_mode)
+                            int l2_mode, int half_out)
 {
     float g = half_bits_to_float(g16) * s->inv;        /* unscale */
     if (l2_mode) {
@@ -165,23 +193,26 @@ static inline void step_one(float *p, float *m, float *v, uint16_t g16, uint16_t
     *p = p_new;
     *m = m_new;
     *v = v_new;
-    *p16 = float_to_bf16_bits_rne(p_new);              /* 16-bit working copy of the new p */
+    *p16 = half_out ? float_to_half_bits_rne(p_new)    /* 16-bit working copy of the new p */
+                    : float_to_bf16_bits_rne(p_new);
 }
 
 /* One block step.  Returns the overflow flag (0 or 1); when it is 1 nothing is written.
  * nthreads <= 1 runs the plain serial loop; larger values split the elementwise loop over that
- * many OpenMP threads (the elements are independent, so the result is bit-identical). */
+ * many OpenMP threads (the elements are independent, so the result is bit-identical).
+ * half_out != 0 emits the 16-bit copy as IEEE binary16 instead of bfloat16. */
 int lohan_oracle_adam_block_step(float *param_fp32, float *exp_avg, float *exp_avg_sq,
                                  const uint16_t *grad_fp16, uint16_t *param_bf16_out, uint64_t n,
                                  float lr, float beta1, float beta2, float eps, float weight_decay,
-                                 int64_t step, float loss_scale, int l2_mode, int nthreads)
+                                 int64_t step, float loss_scale, int l2_mode, int half_out,
+                                 int nthreads)
 {
     if (lohan_oracle_grad_overflow_check(grad_fp16, n)) return 1;
     step_scalars s = make_scalars(lr, beta1, beta2, weight_decay, step, loss_scale);
     if (nthreads <= 1) {
         for (uint64_t i = 0; i < n; ++i) {
             step_one(&param_fp32[i], &exp_avg[i], &exp_avg_sq[i], grad_fp16[i],
-                     &param_bf16_out[i], &s, beta1, beta2, eps, weight_decay, l2_mode);
+                     &param_bf16_out[i], &s, beta1, beta2, eps, weight_decay, l2_mode, half_out);
         }
     } else {
 #ifdef _OPENMP
@@ -189,7 +220,7 @@ int lohan_oracle_adam_block_step(float *param_fp32, float *exp_avg, float *exp_a
 #endif
         for (int64_t i = 0; i < (int64_t)n; ++i) {
             step_one(&param_fp32[i], &exp_avg[i], &exp_avg_sq[i], grad_fp16[i],
-                     &param_bf16_out[i], &s, beta1, beta2, eps, weight_decay, l2_mode);
+                     &param_bf16_out[i], &s, beta1, beta2, eps, weight_decay, l2_mode, half_out);
         }
     }
     return 0;
@@ -208,3 +239,4 @@ int lohan_oracle_max_threads(void)
 /* Format helpers exposed so tests can pin them against library conversions. */
 float lohan_oracle_half_bits_to_float(uint16_t h) { return half_bits_to_float(h); }
 uint16_t lohan_oracle_float_to_bf16_bits(float x) { return float_to_bf16_bits_rne(x); }
+uint16_t lohan_oracle_float_to_half_bits(float x) { return float_to_half_bits_rne(x); }

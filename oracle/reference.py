@@ -32,7 +32,7 @@ def _lib():
         lib.lohan_oracle_adam_block_step.argtypes = [
             f32p, f32p, f32p, u16p, u16p, ctypes.c_uint64,
             ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float,
-            ctypes.c_int64, ctypes.c_float, ctypes.c_int, ctypes.c_int]
+            ctypes.c_int64, ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.lohan_oracle_adam_block_step.restype = ctypes.c_int
         lib.lohan_oracle_max_threads.argtypes = []
         lib.lohan_oracle_max_threads.restype = ctypes.c_int
@@ -40,6 +40,8 @@ def _lib():
         lib.lohan_oracle_half_bits_to_float.restype = ctypes.c_float
         lib.lohan_oracle_float_to_bf16_bits.argtypes = [ctypes.c_float]
         lib.lohan_oracle_float_to_bf16_bits.restype = ctypes.c_uint16
+        lib.lohan_oracle_float_to_half_bits.argtypes = [ctypes.c_float]
+        lib.lohan_oracle_float_to_half_bits.restype = ctypes.c_uint16
         _LIB = lib
     return _LIB
 
@@ -74,8 +76,9 @@ def step_scalars(lr, beta1, beta2, weight_decay, step, loss_scale) -> dict:
 
 def adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16_bits, param_bf16_bits, *,
                     lr, beta1, beta2, eps, weight_decay, step, loss_scale, l2_mode=False,
-                    nthreads=1) -> int:
-    """One block step in place on numpy arrays; returns the overflow flag (1 = nothing written)."""
+                    half_out=False, nthreads=1) -> int:
+    """One block step in place on numpy arrays; returns the overflow flag (1 = nothing written).
+    half_out=True emits the 16-bit copy as IEEE binary16 instead of bfloat16."""
     n = param_fp32.size
     for a in (exp_avg, exp_avg_sq, grad_fp16_bits, param_bf16_bits):
         if a.size != n:
@@ -87,7 +90,7 @@ def adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16_bits, param_bf16_
         _ptr(grad_fp16_bits, np.uint16, ctypes.c_uint16),
         _ptr(param_bf16_bits, np.uint16, ctypes.c_uint16),
         n, lr, beta1, beta2, eps, weight_decay, int(step), loss_scale, int(bool(l2_mode)),
-        int(nthreads)))
+        int(bool(half_out)), int(nthreads)))
 
 
 def max_threads() -> int:
@@ -100,6 +103,10 @@ def half_bits_to_float(h: int) -> np.float32:
 
 def float_to_bf16_bits(x) -> int:
     return int(_lib().lohan_oracle_float_to_bf16_bits(np.float32(x)))
+
+
+def float_to_half_bits(x) -> int:
+    return int(_lib().lohan_oracle_float_to_half_bits(np.float32(x)))
 
 
 def clip_loss_scale(sqnorm: float, loss_scale: float, max_norm: float) -> np.float32:

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     lohan_offload_submit,
     lohan_offload_wait_last_step,
     LOHAN_FLAG_L2_MODE,
+    LOHAN_FLAG_P16_FP16,
     LOHAN_FLAG_PRECHECKED,
     LohanError,
     library_path,

@@ -17,6 +17,7 @@ _LIB = None
 LOHAN_OK = 0
 LOHAN_FLAG_L2_MODE = 1
 LOHAN_FLAG_PRECHECKED = 2
+LOHAN_FLAG_P16_FP16 = 4
 
 EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
@@ -147,7 +148,7 @@ def _workspace(workspace, workspace_bytes):
 
 
 _F16 = ("torch.float16", "torch.int16", "torch.uint16")
-_BF16 = ("torch.bfloat16", "torch.int16", "torch.uint16")
+_BF16 = ("torch.bfloat16", "torch.float16", "torch.int16", "torch.uint16")
 _F32 = ("torch.float32",)
 _U32 = ("torch.int32", "torch.uint32")
 _F64 = ("torch.float64",)

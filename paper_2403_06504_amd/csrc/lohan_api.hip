@@ -136,7 +136,7 @@ lohan_status_t validate_step_args(const float *param_fp32, const float *exp_avg,
         misaligned(grad_fp16, 16) || misaligned(param_bf16_out, 16) ||
         misaligned(overflow_flag, 4))
         return LOHAN_ERR_ALIGN;
-    if ((flags & ~(uint32_t)(LOHAN_FLAG_L2_MODE | LOHAN_FLAG_PRECHECKED)) != 0)
+    if ((flags & ~(uint32_t)(LOHAN_FLAG_L2_MODE | LOHAN_FLAG_PRECHECKED | LOHAN_FLAG_P16_FP16)) != 0)
         return LOHAN_ERR_ARG;
     if (step < 1 || !finite_pos(loss_scale) || !finite_nonneg(lr) || !finite_nonneg(eps) ||
         !finite_nonneg(weight_decay) || !unit_interval(beta1) || !unit_interval(beta2))
@@ -164,6 +164,12 @@ lohan::StepScalars make_step_scalars(float lr, float beta1, float beta2, float e
     s.eps = eps;
     s.wd = weight_decay;
     return s;
+}
+
+// Kernel mode bits from the ABI flags.
+int kernel_mode(uint32_t flags)
+{
+    return ((flags & LOHAN_FLAG_L2_MODE) ? 1 : 0) | ((flags & LOHAN_FLAG_P16_FP16) ? 2 : 0);
 }
 
 lohan::AdamLaunch adam_launch_for(uint64_t n)
@@ -204,7 +210,7 @@ lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *e
     }
     hipError_t e = lohan::launch_adam_block_step(
         param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n, s,
-        (flags & LOHAN_FLAG_L2_MODE) != 0, overflow_flag, nullptr, adam_launch_for(n), cus, stream);
+        kernel_mode(flags), overflow_flag, nullptr, adam_launch_for(n), cus, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -236,8 +242,8 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
     hipError_t e = lohan::launch_clip_scale(sqnorm, loss_scale, max_norm, inv_dev, stream);
     if (e != hipSuccess) return LOHAN_ERR_HIP;
     e = lohan::launch_adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out,
-                                      n, s, (flags & LOHAN_FLAG_L2_MODE) != 0, overflow_flag,
-                                      inv_dev, adam_launch_for(n), cus, stream);
+                                      n, s, kernel_mode(flags), overflow_flag, inv_dev,
+                                      adam_launch_for(n), cus, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 

@@ -44,8 +44,10 @@ struct AdamLaunch {
 
 bool adam_variant_valid(int variant);
 
+// mode bits of launch_adam_block_step: 1 = L2 regularisation, 2 = binary16 output copy.
+
 hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
-                                  void *p16, uint64_t n, const StepScalars &s, bool l2,
+                                  void *p16, uint64_t n, const StepScalars &s, int mode,
                                   const uint32_t *flag, const float *inv_override,
                                   const AdamLaunch &cfg, int cus, hipStream_t stream);
 

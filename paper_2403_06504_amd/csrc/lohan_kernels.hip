@@ -217,6 +217,22 @@ __device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
+// fp32 -> IEEE binary16, round to nearest even (v_cvt_f16_f32 under the default rounding mode),
+// overflow to infinity, gradual underflow.  Same packing as bf16_pack_rne.
+__device__ __forceinline__ uint32_t half_pack_rne(float lo, float hi)
+{
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    f32x2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
+}
+
+template <bool HALF_OUT>
+__device__ __forceinline__ uint32_t pack16(float lo, float hi)
+{
+    if constexpr (HALF_OUT) return half_pack_rne(lo, hi);
+    else return bf16_pack_rne(lo, hi);
+}
+
 template <bool L2>
 __device__ __forceinline__ void adam_elem(float &p, float &m, float &v, float g_scaled,
                                           const StepScalars &s)
@@ -245,7 +261,7 @@ __device__ __forceinline__ void adam_elem(float &p, float &m, float &v, float g_
     v = v_new;
 }
 
-template <bool L2>
+template <bool L2, bool HALF_OUT>
 __device__ __forceinline__ void adam_vec4(f32x4 &p, f32x4 &m, f32x4 &v, f16x4 g,
                                           const StepScalars &s, u32x2 &out16)
 {
@@ -257,8 +273,8 @@ __device__ __forceinline__ void adam_vec4(f32x4 &p, f32x4 &m, f32x4 &v, f16x4 g,
         m[k] = me;
         v[k] = ve;
     }
-    out16.x = bf16_pack_rne(p[0], p[1]);
-    out16.y = bf16_pack_rne(p[2], p[3]);
+    out16.x = pack16<HALF_OUT>(p[0], p[1]);
+    out16.y = pack16<HALF_OUT>(p[2], p[3]);
 }
 
 // Streaming stores with the write-through-to-memory cache policy (sc0 sc1 nt).  The compiler has
@@ -299,7 +315,9 @@ __device__ __forceinline__ void st_stream(T *ptr, T val)
 // window sliding through the buffers in address order (measured: this keeps HBM far busier than
 // a persistent grid-stride loop whose workgroups drift apart); the loop only runs more than once
 // when the host caps the grid.
-template <int WG, int UNROLL, int POLICY, bool L2>
+// MODE bits: 1 = L2 regularisation instead of decoupled decay, 2 = emit the 16-bit copy as IEEE
+// binary16 instead of bfloat16.
+template <int WG, int UNROLL, int POLICY, int MODE>
 __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
                                                         float *__restrict__ m,
                                                         float *__restrict__ v,
@@ -309,6 +327,7 @@ __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
                                                         const uint32_t *__restrict__ flag,
                                                         const float *__restrict__ inv_override)
 {
+    constexpr bool L2 = (MODE & 1) != 0, HALF_OUT = (MODE & 2) != 0;
     // Skip rule: a set overflow flag means nothing at all is written by this kernel.
     if (*flag != 0u) return;
     // Device-side clipping: the unscale factor then comes from k_clip_scale's output.
@@ -334,7 +353,8 @@ __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
             vv[j] = ld_stream<POLICY>(reinterpret_cast<const f32x4 *>(v + off));
         }
 #pragma unroll
-        for (int j = 0; j < UNROLL; ++j) adam_vec4<L2>(pv[j], mv[j], vv[j], gv[j], s, hv[j]);
+        for (int j = 0; j < UNROLL; ++j)
+            adam_vec4<L2, HALF_OUT>(pv[j], mv[j], vv[j], gv[j], s, hv[j]);
 #pragma unroll
         for (int j = 0; j < UNROLL; ++j) {
             const uint64_t off = base + j * kRow;
@@ -357,7 +377,7 @@ __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
         f32x4 mq = *reinterpret_cast<const f32x4 *>(m + off);
         f32x4 vq = *reinterpret_cast<const f32x4 *>(v + off);
         u32x2 h;
-        adam_vec4<L2>(pq, mq, vq, gq, s, h);
+        adam_vec4<L2, HALF_OUT>(pq, mq, vq, gq, s, h);
         *reinterpret_cast<f32x4 *>(p + off) = pq;
         *reinterpret_cast<f32x4 *>(m + off) = mq;
         *reinterpret_cast<f32x4 *>(v + off) = vq;
@@ -371,7 +391,7 @@ __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
         p[tail] = pe;
         m[tail] = me;
         v[tail] = ve;
-        p16[tail] = (uint16_t)bf16_pack_rne(pe, 0.0f);
+        p16[tail] = (uint16_t)pack16<HALF_OUT>(pe, 0.0f);
     }
 }
 
@@ -442,41 +462,49 @@ hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_n
 typedef void (*adam_kernel_t)(float *, float *, float *, const uint16_t *, uint16_t *, uint64_t,
                               StepScalars, const uint32_t *, const float *);
 
+template <int WG, int UNROLL, int POLICY>
+static adam_kernel_t pick_mode(int mode)
+{
+    switch (mode & 3) {
+    case 0: return k_adam_block_step<WG, UNROLL, POLICY, 0>;
+    case 1: return k_adam_block_step<WG, UNROLL, POLICY, 1>;
+    case 2: return k_adam_block_step<WG, UNROLL, POLICY, 2>;
+    default: return k_adam_block_step<WG, UNROLL, POLICY, 3>;
+    }
+}
+
 template <int WG, int UNROLL>
-static adam_kernel_t pick_flags(int policy, bool l2)
+static adam_kernel_t pick_policy(int policy, int mode)
 {
     switch (policy) {
-    case 0: return l2 ? k_adam_block_step<WG, UNROLL, 0, true>
-                      : k_adam_block_step<WG, UNROLL, 0, false>;
-    case 1: return l2 ? k_adam_block_step<WG, UNROLL, 1, true>
-                      : k_adam_block_step<WG, UNROLL, 1, false>;
-    case 2: return l2 ? k_adam_block_step<WG, UNROLL, 2, true>
-                      : k_adam_block_step<WG, UNROLL, 2, false>;
+    case 0: return pick_mode<WG, UNROLL, 0>(mode);
+    case 1: return pick_mode<WG, UNROLL, 1>(mode);
+    case 2: return pick_mode<WG, UNROLL, 2>(mode);
     default: return nullptr;
     }
 }
 
 template <int WG>
-static adam_kernel_t pick_unroll(int unroll_index, int policy, bool l2)
+static adam_kernel_t pick_unroll(int unroll_index, int policy, int mode)
 {
     switch (unroll_index) {
-    case 0: return pick_flags<WG, 1>(policy, l2);
-    case 1: return pick_flags<WG, 2>(policy, l2);
-    case 2: return pick_flags<WG, 4>(policy, l2);
+    case 0: return pick_policy<WG, 1>(policy, mode);
+    case 1: return pick_policy<WG, 2>(policy, mode);
     default: return nullptr;
     }
 }
 
-// variant bits: [1:0] workgroup size index (64, 128, 256, 512 lanes), [3:2] unroll index (1, 2, 4
+// variant bits: [1:0] workgroup size index (64, 128, 256 lanes), [3:2] unroll index (1 or 2
 // vectors per lane per tile), [5:4] cache policy (0 default, 1 nontemporal, 2 nontemporal loads
 // with write-through streaming stores).
 bool adam_variant_valid(int variant)
 {
-    return variant >= 0 && variant < 64 && ((variant >> 2) & 3) < 3 && ((variant >> 4) & 3) < 3;
+    return variant >= 0 && variant < 64 && (variant & 3) < 3 && ((variant >> 2) & 3) < 2 &&
+           ((variant >> 4) & 3) < 3;
 }
 
 hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
-                                  void *p16, uint64_t n, const StepScalars &s, bool l2,
+                                  void *p16, uint64_t n, const StepScalars &s, int mode,
                                   const uint32_t *flag, const float *inv_override,
                                   const AdamLaunch &cfg, int cus, hipStream_t stream)
 {
@@ -487,10 +515,9 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
     const int wg = 64 << wg_index, unroll = 1 << unroll_index;
     adam_kernel_t kernel = nullptr;
     switch (wg_index) {
-    case 0: kernel = pick_unroll<64>(unroll_index, policy, l2); break;
-    case 1: kernel = pick_unroll<128>(unroll_index, policy, l2); break;
-    case 2: kernel = pick_unroll<256>(unroll_index, policy, l2); break;
-    default: kernel = pick_unroll<512>(unroll_index, policy, l2); break;
+    case 0: kernel = pick_unroll<64>(unroll_index, policy, mode); break;
+    case 1: kernel = pick_unroll<128>(unroll_index, policy, mode); break;
+    default: kernel = pick_unroll<256>(unroll_index, policy, mode); break;
     }
     if (kernel == nullptr) return hipErrorInvalidValue;
 

@@ -135,7 +135,7 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
         blk->param_bf16_out == nullptr || blk->overflow_flag == nullptr)
         return LOHAN_ERR_NULL;
     if (blk->n == 0 || blk->n > h->max_elems) return LOHAN_ERR_ARG;
-    if ((flags & ~(uint32_t)LOHAN_FLAG_L2_MODE) != 0) return LOHAN_ERR_ARG;
+    if ((flags & ~(uint32_t)(LOHAN_FLAG_L2_MODE | LOHAN_FLAG_P16_FP16)) != 0) return LOHAN_ERR_ARG;
     const bool clip = max_norm > 0.0f;
     if (clip && blk->sqnorm == nullptr) return LOHAN_ERR_NULL;
     if (max_norm != max_norm || max_norm < 0.0f) return LOHAN_ERR_ARG;

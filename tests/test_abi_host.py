@@ -89,7 +89,7 @@ def test_step_validation_returns_before_any_launch(lib):
     for name in ("beta1", "beta2"):
         for bad in (1.0, 1.5, -0.1, math.nan):
             assert step_status(lib, **{name: bad}) == 3
-    assert step_status(lib, flags=4) == 3                         # unknown flag bit
+    assert step_status(lib, flags=8) == 3                         # unknown flag bit
     assert step_status(lib, ws=None) == 1
     assert step_status(lib, ws=A + 8) == 2
     assert step_status(lib, ws_bytes=16) == 4                     # LOHAN_ERR_WORKSPACE
@@ -181,7 +181,7 @@ def test_launch_config_knob(lib):
         assert v == -1 and a >= 0 and w >= 0 and r > 0        # -1: variant chosen per call
         lohan.lohan_set_launch_config(0, 0, 0, 0)
         assert lohan.lohan_get_launch_config()[:3] == (0, 0, 0)
-        for bad in (3 << 2, 3 << 4, 1 << 6, 1000):
+        for bad in (3, 2 << 2, 3 << 4, 1 << 6, 1000):
             with pytest.raises(lohan.LohanError):
                 lohan.lohan_set_launch_config(bad, 0, 0, 0)
         for bad in ((0, 100000, 0, 0), (0, 0, 33, 0), (0, 0, 0, 17)):

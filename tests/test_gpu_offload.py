@@ -138,7 +138,7 @@ def test_pipeline_rejects_bad_arguments():
 
         before = b.got()
         for bad in (dict(step=0), dict(beta1=1.0), dict(loss_scale=0.0), dict(max_norm=-1.0),
-                    dict(flags=lohan.LOHAN_FLAG_PRECHECKED), dict(flags=64)):
+                    dict(flags=lohan.LOHAN_FLAG_PRECHECKED), dict(flags=64)):  # prechecked is implied, not accepted
             with pytest.raises(lohan.LohanError) as e:
                 submit(**bad)
             assert e.value.status == 3

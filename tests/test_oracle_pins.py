@@ -163,7 +163,7 @@ def test_matches_exact_rational_arithmetic(oracle, case, l2_mode):
     g[3 * k:3 * k + len(EDGE_F16)] = np.array(EDGE_F16, np.uint16)
     perm = rng.permutation(n)
     g = g[perm].copy()
-    hy = dict(case, l2_mode=l2_mode)
+    hy = dict(case, l2_mode=l2_mode, half_out=(case["step"] % 2 == 1))
     flag, p2, m2, v2, h = run_oracle(oracle, p, m, v, g, **hy)
     assert flag == 0
     ep, em, ev, eh = exact.adam_block_step_exact(
@@ -333,6 +333,43 @@ def test_bf16_encode_against_library(oracle):
     assert np.array_equal(got[finite_or_inf], t[finite_or_inf])
     nan_out = got[~finite_or_inf]
     assert np.all((nan_out & 0x7F80) == 0x7F80) and np.all((nan_out & 0x007F) != 0)
+
+
+def test_fp16_encode_against_library(oracle):
+    """The optional binary16 working copy: random bit patterns, the half range, ties, the
+    overflow threshold (65520), the subnormal range and its rounding-to-zero threshold (2^-25)
+    against numpy's float16 conversion."""
+    rng = np.random.default_rng(13)
+    raw = rng.integers(0, 2 ** 32, size=20000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    mid = (rng.standard_normal(20000) * 1e-2).astype(np.float32)
+    tiny = (rng.standard_normal(20000) * 3e-7).astype(np.float32)
+    halves = np.arange(0, 0x7C00, 7, dtype=np.uint32).astype(np.uint16).view(np.float16).astype(np.float32)
+    ties = (halves.view(np.uint32) | 0x1000).view(np.float32)             # exactly between halves
+    edge = np.array([65504, 65519.996, 65520, 65535, 65536, 1e30, -65520, 2.0 ** -14,
+                     2.0 ** -14 - 2.0 ** -26, 2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * 1.0000001,
+                     1.5 * 2.0 ** -24, 2.5 * 2.0 ** -24, 0.0, -0.0, np.inf, -np.inf], np.float32)
+    x = np.concatenate([raw, mid, tiny, halves, ties, np.nextafter(ties, np.float32(0)),
+                        np.nextafter(ties, np.float32(1e9)), edge, -ties])
+    x = x[~np.isnan(x)]
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.float_to_half_bits(v) for v in x], np.uint16)
+    assert np.array_equal(got, want)
+    assert (oracle.float_to_half_bits(np.float32(np.nan)) & 0x7FFF) > 0x7C00
+
+
+def test_fp16_copy_option_only_changes_the_copy(oracle):
+    n = 5000
+    p, m, v, g = rand_block(n, 41)
+    p[:8] = np.array([70000.0, -70000.0, 65519.0, 65520.0, 1e-7, -3e-8, 2.0 ** -25, 0.0], np.float32)
+    hy = dict(HY, step=100, loss_scale=65536.0)
+    a = run_oracle(oracle, p, m, v, g, **hy)
+    b = run_oracle(oracle, p, m, v, g, half_out=True, **hy)
+    for x, y in zip(a[1:4], b[1:4]):
+        assert np.array_equal(bits32(x), bits32(y))
+    with np.errstate(over="ignore"):
+        assert np.array_equal(b[4], b[1].astype(np.float16).view(np.uint16))
+    assert not np.array_equal(a[4], b[4])
 
 
 # ------------------------------------------------------------------------------ overflow / skip
