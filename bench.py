@@ -40,7 +40,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="gpt13b",
-                    choices=["gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b"])
+                    choices=["gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b", "shapes"])
     ap.add_argument("--variant", type=int, default=None, help="kernel launch-shape override")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -305,6 +305,69 @@ def bench_offload(args, torch, lohan, synth):
     }
 
 
+def bench_shapes(args, torch, lohan, synth):
+    """Size-versus-bandwidth curve over the block shapes of the paper's evaluation models
+    (Table IV GPT-style, Table VI DiT): one block of each shape through the same two calls."""
+    dev = "cuda:0"
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    sqnorm = torch.zeros(1, dtype=torch.float64, device=dev)
+    ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+    rows = []
+    for wl in synth.shape_workloads():
+        block = synth.make_block(wl, seed=0, device=dev)
+        n = wl.n
+        hy = wl.hyper()
+        reps = max(3, min(args.steps, int(2e10 // n)))
+
+        def one_step(t, ev=None):
+            lohan.lohan_grad_sqnorm(block["g"], n, wl.loss_scale, sqnorm, flag, ws)
+            if ev is not None:
+                ev[0].record()
+            lohan.lohan_adam_block_step(block["p"], block["m"], block["v"], block["g"],
+                                        block["p16"], n, hy["lr"], hy["beta1"], hy["beta2"],
+                                        hy["eps"], hy["weight_decay"], t, hy["loss_scale"], flag,
+                                        lohan.LOHAN_FLAG_PRECHECKED, None)
+            if ev is not None:
+                ev[1].record()
+
+        for w in range(2):
+            one_step(hy["step"] + w)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(reps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(reps):
+            one_step(hy["step"] + 2 + k, evs[k])
+        torch.cuda.synchronize()
+        step_s = (time.perf_counter() - t0) / reps
+        adam_ms = sum(a.elapsed_time(b) for a, b in evs) / reps
+        assert int(flag.cpu().item()) == 0
+        rows.append({"shape": wl.name, "elements": n, "resident_gb": 16 * n / 1e9,
+                     "ms_per_step": step_s * 1e3, "elements_per_s": n / step_s,
+                     "adam_kernel_ms": adam_ms,
+                     "adam_kernel_gbps": ADAM_BYTES_PER_ELEM * n / adam_ms / 1e6,
+                     "adam_kernel_frac_of_peak": ADAM_BYTES_PER_ELEM * n / adam_ms / 1e6 /
+                                                 HBM_PEAK_GBPS})
+        del block
+        torch.cuda.empty_cache()
+    total = sum(r["elements"] for r in rows)
+    total_s = sum(r["ms_per_step"] for r in rows) / 1e3
+    worst = min(rows, key=lambda r: r["adam_kernel_frac_of_peak"])
+    return {
+        "metric": "adam_updated_elements_per_sec", "value": total / total_s,
+        "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": 2,
+        "ms_per_step": total_s * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "shapes: one block of every Table IV (12*h^2) and Table VI "
+                               "(18*h^2) model shape", "elements": total},
+        "roofline": {"kernel": "k_adam_block_step", "bound": "hbm",
+                     "achieved": worst["adam_kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": worst["adam_kernel_frac_of_peak"], "traffic": None,
+                     "note": f"worst shape of the sweep ({worst['shape']})"},
+        "shapes": rows, "cpu_baseline": None,
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -331,6 +394,8 @@ def main():
         out = bench_stream(args, torch, lohan, synth)
     elif args.workload == "offload13b":
         out = bench_offload(args, torch, lohan, synth)
+    elif args.workload == "shapes":
+        out = bench_shapes(args, torch, lohan, synth)
     else:
         out = bench_block(args, torch, lohan, synth)
     print(json.dumps(out))

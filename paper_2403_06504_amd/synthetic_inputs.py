@@ -50,6 +50,26 @@ WORKLOADS = {
     "gpt13b_ragged": Workload("gpt13b_ragged", 12 * 5120 ** 2 + 1, 100, 65536.0, False),
 }
 
+# Block shapes of the paper's evaluation models: (name, layers, hidden size).  A GPT-style
+# decoder block carries 12*h^2 weights (Table IV); a DiT block carries 18*h^2 (attention 4h^2,
+# MLP 8h^2, adaLN modulation 6h^2 -- this reproduces the model sizes of Table VI).
+TABLE_IV_GPT = (("6B", 28, 4096), ("13B", 40, 5120), ("30B", 48, 7168), ("70B", 80, 8192),
+                ("135B", 88, 11264), ("175B", 96, 12288), ("276B", 112, 14336),
+                ("412B", 128, 16384))
+TABLE_VI_DIT = (("0.67B", 28, 1152), ("0.90B", 30, 1280), ("1.4B", 32, 1536), ("10B", 28, 4096),
+                ("20B", 40, 5120), ("40B", 48, 7168))
+
+
+def shape_workloads():
+    """One Workload per evaluation-model block shape, value distributions as gpt13b."""
+    out = []
+    for name, _, h in TABLE_IV_GPT:
+        out.append(Workload(f"gpt{name}_h{h}", 12 * h * h, 100, 65536.0, False))
+    for name, _, h in TABLE_VI_DIT:
+        out.append(Workload(f"dit{name}_h{h}", 18 * h * h, 100, 65536.0, False))
+    return out
+
+
 # fp16 bit patterns with an all-ones exponent: +inf, -inf, quiet NaN, all-ones NaN, signalling NaN
 NONFINITE_FP16 = (0x7C00, 0xFC00, 0x7E00, 0xFFFF, 0x7C01)
 

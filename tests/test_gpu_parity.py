@@ -236,6 +236,33 @@ def test_config4_175b_block_sampled(oracle):
     assert torch.equal(blk.p16.view(torch.int16), blk.p.to(torch.bfloat16).view(torch.int16))
 
 
+def test_every_evaluation_model_block_shape_sampled(oracle):
+    """One block of every model shape the paper evaluates (Table IV: 12*h^2, h = 4096..16384;
+    Table VI DiT: 18*h^2, h = 1152..7168), up to 3.2e9 elements (above 2^31).  Sampled ranges
+    -- head, end, seeded interior -- against the oracle, plus whole-buffer properties."""
+    rng = np.random.default_rng(6)
+    span = 1 << 19
+    for wl in synth.shape_workloads():
+        say(f"[shapes] {wl.name} n={wl.n}")
+        blk = DeviceBlock(synth.make_block(wl, seed=0, device=DEV))
+        starts = [0, wl.n - span] + [int(x) for x in rng.integers(span, wl.n - 2 * span, size=3)]
+        before = {s: blk.host(s, s + span) for s in starts}
+        hy = wl.hyper()
+        assert gpu_steps(blk, hy, 1) == [0]
+        for s in starts:
+            host = before[s]
+            assert oracle_steps(oracle, host, hy, 1, nthreads=8) == [0]
+            worst = assert_state_parity(blk.host(s, s + span), host, what=f"{wl.name} @ {s}")
+            assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
+        assert torch.equal(blk.p16.view(torch.int16), blk.p.to(torch.bfloat16).view(torch.int16))
+        blk.norm(wl.loss_scale)
+        torch.cuda.synchronize()
+        sq = float(blk.sqnorm.cpu().item())
+        assert blk.flag_value() == 0 and abs(sq - wl.n * 1e-6) < 0.01 * wl.n * 1e-6
+        del blk, before
+        torch.cuda.empty_cache()
+
+
 def test_config5_ragged_overflow_skip_and_clipping(oracle):
     """Ragged 13B block (n = 12*5120^2 + 1).  With 0.01 % of the gradients set to inf/NaN the
     flag is 1 and p, m, v, p16 stay bit-identical; without them a clipping run (max-norm 1.0)
