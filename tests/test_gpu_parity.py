@@ -568,3 +568,46 @@ def test_same_input_same_bits():
     for k in ("p", "m", "v", "p16"):
         assert np.array_equal(outs[0][0][k], outs[1][0][k])
     assert outs[0][1] == outs[1][1]
+
+
+def test_step_can_be_captured_in_a_hip_graph(oracle):
+    """The entry points allocate nothing, never synchronise and issue no memsets, so a caller may
+    capture norm + step into a HIP graph and replay it.  Three replays with eager work and
+    synchronisations between them; every replay is checked against the oracle (the step index is
+    baked into the captured launch, so each replay repeats step 100 on the evolving state)."""
+    n = 1_000_003
+    wl = small_workload(n)
+    hy = wl.hyper()
+    blk = DeviceBlock(synth.make_block(wl, seed=8, device=DEV))
+    host = blk.host()
+    # warm-up outside capture (first-use initialisation must not happen while capturing)
+    warm = DeviceBlock(synth.make_block(small_workload(4096), seed=1, device=DEV))
+    warm.norm(wl.loss_scale)
+    warm.step(wl.hyper(), flags=lohan.LOHAN_FLAG_PRECHECKED)
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            blk.norm(wl.loss_scale, stream=side)
+            blk.step(hy, flags=lohan.LOHAN_FLAG_PRECHECKED, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    # capture itself executes nothing
+    assert np.array_equal(blk.host()["p"].view(np.uint32), host["p"].view(np.uint32))
+
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for r in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert oracle_steps(oracle, host, hy, 1, nthreads=8) == [0]
+        worst = assert_state_parity(blk.host(), host, what=f"graph replay {r}")
+        assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
+        want = oracle.grad_sqnorm(host["g"], wl.loss_scale)
+        assert abs(float(blk.sqnorm.cpu().item()) - want) <= RTOL_SQNORM * want
+        scratch.add_(1.0)                       # eager work between replays
+        warm.norm(wl.loss_scale)
+        torch.cuda.synchronize()
+    assert float(scratch[0].cpu()) == 3.0
