@@ -1,0 +1,61 @@
+"""Oracle for the holistic traffic-aware activation swapping planner (Sec. IV-D): the iteration-
+time model of Eq. 1-5 and the greedy search of Algorithm 1, in plain python floats (float64), in
+the paper's notation and step order.  TEST INFRASTRUCTURE; shares nothing with the C++ planner.
+
+Readings where the paper is silent (also listed in the design document):
+  * alpha*A_G2M = A_G2M - MEM_avail (Eq. 3) is clamped at 0: activations only spill to the far tier
+    once main memory is full.
+  * Sizes (A, MEM_avail) are bytes, P is a parameter count (so 2P and 14P are bytes: fp16
+    parameters; fp32 parameters + two moments + fp16 gradients), bandwidths bytes/s, FLOP counts
+    operations, THP_G operations/s.
+  * layer_list is sorted by offloading benefit OB = FLOP_layer / A_layer (Eq. 6), highest first,
+    ties keeping the original order; a layer with A = 0 has infinite benefit.
+  * Algorithm 1 as printed: A_G2M and FLOP_r are advanced before the iteration time is evaluated;
+    a layer whose T_iter does not improve on T_min is still appended while A_G2M < A_interBlock
+    (the floor that avoids running out of GPU memory) and T_min is then left alone; the first
+    non-improving layer at or above the floor ends the search and is not appended.
+"""
+import math
+
+
+def iter_time(hw: dict, a_g2m: float, flop_r: float) -> float:
+    """T_iter = T_f + T_b (Eq. 1) with T_f from Eq. 4 and T_b from Eq. 5."""
+    spill = max(0.0, a_g2m - hw["mem_avail"])                       # Eq. 3, clamped
+    t_f = max(hw["flop_f"] / hw["thp_g"],                           # T_f^G
+              a_g2m / hw["bw_g"],                                   # T_f^G2M
+              2.0 * hw["params"] / hw["bw_g"],                      # T_f^M2G
+              2.0 * hw["params"] / hw["bw_s2m"] + spill / hw["bw_m2s"])   # T_f^S
+    t_b = max((2.0 * hw["flop_f"] + flop_r) / hw["thp_g"],          # T_b^G
+              2.0 * hw["params"] / hw["bw_g"],                      # T_b^G2M
+              (2.0 * hw["params"] + a_g2m) / hw["bw_g"],            # T_b^M2G
+              (14.0 * hw["params"] + spill) / hw["bw_s2m"] + 14.0 * hw["params"] / hw["bw_m2s"])
+    return t_f + t_b
+
+
+def offloading_benefit(flop: float, act_bytes: float) -> float:
+    """OB_layer = FLOP_layer / A_layer (Eq. 6)."""
+    return math.inf if act_bytes == 0 else flop / act_bytes
+
+
+def plan(layers, hw: dict):
+    """Algorithm 1.  layers: list of (flop, act_bytes).  Returns (swap_list as indices into
+    `layers` in swapping order, A_G2M of the swap list, FLOP_r, T_iter of the swap list)."""
+    order = sorted(range(len(layers)), key=lambda i: -offloading_benefit(*layers[i]))
+    swap_list = []
+    t_min = math.inf
+    a_g2m = 0.0
+    flop_r = hw["flop_f"]                                           # full recomputation
+    for i in order:
+        flop, act = layers[i]
+        a_g2m += act
+        flop_r -= flop
+        t_iter = iter_time(hw, a_g2m, flop_r)
+        if t_iter >= t_min:
+            if a_g2m >= hw["a_interblock"]:
+                break
+        else:
+            t_min = t_iter
+        swap_list.append(i)
+    a_sw = sum(layers[i][1] for i in swap_list)
+    f_r = hw["flop_f"] - sum(layers[i][0] for i in swap_list)
+    return swap_list, a_sw, f_r, iter_time(hw, a_sw, f_r)

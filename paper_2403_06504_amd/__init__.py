@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     lohan_offload_slab_bytes,
     lohan_offload_submit,
     lohan_offload_wait_last_step,
+    lohan_plan_activation_swapping,
+    lohan_swap_iter_time,
     LOHAN_FLAG_L2_MODE,
     LOHAN_FLAG_P16_FP16,
     LOHAN_FLAG_PRECHECKED,

@@ -26,10 +26,22 @@ EXPORTS = (
     "lohan_set_launch_config", "lohan_get_launch_config",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
     "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
+    "lohan_swap_iter_time", "lohan_plan_activation_swapping",
 )
 
 LOHAN_OFFLOAD_SERIALIZED = 0
 LOHAN_OFFLOAD_OVERLAPPED = 1
+
+
+class LohanLayer(ctypes.Structure):
+    """Mirror of lohan_layer_t."""
+    _fields_ = [("flop", ctypes.c_double), ("act_bytes", ctypes.c_double)]
+
+
+class LohanSwapHw(ctypes.Structure):
+    """Mirror of lohan_swap_hw_t."""
+    _fields_ = [(k, ctypes.c_double) for k in ("thp_g", "bw_g", "bw_s2m", "bw_m2s", "params",
+                                               "mem_avail", "flop_f", "a_interblock")]
 
 
 class LohanOffloadBlock(ctypes.Structure):
@@ -98,6 +110,14 @@ def load_library():
     lib.lohan_offload_drain.restype = ctypes.c_int
     lib.lohan_offload_destroy.argtypes = [vp]
     lib.lohan_offload_destroy.restype = ctypes.c_int
+    lib.lohan_swap_iter_time.argtypes = [ctypes.POINTER(LohanSwapHw), ctypes.c_double,
+                                         ctypes.c_double]
+    lib.lohan_swap_iter_time.restype = ctypes.c_double
+    lib.lohan_plan_activation_swapping.argtypes = [
+        ctypes.POINTER(LohanLayer), sz, ctypes.POINTER(LohanSwapHw),
+        ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_double),
+        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.lohan_plan_activation_swapping.restype = ctypes.c_int
     _LIB = lib
     return lib
 
@@ -267,3 +287,26 @@ def lohan_offload_drain(handle):
 
 def lohan_offload_destroy(handle):
     _check(load_library().lohan_offload_destroy(handle))
+
+
+def _swap_hw(hw: dict) -> LohanSwapHw:
+    return LohanSwapHw(*[float(hw[k]) for k, _ in LohanSwapHw._fields_])
+
+
+def lohan_swap_iter_time(hw: dict, a_g2m, flop_r) -> float:
+    h = _swap_hw(hw)
+    return float(load_library().lohan_swap_iter_time(ctypes.byref(h), float(a_g2m), float(flop_r)))
+
+
+def lohan_plan_activation_swapping(layers, hw: dict):
+    """layers: sequence of (flop, act_bytes).  Returns (swap_list, a_g2m, flop_r, t_iter)."""
+    n = len(layers)
+    arr = (LohanLayer * max(n, 1))(*[LohanLayer(float(f), float(a)) for f, a in layers])
+    out = (ctypes.c_uint32 * max(n, 1))()
+    count = ctypes.c_size_t()
+    a, f, t = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    h = _swap_hw(hw)
+    _check(load_library().lohan_plan_activation_swapping(
+        arr, n, ctypes.byref(h), out, ctypes.byref(count), ctypes.byref(a), ctypes.byref(f),
+        ctypes.byref(t)))
+    return [int(out[i]) for i in range(count.value)], a.value, f.value, t.value

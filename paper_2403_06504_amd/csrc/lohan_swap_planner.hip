@@ -1,0 +1,99 @@
+// Holistic traffic-aware activation swapping planner (Sec. IV-D): iteration-time model of
+// Eq. 1-5 and the greedy search of Algorithm 1.  Host code only; see include/lohan_swap_planner.h.
+
+#include <algorithm>
+#include <cmath>
+#include <limits>
+#include <numeric>
+#include <vector>
+
+#include "lohan_swap_planner.h"
+
+namespace {
+
+bool rates_ok(const lohan_swap_hw_t *hw)
+{
+    return hw != nullptr && hw->thp_g > 0.0 && hw->bw_g > 0.0 && hw->bw_s2m > 0.0 &&
+           hw->bw_m2s > 0.0 && std::isfinite(hw->thp_g) && std::isfinite(hw->bw_g) &&
+           std::isfinite(hw->bw_s2m) && std::isfinite(hw->bw_m2s);
+}
+
+bool nonneg_finite(double x) { return std::isfinite(x) && x >= 0.0; }
+
+// T_f (Eq. 4) + T_b (Eq. 5); each stage is as long as its slowest resource.
+double iter_time(const lohan_swap_hw_t &hw, double a_g2m, double flop_r)
+{
+    const double spill = std::max(0.0, a_g2m - hw.mem_avail);          // Eq. 3
+    const double p2 = 2.0 * hw.params, p14 = 14.0 * hw.params;
+    const double t_f = std::max(std::max(hw.flop_f / hw.thp_g, a_g2m / hw.bw_g),
+                                std::max(p2 / hw.bw_g, p2 / hw.bw_s2m + spill / hw.bw_m2s));
+    const double t_b = std::max(std::max((2.0 * hw.flop_f + flop_r) / hw.thp_g, p2 / hw.bw_g),
+                                std::max((p2 + a_g2m) / hw.bw_g,
+                                         (p14 + spill) / hw.bw_s2m + p14 / hw.bw_m2s));
+    return t_f + t_b;
+}
+
+}  // namespace
+
+extern "C" {
+
+double lohan_swap_iter_time(const lohan_swap_hw_t *hw, double a_g2m, double flop_r)
+{
+    if (!rates_ok(hw)) return std::numeric_limits<double>::quiet_NaN();
+    return iter_time(*hw, a_g2m, flop_r);
+}
+
+lohan_status_t lohan_plan_activation_swapping(const lohan_layer_t *layers, size_t n,
+                                              const lohan_swap_hw_t *hw, uint32_t *swap_list,
+                                              size_t *n_swapped, double *a_g2m, double *flop_r,
+                                              double *t_iter)
+{
+    if (hw == nullptr || n_swapped == nullptr || a_g2m == nullptr || flop_r == nullptr ||
+        t_iter == nullptr || (n != 0 && (layers == nullptr || swap_list == nullptr)))
+        return LOHAN_ERR_NULL;
+    if (!rates_ok(hw) || !nonneg_finite(hw->params) || !nonneg_finite(hw->mem_avail) ||
+        !nonneg_finite(hw->flop_f) || !nonneg_finite(hw->a_interblock) || n > 0xFFFFFFFFull)
+        return LOHAN_ERR_ARG;
+    for (size_t i = 0; i < n; ++i)
+        if (!nonneg_finite(layers[i].flop) || !nonneg_finite(layers[i].act_bytes))
+            return LOHAN_ERR_ARG;
+
+    // layer_list.sortByOffloadingBenefit(): OB = FLOP/A (Eq. 6), highest first, stable.
+    std::vector<uint32_t> order(n);
+    std::iota(order.begin(), order.end(), 0u);
+    auto benefit = [&](uint32_t i) {
+        return layers[i].act_bytes == 0.0 ? std::numeric_limits<double>::infinity()
+                                          : layers[i].flop / layers[i].act_bytes;
+    };
+    std::stable_sort(order.begin(), order.end(),
+                     [&](uint32_t a, uint32_t b) { return benefit(a) > benefit(b); });
+
+    size_t count = 0;
+    double t_min = std::numeric_limits<double>::infinity();
+    double a_run = 0.0;
+    double f_run = hw->flop_f;                                  // full recomputation
+    for (uint32_t idx : order) {
+        a_run += layers[idx].act_bytes;
+        f_run -= layers[idx].flop;
+        const double t = iter_time(*hw, a_run, f_run);
+        if (t >= t_min) {
+            if (a_run >= hw->a_interblock) break;               // past the out-of-memory floor
+        } else {
+            t_min = t;
+        }
+        swap_list[count++] = idx;
+    }
+    // Describe the list that is returned (the layer that ended the search is not part of it).
+    double a_sw = 0.0, f_sw = 0.0;
+    for (size_t k = 0; k < count; ++k) {
+        a_sw += layers[swap_list[k]].act_bytes;
+        f_sw += layers[swap_list[k]].flop;
+    }
+    *n_swapped = count;
+    *a_g2m = a_sw;
+    *flop_r = hw->flop_f - f_sw;
+    *t_iter = iter_time(*hw, a_sw, hw->flop_f - f_sw);
+    return LOHAN_OK;
+}
+
+}  // extern "C"

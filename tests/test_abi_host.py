@@ -14,7 +14,8 @@ import paper_2403_06504_amd as lohan
 from paper_2403_06504_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "lohan_adam.h")
+HEADERS = [os.path.join(ROOT, "include", "lohan_adam.h"),
+           os.path.join(ROOT, "include", "lohan_swap_planner.h")]
 
 
 @pytest.fixture(scope="module")
@@ -26,7 +27,7 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(lohan_[a-z_0-9]+)\s*\(", text)))
 
