@@ -52,7 +52,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(block, wl, sample_elems=1 << 26):
+def cpu_baseline(block, wl, sample_elems=1 << 27):
     """Time the CPU oracle, as it stands, on the first `sample_elems` elements of the same block
     (copied to the host before the timed GPU region)."""
     import numpy as np
@@ -77,7 +77,7 @@ def cpu_baseline(block, wl, sample_elems=1 << 26):
         return best
 
     t_multi = time_step(threads, 5)
-    t_single = time_step(1, 2)
+    t_single = time_step(1, 3)
     t0 = time.perf_counter()
     oracle.grad_sqnorm(host["g"], wl.loss_scale)
     t_norm = time.perf_counter() - t0
@@ -135,7 +135,8 @@ def bench_block(args, torch, lohan, synth):
     elapsed = time.perf_counter() - t0
 
     assert int(flag.cpu().item()) == 0, "synthetic gradients must not overflow"
-    adam_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    adam_all = sorted(e[0].elapsed_time(e[1]) for e in events)
+    adam_ms = sum(adam_all) / args.steps
     reduce_ms = sum(e[2].elapsed_time(e[0]) for e in events) / args.steps
     ms_per_step = elapsed * 1e3 / args.steps
     achieved = ADAM_BYTES_PER_ELEM * n / (adam_ms * 1e-3) / 1e9
@@ -157,6 +158,8 @@ def bench_block(args, torch, lohan, synth):
         "roofline": {"kernel": "k_adam_block_step", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "avg_launch_ms": adam_ms,
+                     "median_launch_ms": adam_all[len(adam_all) // 2],
+                     "min_launch_ms": adam_all[0],
                      "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
         "reduce_kernel": {"kernel": "k_grad_reduce+k_grad_finalize", "avg_ms": reduce_ms,
                           "achieved_gbps": REDUCE_BYTES_PER_ELEM * n / (reduce_ms * 1e-3) / 1e9},
@@ -187,9 +190,10 @@ def bench_stream(args, torch, lohan, synth):
         for _ in range(nblocks):
             torch.matmul(a, b)
 
-    def one_pass(t):
+    def one_pass(t, gemm=True):
         for i in reversed(range(nblocks)):
-            torch.matmul(a, b)
+            if gemm:
+                torch.matmul(a, b)
             ev = torch.cuda.Event()
             ev.record(main)
             s = side[i % 2]
@@ -214,7 +218,12 @@ def bench_stream(args, torch, lohan, synth):
     gemm_s = (time.perf_counter() - t0) / args.steps
     t0 = time.perf_counter()
     for k in range(args.steps):
-        one_pass(hy["step"] + args.warmup + k)
+        one_pass(hy["step"] + args.warmup + k, gemm=False)
+    torch.cuda.synchronize()
+    steps_only_s = (time.perf_counter() - t0) / args.steps
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_pass(hy["step"] + args.warmup + args.steps + k)
     torch.cuda.synchronize()
     elapsed = (time.perf_counter() - t0) / args.steps
     assert all(int(f.cpu().item()) == 0 for f in flags)
@@ -228,7 +237,9 @@ def bench_stream(args, torch, lohan, synth):
                                "GEMM 2048x5120x20480 per block on the main stream",
                    "elements": total, "blocks": nblocks},
         "step_hbm_gbps": 30 * total / elapsed / 1e9,
-        "gemm_only_ms": gemm_s * 1e3,
+        "ms_per_block": elapsed * 1e3 / nblocks,
+        "gemm_only_ms": gemm_s * 1e3, "steps_only_ms": steps_only_s * 1e3,
+        "pass_over_sum_of_parts": elapsed / (gemm_s + steps_only_s),
         "roofline": {"kernel": "k_adam_block_step", "bound": "hbm",
                      "achieved": 28 * total / elapsed / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": 28 * total / elapsed / 1e9 / HBM_PEAK_GBPS,
