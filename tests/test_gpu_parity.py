@@ -263,6 +263,42 @@ def test_every_evaluation_model_block_shape_sampled(oracle):
         torch.cuda.empty_cache()
 
 
+def test_element_count_beyond_32_bits(oracle):
+    """n = 2^32 + 4099 elements (68.7 GB resident, ragged): every index, offset and trip count
+    in the kernels must be 64-bit.  Sampled ranges around the 2^32-element boundary, at the
+    ragged end and at the head; a non-finite gradient in the very last element must raise the
+    flag and skip the step."""
+    n = (1 << 32) + 4099
+    wl = small_workload(n)
+    say(f"[2^32] n={n} generating")
+    blk = DeviceBlock(synth.make_block(wl, seed=0, device=DEV))
+    span = 1 << 19
+    starts = [0, (1 << 32) - span // 2, (1 << 32) - 3, n - span, (1 << 31) - 7, 3 * (1 << 30) + 11]
+    before = {s: blk.host(s, min(n, s + span)) for s in starts}
+    hy = wl.hyper()
+    blk.g.view(torch.int16)[n - 1] = 0x7C00                   # +inf in the last element
+    p_tail = blk.p[n - 8:].clone()
+    assert gpu_steps(blk, hy, 1) == [1]
+    assert torch.equal(blk.p[n - 8:].view(torch.int32), p_tail.view(torch.int32))
+    assert torch.equal(blk.p[:span].view(torch.int32),
+                       torch.from_numpy(before[0]["p"]).to(DEV).view(torch.int32))
+    blk.g.view(torch.int16)[n - 1] = int(before[n - span]["g"][-1]) - (
+        0x10000 if before[n - span]["g"][-1] >= 0x8000 else 0)  # restore the original value
+    say("[2^32] step")
+    assert gpu_steps(blk, hy, 1) == [0]
+    for s in starts:
+        host = before[s]
+        assert oracle_steps(oracle, host, hy, 1, nthreads=8) == [0]
+        worst = assert_state_parity(blk.host(s, min(n, s + span)), host, what=f"2^32 range {s}")
+        assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
+    blk.norm(wl.loss_scale)
+    torch.cuda.synchronize()
+    sq = float(blk.sqnorm.cpu().item())
+    assert blk.flag_value() == 0 and abs(sq - n * 1e-6) < 0.01 * n * 1e-6
+    # nothing left unwritten anywhere: the sentinel of the bf16 buffer is gone
+    assert torch.equal(blk.p16.view(torch.int16), blk.p.to(torch.bfloat16).view(torch.int16))
+
+
 def test_config5_ragged_overflow_skip_and_clipping(oracle):
     """Ragged 13B block (n = 12*5120^2 + 1).  With 0.01 % of the gradients set to inf/NaN the
     flag is 1 and p, m, v, p16 stay bit-identical; without them a clipping run (max-norm 1.0)
