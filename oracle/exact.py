@@ -4,7 +4,7 @@ Every fp32 operation of the step is carried out on python Fractions (infinitely 
 rounded to the nearest fp32 value, ties to even, with gradual underflow -- i.e. IEEE-754 binary32
 arithmetic built from its definition rather than from a floating-point unit.  It follows the same
 reading of the update as lohan_oracle.c (Sec. IV-C "CPU Compute" step; Table II tensors; Adam per
-Sec. II; all numerical conventions from the design document) but shares no code with it, so that
+Sec. II; the numerical conventions are restated in the code below) but shares no code with it, so that
 agreement between the two pins the C file's conversions, rounding and compiler flags.
 
 Only finite values are supported (an overflow to infinity raises); pure-python loops, so keep

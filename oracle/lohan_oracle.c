@@ -15,7 +15,7 @@
  *     hence P16 is always the rounding of the P32 written by the same step.
  * The paper never writes the update down.  Everything else (loss-scale unscale, inf/nan skip,
  * AdamW decoupled decay, eps outside the square root after bias correction, bf16 round-to-nearest-
- * even, operation order) is the reading listed in the design document, restated here step by step.
+ * even, operation order) is a reading of the paper, stated here step by step where it is used.
  *
  * Precision: the state is fp32 by Table II and the parity bar is in fp32 ulps after ten chained
  * steps, so the step is evaluated in fp32, one IEEE-754 operation at a time, each rounded to

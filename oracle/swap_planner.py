@@ -2,7 +2,7 @@
 time model of Eq. 1-5 and the greedy search of Algorithm 1, in plain python floats (float64), in
 the paper's notation and step order.  TEST INFRASTRUCTURE; shares nothing with the C++ planner.
 
-Readings where the paper is silent (also listed in the design document):
+Readings where the paper is silent:
   * alpha*A_G2M = A_G2M - MEM_avail (Eq. 3) is clamped at 0: activations only spill to the far tier
     once main memory is full.
   * Sizes (A, MEM_avail) are bytes, P is a parameter count (so 2P and 14P are bytes: fp16
