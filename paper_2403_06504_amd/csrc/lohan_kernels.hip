@@ -3,10 +3,13 @@
 // The step is the "CPU Compute" box of LoHan's active gradient offloading (Sec. IV-C): update the
 // model states of block i (P32 and the two OS32 moments of Table II) from its G16 gradients and
 // emit the P16 working copy, here moved from the host into HBM.  It is an elementwise stream of
-// 28 bytes per element with ~1 flop/byte, so there is no MFMA anywhere: what matters is that every
-// global access of a wavefront is one contiguous run (128-bit per lane for fp32 streams, 64-bit
-// per lane for the two 16-bit streams), that enough independent loads are in flight per lane, and
-// that the grid is sized to the CU count.
+// 28 bytes per element with ~1 flop/byte, so there is no MFMA anywhere.  What decides the
+// bandwidth on MI355X (all measured): every global access of a wavefront is one contiguous run
+// (128-bit per lane for the fp32 streams, 64-bit per lane for the two 16-bit streams); the grid is
+// one small tile per workgroup, handed out by the hardware dispatcher in address order, so the
+// tiles in flight form a compact sliding window; the number of wavefronts resident per CU is
+// bounded well below the hardware limit (more bytes in flight make a mixed read/write HBM stream
+// slower); and loads and stores carry streaming cache policies.
 //
 // Arithmetic contract (must match lohan_adam.h): fp32, one rounding per operation, no contraction
 // -- this file is compiled with -ffp-contract=off and with correctly rounded fp32 divide / sqrt
