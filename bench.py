@@ -31,7 +31,7 @@ REDUCE_BYTES_PER_ELEM = 2       # one read of g16
 # HBM bytes per k_adam_block_step launch measured with two rocprofv3 --pmc runs of this script
 # (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy:
 # factor 2.000 and 1.000 on gfx950).  Summary: profiles/k_adam_block_step_gpt13b_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"gpt13b": 8601651 * 1024,      # profiles/..._gpt13b_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {"gpt13b": 8601691 * 1024,      # profiles/..._gpt13b_hbm_traffic.md
                           "gpt175b": 49545515 * 1024}    # profiles/..._gpt175b_trace_and_traffic.md
 
 

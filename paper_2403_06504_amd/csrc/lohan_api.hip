@@ -26,7 +26,7 @@ constexpr int kCacheResidentVariant = 0 | (0 << 2) | (0 << 4);
 constexpr uint64_t kCacheResidentBytes = 256ull << 20;
 constexpr int kDefaultAdamWgsPerCu = 0;                       // one tile per workgroup
 constexpr int kDefaultAdamWavesPerCu = 11;                    // occupancy throttle
-constexpr int kDefaultReduceWgsPerCu = 2;
+constexpr int kDefaultReduceWgsPerCu = 4;
 std::atomic<int> g_adam_variant{kAutoAdamVariant};
 std::atomic<int> g_adam_wgs_per_cu{kDefaultAdamWgsPerCu};
 std::atomic<int> g_adam_waves_per_cu{kDefaultAdamWavesPerCu};
