@@ -117,6 +117,9 @@ lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_s
  *   overflow_flag  device, in/out: one uint32 (written by pass 1, or read-only when prechecked)
  *   flags       OR of LOHAN_FLAG_*; unknown bits -> LOHAN_ERR_ARG
  * Moves 28 bytes per element (14 read, 14 written), plus 2 read by pass 1 when it runs.
+ * "device" above means device-accessible: pinned host memory (hipHostMalloc or equivalent) is
+ * accepted for any of the arrays, and the kernel then reads and writes it over the host link
+ * (the zero-copy form of the offloaded step of Sec. IV-C; no staging buffer is needed).
  */
 lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *exp_avg_sq,
                                      const void *grad_fp16, void *param_bf16_out, uint64_t n,

@@ -151,3 +151,32 @@ def test_pipeline_rejects_bad_arguments():
             assert np.array_equal(before[k], after[k])  # rejected calls enqueue nothing
     finally:
         lohan.lohan_offload_destroy(h)
+
+
+def test_step_runs_directly_on_pinned_host_state(oracle):
+    """Pinned host memory is device-accessible, so the unchanged entry points also work with the
+    fp32 state left in host memory (every access then crosses PCIe): same bits as the oracle,
+    and an overflowing block leaves the host state untouched."""
+    for i, n in enumerate((1_000_003, 65_536, 17)):
+        for overflow in (False, True):
+            b = HostBlock(n, seed=40 + i, overflow=overflow)
+            ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=DEV)
+            hy = b.hy
+            before = {k: b.oracle_state[k].copy() for k in ("p", "m", "v", "p16")}
+            for k in range(2):
+                lohan.lohan_adam_block_step(b.p, b.m, b.v, b.g, b.p16, n, hy["lr"], hy["beta1"],
+                                            hy["beta2"], hy["eps"], hy["weight_decay"],
+                                            hy["step"] + k, hy["loss_scale"], b.flag, 0, ws)
+            torch.cuda.synchronize()
+            st = b.oracle_state
+            flags = [oracle.adam_block_step(st["p"], st["m"], st["v"], st["g"], st["p16"],
+                                            nthreads=4, **dict(hy, step=hy["step"] + k))
+                     for k in range(2)]
+            assert int(b.flag.cpu().item()) == flags[-1] == int(overflow)
+            got = b.got()
+            if overflow:
+                for k in ("p", "m", "v", "p16"):
+                    assert np.array_equal(got[k].view(np.uint8), before[k].view(np.uint8)), k
+            else:
+                worst = assert_state_parity(got, st, what=f"pinned host state n={n}")
+                assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
