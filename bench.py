@@ -9,7 +9,11 @@ Adam-updated elements per second; the roofline object prices the dominant kernel
 (k_adam_block_step, 28 algorithmic bytes per element) against the 8 TB/s HBM peak using HIP events
 recorded on the launch stream inside the timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt13b|gpt175b|gpt_h768|stream13b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt13b|gpt175b|gpt_h768|
+                     stream13b|offload13b|shapes|gpt13b_oop|gpt175b_oop]
+
+The *_oop workloads time lohan_adam_block_step_out_of_place instead: the overflow test fused into
+a single 28 B/element pass between two sets of state (not the default: it doubles the state).
 
 Prints ONE JSON line.  There is no multi-GPU path: the step is elementwise and would shard by
 contiguous element ranges, but this build runs on one GPU only.
@@ -41,9 +45,12 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="gpt13b",
-                    choices=["gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b", "shapes"])
+                    choices=["gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b", "shapes",
+                             "gpt13b_oop", "gpt175b_oop"])
     ap.add_argument("--variant", type=int, default=None, help="kernel launch-shape override")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
+    ap.add_argument("--waves-per-cu", type=int, default=-1,
+                    help="occupancy throttle override (0 = none, -1 = built-in default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks", type=int, default=None,
                     help="stream13b: number of blocks (default 40); offload13b: default 6")
@@ -167,6 +174,62 @@ def bench_block(args, torch, lohan, synth):
         "cpu_baseline": base,
     }
     return out
+
+
+def bench_block_oop(args, torch, lohan, synth):
+    """One call of the out-of-place step per "step"; the two state sets swap roles every step, as
+    a caller does after reading flag == 0."""
+    wl = synth.WORKLOADS[args.workload[:-len("_oop")]]
+    dev = "cuda:0"
+    block = synth.make_block(wl, seed=0, device=dev)
+    n = wl.n
+    sets = [{k: block[k] for k in ("p", "m", "v", "p16")},
+            {k: torch.empty_like(block[k]) for k in ("p", "m", "v", "p16")}]
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    hy = wl.hyper()
+
+    def one_step(k, t):
+        a, b = sets[k & 1], sets[(k & 1) ^ 1]
+        lohan.lohan_adam_block_step_out_of_place(
+            a["p"], a["m"], a["v"], block["g"], b["p"], b["m"], b["v"], b["p16"], n, hy["lr"],
+            hy["beta1"], hy["beta2"], hy["eps"], hy["weight_decay"], t, hy["loss_scale"], flag, 0)
+
+    for w in range(args.warmup):
+        one_step(w, hy["step"] + w)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        events[k][0].record()
+        one_step(args.warmup + k, hy["step"] + args.warmup + k)
+        events[k][1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert int(flag.cpu().item()) == 0, "synthetic gradients must not overflow"
+    all_ms = sorted(e[0].elapsed_time(e[1]) for e in events)
+    call_ms = sum(all_ms) / args.steps
+    achieved = ADAM_BYTES_PER_ELEM * n / (call_ms * 1e-3) / 1e9
+    return {
+        "metric": "adam_updated_elements_per_sec",
+        "value": n / (elapsed / args.steps), "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}, out-of-place step with the overflow test fused in: "
+                               f"n={n} elements, two sets of fp32 p/m/v and of the bf16 copy",
+                   "elements": n, "bytes_per_element_step": 28,
+                   "launch_config": list(lohan.lohan_get_launch_config())},
+        "step_hbm_gbps": ADAM_BYTES_PER_ELEM * n / (elapsed / args.steps) / 1e9,
+        "roofline": {"kernel": "k_adam_block_step_oop (events also span the one-lane flag clear)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "avg_launch_ms": call_ms, "median_launch_ms": all_ms[len(all_ms) // 2],
+                     "min_launch_ms": all_ms[0],
+                     "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
+        "cpu_baseline": None,
+    }
 
 
 def bench_stream(args, torch, lohan, synth):
@@ -420,17 +483,17 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     lohan.load_library()
-    if args.variant is not None:
-        lohan.lohan_set_launch_config(args.variant, args.wgs_per_cu, 0)
-    elif args.wgs_per_cu:
-        v, _, _ = lohan.lohan_get_launch_config()
-        lohan.lohan_set_launch_config(v, args.wgs_per_cu, 0)
+    if args.variant is not None or args.wgs_per_cu or args.waves_per_cu >= 0:
+        lohan.lohan_set_launch_config(-1 if args.variant is None else args.variant,
+                                      args.wgs_per_cu, args.waves_per_cu, 0)
     if args.workload == "stream13b":
         out = bench_stream(args, torch, lohan, synth)
     elif args.workload == "offload13b":
         out = bench_offload(args, torch, lohan, synth)
     elif args.workload == "shapes":
         out = bench_shapes(args, torch, lohan, synth)
+    elif args.workload.endswith("_oop"):
+        out = bench_block_oop(args, torch, lohan, synth)
     else:
         out = bench_block(args, torch, lohan, synth)
     print(json.dumps(out))

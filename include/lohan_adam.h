@@ -153,6 +153,37 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
                                              size_t workspace_bytes, hipStream_t stream);
 
 /*
+ * Out-of-place block step with the overflow test fused into the update: ONE pass of 28 bytes per
+ * element instead of the 2-byte flag pass followed by the in-place step (same tensors, same
+ * arithmetic and same skip rule of Sec. IV-C / Table II as lohan_adam_block_step; what changes is
+ * where the results land).  The kernel reads param_fp32_in, exp_avg_in, exp_avg_sq_in and
+ * grad_fp16, writes the updated values to the three *_out arrays and the 16-bit copy, and raises
+ * *overflow_flag if any gradient has an all-ones exponent.  The inputs are never written, so the
+ * skip costs nothing:
+ *     *overflow_flag == 0 : the *_out arrays and param_bf16_out hold the step's results; the
+ *                           caller commits by using them as the next step's inputs (pointer swap)
+ *     *overflow_flag == 1 : the inputs are the block's state, bit-identical; the contents of the
+ *                           *_out arrays and of param_bf16_out are unspecified and to be discarded
+ *                           (so param_bf16_out must not be the only live copy of the old P16)
+ * The price is a second set of the 12 B/element fp32 state (and of the 16-bit copy).  Clipping by
+ * the block's own norm cannot be fused this way (the scale depends on the whole block): use
+ * lohan_grad_sqnorm + lohan_adam_block_step_clipped for that.
+ *   *_in            device, in : n floats each; must not overlap any output
+ *   *_out           device, out: n floats each; each must differ from its input array, else
+ *                   LOHAN_ERR_ARG (other overlaps are undefined)
+ *   overflow_flag   device, out: always written (0 or 1)
+ *   flags           LOHAN_FLAG_L2_MODE and/or LOHAN_FLAG_P16_FP16; LOHAN_FLAG_PRECHECKED ->
+ *                   LOHAN_ERR_ARG (with a known flag the in-place step is the one to call)
+ * No workspace is needed.  n = 0 writes flag = 0 only.  Everything else as lohan_adam_block_step.
+ */
+lohan_status_t lohan_adam_block_step_out_of_place(
+    const float *param_fp32_in, const float *exp_avg_in, const float *exp_avg_sq_in,
+    const void *grad_fp16, float *param_fp32_out, float *exp_avg_out, float *exp_avg_sq_out,
+    void *param_bf16_out, uint64_t n, float lr, float beta1, float beta2, float eps,
+    float weight_decay, int64_t step, float loss_scale, uint32_t *overflow_flag, uint32_t flags,
+    hipStream_t stream);
+
+/*
  * Host-only helper for per-block gradient-norm clipping: returns the loss scale to hand to
  * lohan_adam_block_step so that unscaling and clipping are one multiply,
  *     coef = min(1, max_norm / (sqrt(sqnorm) + 1e-6)),   result = (float)(loss_scale / coef),

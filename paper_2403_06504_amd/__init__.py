@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     load_library,
     lohan_adam_block_step,
     lohan_adam_block_step_clipped,
+    lohan_adam_block_step_out_of_place,
     lohan_clip_loss_scale,
     lohan_get_launch_config,
     lohan_grad_overflow_check,

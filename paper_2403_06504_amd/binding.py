@@ -22,7 +22,7 @@ LOHAN_FLAG_P16_FP16 = 4
 EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
     "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
-    "lohan_clip_loss_scale",
+    "lohan_adam_block_step_out_of_place", "lohan_clip_loss_scale",
     "lohan_set_launch_config", "lohan_get_launch_config",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
     "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
@@ -90,6 +90,10 @@ def load_library():
                                                   f32, ctypes.c_int64, f32, vp, f32, vp,
                                                   ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_block_step_clipped.restype = ctypes.c_int
+    lib.lohan_adam_block_step_out_of_place.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u64, f32,
+                                                       f32, f32, f32, f32, ctypes.c_int64, f32,
+                                                       vp, ctypes.c_uint32, vp]
+    lib.lohan_adam_block_step_out_of_place.restype = ctypes.c_int
     lib.lohan_clip_loss_scale.argtypes = [ctypes.c_double, f32, f32]
     lib.lohan_clip_loss_scale.restype = f32
     lib.lohan_set_launch_config.argtypes = [ctypes.c_int] * 4
@@ -224,6 +228,22 @@ def lohan_adam_block_step_clipped(param_fp32, exp_avg, exp_avg_sq, grad_fp16, pa
         float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
         float(loss_scale), _addr(sqnorm, 1, _F64, "sqnorm"), float(max_norm),
         _addr(overflow_flag, 1, _U32, "overflow_flag"), int(flags), ws, ws_bytes,
+        _stream(stream)))
+
+
+def lohan_adam_block_step_out_of_place(param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16,
+                                       param_fp32_out, exp_avg_out, exp_avg_sq_out,
+                                       param_bf16_out, n, lr, beta1, beta2, eps, weight_decay,
+                                       step, loss_scale, overflow_flag, flags=0, stream=None):
+    _check(load_library().lohan_adam_block_step_out_of_place(
+        _addr(param_fp32_in, n, _F32, "param_fp32_in"), _addr(exp_avg_in, n, _F32, "exp_avg_in"),
+        _addr(exp_avg_sq_in, n, _F32, "exp_avg_sq_in"), _addr(grad_fp16, n, _F16, "grad_fp16"),
+        _addr(param_fp32_out, n, _F32, "param_fp32_out"),
+        _addr(exp_avg_out, n, _F32, "exp_avg_out"),
+        _addr(exp_avg_sq_out, n, _F32, "exp_avg_sq_out"),
+        _addr(param_bf16_out, n, _BF16, "param_bf16_out"), int(n),
+        float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
+        float(loss_scale), _addr(overflow_flag, 1, _U32, "overflow_flag"), int(flags),
         _stream(stream)))
 
 

@@ -247,6 +247,38 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
+lohan_status_t lohan_adam_block_step_out_of_place(
+    const float *param_fp32_in, const float *exp_avg_in, const float *exp_avg_sq_in,
+    const void *grad_fp16, float *param_fp32_out, float *exp_avg_out, float *exp_avg_sq_out,
+    void *param_bf16_out, uint64_t n, float lr, float beta1, float beta2, float eps,
+    float weight_decay, int64_t step, float loss_scale, uint32_t *overflow_flag, uint32_t flags,
+    hipStream_t stream)
+{
+    if ((flags & LOHAN_FLAG_PRECHECKED) != 0) return LOHAN_ERR_ARG;
+    lohan_status_t st = validate_step_args(param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16,
+                                           param_bf16_out, n, lr, beta1, beta2, eps, weight_decay,
+                                           step, loss_scale, overflow_flag, flags);
+    if (st != LOHAN_OK) return st;
+    if (n != 0 &&
+        (param_fp32_out == nullptr || exp_avg_out == nullptr || exp_avg_sq_out == nullptr))
+        return LOHAN_ERR_NULL;
+    if (misaligned(param_fp32_out, 16) || misaligned(exp_avg_out, 16) ||
+        misaligned(exp_avg_sq_out, 16))
+        return LOHAN_ERR_ALIGN;
+    if (n != 0 && (param_fp32_out == param_fp32_in || exp_avg_out == exp_avg_in ||
+                   exp_avg_sq_out == exp_avg_sq_in))
+        return LOHAN_ERR_ARG;
+    const int cus = current_cu_count();
+    if (cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::StepScalars s =
+        make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
+    hipError_t e = lohan::launch_adam_block_step_oop(
+        param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16, param_fp32_out, exp_avg_out,
+        exp_avg_sq_out, param_bf16_out, n, s, kernel_mode(flags), overflow_flag,
+        adam_launch_for(n), cus, stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
 float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm)
 {
     if (!(sqnorm >= 0.0) || !std::isfinite(sqnorm) || !finite_pos(loss_scale) ||

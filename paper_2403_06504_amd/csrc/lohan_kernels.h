@@ -51,6 +51,13 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
                                   const uint32_t *flag, const float *inv_override,
                                   const AdamLaunch &cfg, int cus, hipStream_t stream);
 
+// Out-of-place form with the overflow test fused in (clears *flag, then one 28 B/element pass).
+hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, const float *v_in,
+                                      const void *grad_fp16, float *p_out, float *m_out,
+                                      float *v_out, void *p16, uint64_t n, const StepScalars &s,
+                                      int mode, uint32_t *flag, const AdamLaunch &cfg, int cus,
+                                      hipStream_t stream);
+
 hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,
                              float *inv_out, hipStream_t stream);
 

@@ -405,6 +405,92 @@ __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
     }
 }
 
+// Out-of-place form with the overflow test fused in: one pass of 28 B/element instead of the
+// 2 B/element flag pass followed by the in-place step.  The inputs are only read, so a block
+// whose gradients turn out to hold inf/NaN loses nothing: the kernel raises *flag (cleared by a
+// one-lane kernel ahead of it) and the caller discards the outputs.  Each wavefront tests the
+// gradient bits it has loaded anyway; only a wavefront that found a non-finite value touches
+// *flag, with a vector atomic OR.
+template <int WG, int UNROLL, int POLICY, int MODE>
+__global__ __launch_bounds__(WG) void k_adam_block_step_oop(
+    const float *__restrict__ pi, const float *__restrict__ mi, const float *__restrict__ vi,
+    const uint16_t *__restrict__ g, float *__restrict__ po, float *__restrict__ mo,
+    float *__restrict__ vo, uint16_t *__restrict__ p16, uint64_t n, StepScalars s,
+    uint32_t *__restrict__ flag)
+{
+    constexpr bool L2 = (MODE & 1) != 0, HALF_OUT = (MODE & 2) != 0;
+    constexpr uint64_t kVec = 4;
+    constexpr uint64_t kRow = (uint64_t)WG * kVec;
+    constexpr uint64_t kTile = kRow * UNROLL;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t ntiles = n / kTile;
+    uint32_t ovf = 0;
+
+    for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const uint64_t base = tile * kTile + (uint64_t)tid * kVec;
+        f16x4 gv[UNROLL];
+        f32x4 pv[UNROLL], mv[UNROLL], vv[UNROLL];
+        u32x2 hv[UNROLL];
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) {
+            const uint64_t off = base + j * kRow;
+            gv[j] = ld_stream<POLICY>(reinterpret_cast<const f16x4 *>(g + off));
+            pv[j] = ld_stream<POLICY>(reinterpret_cast<const f32x4 *>(pi + off));
+            mv[j] = ld_stream<POLICY>(reinterpret_cast<const f32x4 *>(mi + off));
+            vv[j] = ld_stream<POLICY>(reinterpret_cast<const f32x4 *>(vi + off));
+        }
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) {
+            const u32x2 bits = __builtin_bit_cast(u32x2, gv[j]);
+            ovf = overflow_bits(bits.x, ovf);
+            ovf = overflow_bits(bits.y, ovf);
+            adam_vec4<L2, HALF_OUT>(pv[j], mv[j], vv[j], gv[j], s, hv[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) {
+            const uint64_t off = base + j * kRow;
+            st_stream<POLICY>(reinterpret_cast<f32x4 *>(po + off), pv[j]);
+            st_stream<POLICY>(reinterpret_cast<f32x4 *>(mo + off), mv[j]);
+            st_stream<POLICY>(reinterpret_cast<f32x4 *>(vo + off), vv[j]);
+            st_stream<POLICY>(reinterpret_cast<u32x2 *>(p16 + off), hv[j]);
+        }
+    }
+
+    const uint64_t rem_start = ntiles * kTile;
+    const uint64_t rem_vecs = (n - rem_start) / kVec;
+    for (uint64_t i = (uint64_t)blockIdx.x * WG + tid; i < rem_vecs;
+         i += (uint64_t)gridDim.x * WG) {
+        const uint64_t off = rem_start + i * kVec;
+        f16x4 gq = *reinterpret_cast<const f16x4 *>(g + off);
+        f32x4 pq = *reinterpret_cast<const f32x4 *>(pi + off);
+        f32x4 mq = *reinterpret_cast<const f32x4 *>(mi + off);
+        f32x4 vq = *reinterpret_cast<const f32x4 *>(vi + off);
+        const u32x2 bits = __builtin_bit_cast(u32x2, gq);
+        ovf = overflow_bits(bits.x, ovf);
+        ovf = overflow_bits(bits.y, ovf);
+        u32x2 h;
+        adam_vec4<L2, HALF_OUT>(pq, mq, vq, gq, s, h);
+        *reinterpret_cast<f32x4 *>(po + off) = pq;
+        *reinterpret_cast<f32x4 *>(mo + off) = mq;
+        *reinterpret_cast<f32x4 *>(vo + off) = vq;
+        *reinterpret_cast<u32x2 *>(p16 + off) = h;
+    }
+    const uint64_t tail = rem_start + rem_vecs * kVec + tid;
+    if (blockIdx.x == 0 && tail < n) {
+        const uint32_t gbits = g[tail];
+        ovf = overflow_bits(gbits, ovf);
+        _Float16 gh = __builtin_bit_cast(_Float16, (uint16_t)gbits);
+        float pe = pi[tail], me = mi[tail], ve = vi[tail];
+        adam_elem<L2>(pe, me, ve, (float)gh, s);
+        po[tail] = pe;
+        mo[tail] = me;
+        vo[tail] = ve;
+        p16[tail] = (uint16_t)pack16<HALF_OUT>(pe, 0.0f);
+    }
+
+    if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0 && (tid & 63u) == 0) atomicOr(flag, 1u);
+}
+
 // Per-block norm clipping without a host round trip: from the squared norm that
 // lohan_grad_sqnorm left in device memory, compute the unscale factor of the clipped step,
 //     coef = min(1, max_norm / (sqrt(sqnorm) + 1e-6)),  S_eff = fp32(S / coef),  inv = fl(1 / S_eff),
@@ -473,35 +559,51 @@ hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_n
 
 typedef void (*adam_kernel_t)(float *, float *, float *, const uint16_t *, uint16_t *, uint64_t,
                               StepScalars, const uint32_t *, const float *);
+typedef void (*adam_oop_kernel_t)(const float *, const float *, const float *, const uint16_t *,
+                                  float *, float *, float *, uint16_t *, uint64_t, StepScalars,
+                                  uint32_t *);
 
-template <int WG, int UNROLL, int POLICY>
-static adam_kernel_t pick_mode(int mode)
+// The two kernel families share the variant space; a family names the function-pointer type and
+// the instantiation for one point of it.
+struct InPlaceFamily {
+    typedef adam_kernel_t fn;
+    template <int WG, int UNROLL, int POLICY, int MODE>
+    static fn get() { return k_adam_block_step<WG, UNROLL, POLICY, MODE>; }
+};
+struct OutOfPlaceFamily {
+    typedef adam_oop_kernel_t fn;
+    template <int WG, int UNROLL, int POLICY, int MODE>
+    static fn get() { return k_adam_block_step_oop<WG, UNROLL, POLICY, MODE>; }
+};
+
+template <class F, int WG, int UNROLL, int POLICY>
+static typename F::fn pick_mode(int mode)
 {
     switch (mode & 3) {
-    case 0: return k_adam_block_step<WG, UNROLL, POLICY, 0>;
-    case 1: return k_adam_block_step<WG, UNROLL, POLICY, 1>;
-    case 2: return k_adam_block_step<WG, UNROLL, POLICY, 2>;
-    default: return k_adam_block_step<WG, UNROLL, POLICY, 3>;
+    case 0: return F::template get<WG, UNROLL, POLICY, 0>();
+    case 1: return F::template get<WG, UNROLL, POLICY, 1>();
+    case 2: return F::template get<WG, UNROLL, POLICY, 2>();
+    default: return F::template get<WG, UNROLL, POLICY, 3>();
     }
 }
 
-template <int WG, int UNROLL>
-static adam_kernel_t pick_policy(int policy, int mode)
+template <class F, int WG, int UNROLL>
+static typename F::fn pick_policy(int policy, int mode)
 {
     switch (policy) {
-    case 0: return pick_mode<WG, UNROLL, 0>(mode);
-    case 1: return pick_mode<WG, UNROLL, 1>(mode);
-    case 2: return pick_mode<WG, UNROLL, 2>(mode);
+    case 0: return pick_mode<F, WG, UNROLL, 0>(mode);
+    case 1: return pick_mode<F, WG, UNROLL, 1>(mode);
+    case 2: return pick_mode<F, WG, UNROLL, 2>(mode);
     default: return nullptr;
     }
 }
 
-template <int WG>
-static adam_kernel_t pick_unroll(int unroll_index, int policy, int mode)
+template <class F, int WG>
+static typename F::fn pick_unroll(int unroll_index, int policy, int mode)
 {
     switch (unroll_index) {
-    case 0: return pick_policy<WG, 1>(policy, mode);
-    case 1: return pick_policy<WG, 2>(policy, mode);
+    case 0: return pick_policy<F, WG, 1>(policy, mode);
+    case 1: return pick_policy<F, WG, 2>(policy, mode);
     default: return nullptr;
     }
 }
@@ -515,24 +617,30 @@ bool adam_variant_valid(int variant)
            ((variant >> 4) & 3) < 3;
 }
 
-hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
-                                  void *p16, uint64_t n, const StepScalars &s, int mode,
-                                  const uint32_t *flag, const float *inv_override,
-                                  const AdamLaunch &cfg, int cus, hipStream_t stream)
+template <class F>
+static typename F::fn pick_kernel(int variant, int mode)
 {
-    if (n == 0) return hipSuccess;
-    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
-    const int wg_index = cfg.variant & 3, unroll_index = (cfg.variant >> 2) & 3;
-    const int policy = (cfg.variant >> 4) & 3;
-    const int wg = 64 << wg_index, unroll = 1 << unroll_index;
-    adam_kernel_t kernel = nullptr;
+    const int wg_index = variant & 3, unroll_index = (variant >> 2) & 3;
+    const int policy = (variant >> 4) & 3;
     switch (wg_index) {
-    case 0: kernel = pick_unroll<64>(unroll_index, policy, mode); break;
-    case 1: kernel = pick_unroll<128>(unroll_index, policy, mode); break;
-    default: kernel = pick_unroll<256>(unroll_index, policy, mode); break;
+    case 0: return pick_unroll<F, 64>(unroll_index, policy, mode);
+    case 1: return pick_unroll<F, 128>(unroll_index, policy, mode);
+    default: return pick_unroll<F, 256>(unroll_index, policy, mode);
     }
-    if (kernel == nullptr) return hipErrorInvalidValue;
+}
 
+// Grid, workgroup size and the dynamic LDS request for n elements under cfg.
+struct AdamGeometry {
+    uint32_t grid;
+    int wg;
+    size_t lds;
+};
+
+static hipError_t adam_geometry(const void *kernel, uint64_t n, const AdamLaunch &cfg, int cus,
+                                AdamGeometry &out)
+{
+    const int wg_index = cfg.variant & 3, unroll_index = (cfg.variant >> 2) & 3;
+    const int wg = 64 << wg_index, unroll = 1 << unroll_index;
     const uint64_t tile = (uint64_t)wg * 4 * unroll;
     uint64_t want = n / tile;
     if (want < 1) want = 1;
@@ -542,7 +650,7 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
     }
     if (want > 0x7FFFFFFFull) want = 0x7FFFFFFFull;      // grid-stride loop covers the rest
 
-    // Occupancy throttle: the kernel uses no LDS, so a dynamic LDS request per workgroup sized
+    // Occupancy throttle: the kernels use no LDS, so a dynamic LDS request per workgroup sized
     // as a fraction of the CU's 160 KB bounds how many workgroups (hence wavefronts, hence bytes
     // in flight) a CU holds at once.
     size_t lds = 0;
@@ -552,15 +660,54 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
         if (wgs < 1) wgs = 1;
         lds = (size_t)(kLdsBytesPerCu / wgs) / 256 * 256;
         if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+            hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)lds);
             if (e != hipSuccess) return e;
         }
     }
-    hipLaunchKernelGGL(kernel, dim3((uint32_t)want), dim3(wg), lds, stream, p, m, v,
+    out.grid = (uint32_t)want;
+    out.wg = wg;
+    out.lds = lds;
+    return hipSuccess;
+}
+
+hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
+                                  void *p16, uint64_t n, const StepScalars &s, int mode,
+                                  const uint32_t *flag, const float *inv_override,
+                                  const AdamLaunch &cfg, int cus, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    adam_kernel_t kernel = pick_kernel<InPlaceFamily>(cfg.variant, mode);
+    if (kernel == nullptr) return hipErrorInvalidValue;
+    AdamGeometry geo;
+    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, cus, geo);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kernel, dim3(geo.grid), dim3(geo.wg), geo.lds, stream, p, m, v,
                        reinterpret_cast<const uint16_t *>(grad_fp16),
                        reinterpret_cast<uint16_t *>(p16), n, s, flag, inv_override);
+    return hipGetLastError();
+}
+
+hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, const float *v_in,
+                                      const void *grad_fp16, float *p_out, float *m_out,
+                                      float *v_out, void *p16, uint64_t n, const StepScalars &s,
+                                      int mode, uint32_t *flag, const AdamLaunch &cfg, int cus,
+                                      hipStream_t stream)
+{
+    // The flag starts at 0 on the stream; the update kernel can only raise it.
+    hipLaunchKernelGGL(k_grad_empty, dim3(1), dim3(64), 0, stream, (double *)nullptr, flag);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n == 0) return e;
+    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    adam_oop_kernel_t kernel = pick_kernel<OutOfPlaceFamily>(cfg.variant, mode);
+    if (kernel == nullptr) return hipErrorInvalidValue;
+    AdamGeometry geo;
+    e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, cus, geo);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kernel, dim3(geo.grid), dim3(geo.wg), geo.lds, stream, p_in, m_in, v_in,
+                       reinterpret_cast<const uint16_t *>(grad_fp16), p_out, m_out, v_out,
+                       reinterpret_cast<uint16_t *>(p16), n, s, flag);
     return hipGetLastError();
 }
 

@@ -131,6 +131,29 @@ def test_clipped_step_validation_returns_before_any_launch(lib):
     assert status(wsb=ws_bytes - 1) == 4
 
 
+def test_out_of_place_step_validation_returns_before_any_launch(lib):
+    def status(pi=A, mi=A * 2, vi=A * 3, g=A * 4, po=A * 5, mo=A * 6, vo=A * 7, p16=A * 8, n=16,
+               step=1, loss_scale=1024.0, flag=A * 9, flags=0, **over):
+        h = dict(GOOD, **over)
+        return lib.lohan_adam_block_step_out_of_place(
+            pi, mi, vi, g, po, mo, vo, p16, n, h["lr"], h["beta1"], h["beta2"], h["eps"],
+            h["weight_decay"], step, loss_scale, flag, flags, None)
+
+    for name in ("pi", "mi", "vi", "g", "po", "mo", "vo", "p16", "flag"):
+        assert status(**{name: None}) == 1, name
+    for name in ("pi", "mi", "vi", "g", "po", "mo", "vo", "p16"):
+        assert status(**{name: A * 10 + 8}) == 2, name
+    assert status(flag=A * 9 + 2) == 2
+    assert status(po=A) == 3 and status(mo=A * 2) == 3 and status(vo=A * 3) == 3   # in == out
+    assert status(flags=2) == 3                  # a prechecked flag belongs to the in-place step
+    assert status(flags=8) == 3
+    assert status(step=0) == 3
+    for bad in (0.0, -1.0, math.inf, math.nan):
+        assert status(loss_scale=bad) == 3
+    assert status(beta1=1.0) == 3 and status(beta2=-0.1) == 3 and status(lr=-1.0) == 3
+    assert status(eps=math.nan) == 3 and status(weight_decay=math.inf) == 3
+
+
 def test_offload_create_validation_touches_no_device(lib):
     handle = ctypes.c_void_p()
     need = lib.lohan_offload_slab_bytes(1000, 3)
