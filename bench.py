@@ -10,7 +10,7 @@ Adam-updated elements per second; the roofline object prices the dominant kernel
 recorded on the launch stream inside the timed region.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt13b|gpt175b|gpt_h768|
-                     stream13b|offload13b|shapes|gpt13b_oop|gpt175b_oop]
+                     stream13b|offload13b|shapes|models|gpt13b_oop|gpt175b_oop]
 
 The *_oop workloads time lohan_adam_block_step_out_of_place instead: the overflow test fused into
 a single 28 B/element pass between two sets of state (not the default: it doubles the state).
@@ -46,7 +46,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="gpt13b",
                     choices=["gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b", "shapes",
-                             "gpt13b_oop", "gpt175b_oop"])
+                             "gpt13b_oop", "gpt175b_oop", "models"])
     ap.add_argument("--variant", type=int, default=None, help="kernel launch-shape override")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--waves-per-cu", type=int, default=-1,
@@ -466,6 +466,84 @@ def bench_shapes(args, torch, lohan, synth):
     }
 
 
+def bench_models(args, torch, lohan, synth):
+    """Whole small models, all blocks' gradients present: the step of every block issued (a) block
+    by block (lohan_grad_sqnorm + lohan_adam_block_step per block) and (b) through one
+    lohan_adam_multi_block_step call.  One "step" = one pass over all blocks of one model."""
+    dev = "cuda:0"
+    models = [("gpt_h768_12blocks", 12, 12 * 768 ** 2)]
+    models += [(f"dit{name}_{layers}blocks", layers, 18 * h * h)
+               for name, layers, h in synth.TABLE_VI_DIT[:4]]
+    models += [("gpt6B_28blocks", 28, 12 * 4096 ** 2)]
+    rows = []
+    for name, layers, n in models:
+        wl = synth.Workload(name, n, 100, 65536.0, False)
+        hy = wl.hyper()
+        blocks = [synth.make_block(wl, seed=i, device=dev) for i in range(layers)]
+        flags = torch.zeros(layers, dtype=torch.int32, device=dev)
+        norms = torch.zeros(layers, dtype=torch.float64, device=dev)
+        ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+        array = lohan.make_block_array([(b["p"], b["m"], b["v"], b["g"], b["p16"], n)
+                                        for b in blocks])
+        reps = max(3, min(args.steps, int(4e10 // (n * layers))))
+
+        def per_block(t):
+            for i, b in enumerate(blocks):
+                lohan.lohan_grad_sqnorm(b["g"], n, wl.loss_scale, norms[i:i + 1],
+                                        flags[i:i + 1], ws)
+                lohan.lohan_adam_block_step(b["p"], b["m"], b["v"], b["g"], b["p16"], n,
+                                            hy["lr"], hy["beta1"], hy["beta2"], hy["eps"],
+                                            hy["weight_decay"], t, hy["loss_scale"],
+                                            flags[i:i + 1], lohan.LOHAN_FLAG_PRECHECKED, None)
+
+        def multi(t):
+            lohan.lohan_adam_multi_block_step(array, hy["lr"], hy["beta1"], hy["beta2"],
+                                              hy["eps"], hy["weight_decay"], t,
+                                              hy["loss_scale"], 0.0, flags, norms, 0, ws,
+                                              num_blocks=layers)
+
+        def timed(fn, t_first):
+            fn(t_first)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for k in range(reps):
+                fn(t_first + 1 + k)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps
+
+        t_blk = timed(per_block, hy["step"])
+        t_multi = timed(multi, hy["step"] + reps + 1)
+        assert int(flags.max().cpu().item()) == 0
+        total = n * layers
+        rows.append({"model": name, "blocks": layers, "elements_per_block": n,
+                     "per_block_calls_ms": t_blk * 1e3, "multi_block_call_ms": t_multi * 1e3,
+                     "per_block_calls_elements_per_s": total / t_blk,
+                     "multi_block_call_elements_per_s": total / t_multi,
+                     "multi_block_call_step_hbm_gbps":
+                         (ADAM_BYTES_PER_ELEM + REDUCE_BYTES_PER_ELEM) * total / t_multi / 1e9,
+                     "speedup": t_blk / t_multi})
+        del blocks, array
+        torch.cuda.empty_cache()
+    total = sum(r["blocks"] * r["elements_per_block"] for r in rows)
+    total_s = sum(r["multi_block_call_ms"] for r in rows) / 1e3
+    worst = min(rows, key=lambda r: r["multi_block_call_step_hbm_gbps"])
+    return {
+        "metric": "adam_updated_elements_per_sec", "value": total / total_s,
+        "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": 1,
+        "ms_per_step": total_s * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "models: all blocks of six small models (h=768 x12, the four "
+                               "smallest DiT shapes of Table VI, GPT 6B), one multi-block call "
+                               "per model", "elements": total},
+        "roofline": {"kernel": "whole multi-block call (reduction + update), 30 B/element",
+                     "bound": "hbm", "achieved": worst["multi_block_call_step_hbm_gbps"],
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": worst["multi_block_call_step_hbm_gbps"] / HBM_PEAK_GBPS,
+                     "traffic": None, "note": f"worst model of the sweep ({worst['model']})"},
+        "models": rows, "cpu_baseline": None,
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -492,6 +570,8 @@ def main():
         out = bench_offload(args, torch, lohan, synth)
     elif args.workload == "shapes":
         out = bench_shapes(args, torch, lohan, synth)
+    elif args.workload == "models":
+        out = bench_models(args, torch, lohan, synth)
     elif args.workload.endswith("_oop"):
         out = bench_block_oop(args, torch, lohan, synth)
     else:

@@ -184,6 +184,47 @@ lohan_status_t lohan_adam_block_step_out_of_place(
     hipStream_t stream);
 
 /*
+ * One block of a multi-block call: the tensors of Table II for that block, as the arguments of
+ * lohan_adam_block_step (same layout, alignment and aliasing rules).
+ */
+typedef struct {
+    float *param_fp32;       /* device, in/out: n floats */
+    float *exp_avg;          /* device, in/out: n floats */
+    float *exp_avg_sq;       /* device, in/out: n floats */
+    const void *grad_fp16;   /* device, in    : n binary16 values */
+    void *param_bf16_out;    /* device, out   : n 16-bit values */
+    uint64_t n;              /* may be 0 */
+} lohan_block_t;
+
+/*
+ * The block step of Sec. IV-C for several blocks whose gradients are all present, in a constant
+ * number of launches instead of two or three per block (small blocks -- the DiT shapes of
+ * Table VI, the h=768 test block -- are otherwise bound by launch gaps and by the ramp of each
+ * short kernel).  Every block keeps its own overflow flag, its own norm and its own skip
+ * decision, exactly as if lohan_grad_sqnorm / lohan_adam_block_step[_clipped] had been called on
+ * it alone; the results are bit-identical to those calls.
+ *   blocks          HOST array of num_blocks descriptors (read during the call only; they travel
+ *                   to the device inside the kernel arguments, nothing is uploaded or allocated)
+ *   num_blocks      any count; runs of up to 64 consecutive blocks of similar length share one
+ *                   launch.  0 -> LOHAN_OK, nothing done
+ *   max_norm        0: no clipping.  > 0 and finite: each block is clipped by its own norm,
+ *                   resolved on the device as in lohan_adam_block_step_clipped.  Else LOHAN_ERR_ARG
+ *   overflow_flags  device, num_blocks uint32: written per block (0 or 1), or read-only with
+ *                   LOHAN_FLAG_PRECHECKED
+ *   sqnorms         device, num_blocks doubles, 8-byte aligned, or NULL: per-block squared norm
+ *                   of the unscaled gradients (unspecified for a block whose flag is 1)
+ *   flags           as lohan_adam_block_step
+ *   workspace       required, lohan_workspace_bytes() bytes, as for the other entry points
+ * Errors as lohan_adam_block_step; all blocks are validated before the first launch.
+ */
+lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t num_blocks,
+                                           float lr, float beta1, float beta2, float eps,
+                                           float weight_decay, int64_t step, float loss_scale,
+                                           float max_norm, uint32_t *overflow_flags,
+                                           double *sqnorms, uint32_t flags, void *workspace,
+                                           size_t workspace_bytes, hipStream_t stream);
+
+/*
  * Host-only helper for per-block gradient-norm clipping: returns the loss scale to hand to
  * lohan_adam_block_step so that unscaling and clipping are one multiply,
  *     coef = min(1, max_norm / (sqrt(sqnorm) + 1e-6)),   result = (float)(loss_scale / coef),

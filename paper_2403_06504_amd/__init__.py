@@ -25,6 +25,9 @@ from .binding import (  # noqa: F401
     lohan_adam_block_step,
     lohan_adam_block_step_clipped,
     lohan_adam_block_step_out_of_place,
+    lohan_adam_multi_block_step,
+    make_block_array,
+    LohanBlock,
     lohan_clip_loss_scale,
     lohan_get_launch_config,
     lohan_grad_overflow_check,

@@ -22,7 +22,7 @@ LOHAN_FLAG_P16_FP16 = 4
 EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
     "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
-    "lohan_adam_block_step_out_of_place", "lohan_clip_loss_scale",
+    "lohan_adam_block_step_out_of_place", "lohan_adam_multi_block_step", "lohan_clip_loss_scale",
     "lohan_set_launch_config", "lohan_get_launch_config",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
     "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
@@ -50,6 +50,13 @@ class LohanOffloadBlock(ctypes.Structure):
                 ("host_exp_avg_sq", ctypes.c_void_p), ("grad_fp16", ctypes.c_void_p),
                 ("param_bf16_out", ctypes.c_void_p), ("n", ctypes.c_uint64),
                 ("overflow_flag", ctypes.c_void_p), ("sqnorm", ctypes.c_void_p)]
+
+
+class LohanBlock(ctypes.Structure):
+    """Mirror of lohan_block_t."""
+    _fields_ = [("param_fp32", ctypes.c_void_p), ("exp_avg", ctypes.c_void_p),
+                ("exp_avg_sq", ctypes.c_void_p), ("grad_fp16", ctypes.c_void_p),
+                ("param_bf16_out", ctypes.c_void_p), ("n", ctypes.c_uint64)]
 
 
 class LohanError(RuntimeError):
@@ -94,6 +101,10 @@ def load_library():
                                                        f32, f32, f32, f32, ctypes.c_int64, f32,
                                                        vp, ctypes.c_uint32, vp]
     lib.lohan_adam_block_step_out_of_place.restype = ctypes.c_int
+    lib.lohan_adam_multi_block_step.argtypes = [ctypes.POINTER(LohanBlock), ctypes.c_uint32, f32,
+                                                f32, f32, f32, f32, ctypes.c_int64, f32, f32, vp,
+                                                vp, ctypes.c_uint32, vp, sz, vp]
+    lib.lohan_adam_multi_block_step.restype = ctypes.c_int
     lib.lohan_clip_loss_scale.argtypes = [ctypes.c_double, f32, f32]
     lib.lohan_clip_loss_scale.restype = f32
     lib.lohan_set_launch_config.argtypes = [ctypes.c_int] * 4
@@ -245,6 +256,36 @@ def lohan_adam_block_step_out_of_place(param_fp32_in, exp_avg_in, exp_avg_sq_in,
         float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
         float(loss_scale), _addr(overflow_flag, 1, _U32, "overflow_flag"), int(flags),
         _stream(stream)))
+
+
+def make_block_array(blocks):
+    """ctypes array of lohan_block_t from a sequence of (param_fp32, exp_avg, exp_avg_sq,
+    grad_fp16, param_bf16_out, n) tuples of tensors / addresses.  Build it once and pass it to
+    lohan_adam_multi_block_step on every step: the addresses do not change."""
+    arr = (LohanBlock * max(1, len(blocks)))()
+    for i, (p, m, v, g, h, n) in enumerate(blocks):
+        arr[i] = LohanBlock(_addr(p, n, _F32, "param_fp32"), _addr(m, n, _F32, "exp_avg"),
+                            _addr(v, n, _F32, "exp_avg_sq"), _addr(g, n, _F16, "grad_fp16"),
+                            _addr(h, n, _BF16, "param_bf16_out"), int(n))
+    return arr
+
+
+def lohan_adam_multi_block_step(blocks, lr, beta1, beta2, eps, weight_decay, step, loss_scale,
+                                max_norm, overflow_flags, sqnorms, flags, workspace,
+                                workspace_bytes=None, stream=None, num_blocks=None):
+    """`blocks`: a sequence of tuples (see make_block_array) or an array it returned (then pass
+    num_blocks)."""
+    if isinstance(blocks, (list, tuple)):
+        num_blocks = len(blocks)
+        blocks = make_block_array(blocks)
+    elif num_blocks is None:
+        num_blocks = len(blocks)
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_adam_multi_block_step(
+        blocks, int(num_blocks), float(lr), float(beta1), float(beta2), float(eps),
+        float(weight_decay), int(step), float(loss_scale), float(max_norm),
+        _addr(overflow_flags, num_blocks, _U32, "overflow_flags"),
+        _addr(sqnorms, num_blocks, _F64, "sqnorms"), int(flags), ws, ws_bytes, _stream(stream)))
 
 
 def lohan_clip_loss_scale(sqnorm, loss_scale, max_norm) -> float:

@@ -239,7 +239,7 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
         make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
     float *inv_dev = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
                                                lohan::kScalarsOffset);
-    hipError_t e = lohan::launch_clip_scale(sqnorm, loss_scale, max_norm, inv_dev, stream);
+    hipError_t e = lohan::launch_clip_scale(sqnorm, loss_scale, max_norm, inv_dev, 1, stream);
     if (e != hipSuccess) return LOHAN_ERR_HIP;
     e = lohan::launch_adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out,
                                       n, s, kernel_mode(flags), overflow_flag, inv_dev,
@@ -277,6 +277,90 @@ lohan_status_t lohan_adam_block_step_out_of_place(
         exp_avg_sq_out, param_bf16_out, n, s, kernel_mode(flags), overflow_flag,
         adam_launch_for(n), cus, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
+lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t num_blocks,
+                                           float lr, float beta1, float beta2, float eps,
+                                           float weight_decay, int64_t step, float loss_scale,
+                                           float max_norm, uint32_t *overflow_flags,
+                                           double *sqnorms, uint32_t flags, void *workspace,
+                                           size_t workspace_bytes, hipStream_t stream)
+{
+    if (num_blocks == 0) return LOHAN_OK;
+    if (blocks == nullptr) return LOHAN_ERR_NULL;
+    for (uint32_t b = 0; b < num_blocks; ++b) {
+        const lohan_block_t &blk = blocks[b];
+        lohan_status_t st = validate_step_args(blk.param_fp32, blk.exp_avg, blk.exp_avg_sq,
+                                               blk.grad_fp16, blk.param_bf16_out, blk.n, lr, beta1,
+                                               beta2, eps, weight_decay, step, loss_scale,
+                                               overflow_flags, flags);
+        if (st != LOHAN_OK) return st;
+    }
+    if (misaligned(sqnorms, 8)) return LOHAN_ERR_ALIGN;
+    const bool clip = max_norm != 0.0f;
+    if (clip && !finite_pos(max_norm)) return LOHAN_ERR_ARG;
+    lohan_status_t st = check_workspace(workspace, workspace_bytes);
+    if (st != LOHAN_OK) return st;
+    const int cus = current_cu_count();
+    if (cus <= 0) return LOHAN_ERR_HIP;
+
+    const bool prechecked = (flags & LOHAN_FLAG_PRECHECKED) != 0;
+    const bool want_norm = clip || sqnorms != nullptr;
+    const lohan::StepScalars s =
+        make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
+    const uint32_t red_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
+    const double inv = 1.0 / (double)loss_scale;
+    char *ws = reinterpret_cast<char *>(workspace);
+    float *inv_dev = reinterpret_cast<float *>(ws + lohan::kScalarsOffset);
+    double *norms_ws = reinterpret_cast<double *>(ws + lohan::kNormsOffset);
+
+    // One launch covers a run of consecutive blocks: at most kMultiMaxBlocks of them, and of
+    // similar enough length that the grid, sized for the longest, holds few empty workgroups.
+    uint32_t first = 0;
+    while (first < num_blocks) {
+        lohan::MultiArgs args;
+        uint32_t count = 0;
+        uint64_t longest = 0, total = 0;
+        while (first + count < num_blocks && count < lohan::kMultiMaxBlocks) {
+            const uint64_t n = blocks[first + count].n;
+            const uint64_t new_longest = n > longest ? n : longest;
+            const double covered = (double)new_longest * (double)(count + 1);
+            const double used = (double)(total + n);
+            if (count > 0 && covered - used > 0.5 * used + 1048576.0) break;
+            const lohan_block_t &blk = blocks[first + count];
+            lohan::MultiDesc &d = args.d[count];
+            d.p = blk.param_fp32;
+            d.m = blk.exp_avg;
+            d.v = blk.exp_avg_sq;
+            d.g = reinterpret_cast<const uint16_t *>(blk.grad_fp16);
+            d.p16 = reinterpret_cast<uint16_t *>(blk.param_bf16_out);
+            d.n = n;
+            longest = new_longest;
+            total += n;
+            ++count;
+        }
+        for (uint32_t b = count; b < lohan::kMultiMaxBlocks; ++b) args.d[b] = lohan::MultiDesc{};
+
+        uint32_t *flags_dev = overflow_flags + first;
+        double *norms_dev = sqnorms != nullptr ? sqnorms + first : norms_ws;
+        if (!prechecked || want_norm) {
+            hipError_t e = lohan::launch_multi_grad_reduce(
+                args, count, want_norm, inv * inv, want_norm ? norms_dev : nullptr,
+                prechecked ? nullptr : flags_dev, workspace, red_wgs, stream);
+            if (e != hipSuccess) return LOHAN_ERR_HIP;
+        }
+        if (clip) {
+            hipError_t e = lohan::launch_clip_scale(norms_dev, loss_scale, max_norm, inv_dev,
+                                                    count, stream);
+            if (e != hipSuccess) return LOHAN_ERR_HIP;
+        }
+        hipError_t e = lohan::launch_adam_multi_block_step(
+            args, count, s, kernel_mode(flags), flags_dev, clip ? inv_dev : nullptr,
+            adam_launch_for(total), cus, stream);
+        if (e != hipSuccess) return LOHAN_ERR_HIP;
+        first += count;
+    }
+    return LOHAN_OK;
 }
 
 float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm)

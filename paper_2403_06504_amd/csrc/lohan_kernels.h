@@ -22,11 +22,27 @@ struct StepScalars {
     float wd;
 };
 
-// Workspace layout: kMaxPartials doubles, then kMaxPartials uint32 flags, then 256 bytes of
-// per-call scalars (the clipped step's unscale factor).
+// Blocks of a multi-block launch travel by value in the kernel arguments (no table in device
+// memory, nothing to upload): kMultiMaxBlocks descriptors of 48 bytes stay under the 4 KB limit.
+constexpr uint32_t kMultiMaxBlocks = 64;
+struct MultiDesc {
+    float *p, *m, *v;
+    const uint16_t *g;
+    uint16_t *p16;
+    uint64_t n;
+};
+struct MultiArgs {
+    MultiDesc d[kMultiMaxBlocks];
+};
+
+// Workspace layout: kMaxPartials doubles, then kMaxPartials uint32 flags, then the per-call
+// scalars: kMultiMaxBlocks unscale factors (float; a single-block clipped step uses the first),
+// then kMultiMaxBlocks squared norms (double) for multi-block calls whose caller wants none.
 constexpr uint32_t kMaxPartials = 4096;
 constexpr size_t kScalarsOffset = (size_t)kMaxPartials * (sizeof(double) + sizeof(uint32_t));
-constexpr size_t kWorkspaceBytes = kScalarsOffset + 256;
+constexpr size_t kNormsOffset = kScalarsOffset + 256;
+constexpr size_t kWorkspaceBytes = kNormsOffset + kMultiMaxBlocks * sizeof(double);
+static_assert(kMultiMaxBlocks * sizeof(float) <= 256, "unscale factors must fit their area");
 
 hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm, double inv2,
                               double *sqnorm, uint32_t *flag, void *workspace, uint32_t max_wgs,
@@ -58,8 +74,19 @@ hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, cons
                                       int mode, uint32_t *flag, const AdamLaunch &cfg, int cus,
                                       hipStream_t stream);
 
+// sqnorm[0..count) -> inv_out[0..count)
 hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,
-                             float *inv_out, hipStream_t stream);
+                             float *inv_out, uint32_t count, hipStream_t stream);
+
+// Multi-block forms: num_blocks in [1, kMultiMaxBlocks]; flags / sqnorms / inv_override are
+// arrays indexed by block.
+hipError_t launch_multi_grad_reduce(const MultiArgs &args, uint32_t num_blocks, bool with_norm,
+                                    double inv2, double *sqnorms, uint32_t *flags,
+                                    void *workspace, uint32_t max_wgs, hipStream_t stream);
+hipError_t launch_adam_multi_block_step(const MultiArgs &args, uint32_t num_blocks,
+                                        const StepScalars &s, int mode, const uint32_t *flags,
+                                        const float *inv_override, const AdamLaunch &cfg, int cus,
+                                        hipStream_t stream);
 
 }  // namespace lohan
 

@@ -92,11 +92,12 @@ __device__ __forceinline__ void reduce_vec(u32x4 q, uint32_t &ovf, double &acc)
 constexpr int kReduceThreads = 64;
 constexpr int kReduceUnroll = 8;
 
+// Workgroup `wg` of `nwg` reduces its interleaved share of g[0, n) and writes partial `slot`.
 template <bool WITH_NORM, int UNROLL>
-__global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *__restrict__ g,
-                                                                uint64_t n,
-                                                                double *__restrict__ partial_sum,
-                                                                uint32_t *__restrict__ partial_flag)
+__device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g, uint64_t n,
+                                                 uint32_t wg, uint32_t nwg, uint32_t slot,
+                                                 double *__restrict__ partial_sum,
+                                                 uint32_t *__restrict__ partial_flag)
 {
     constexpr int kThreads = kReduceThreads;
     constexpr int kWaves = kThreads / 64;
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *
     uint32_t ovf = 0;
     double acc = 0.0;
 
-    for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    for (uint64_t tile = wg; tile < ntiles; tile += nwg) {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(g + tile * kTile) + tid;
         u32x4 q[UNROLL];
 #pragma unroll
@@ -120,13 +121,12 @@ __global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *
     // Ragged end: whole 8-element vectors first, then up to 7 single elements.
     const uint64_t rem_start = ntiles * kTile;
     const uint64_t rem_vecs = (n - rem_start) / kVec;
-    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + tid; i < rem_vecs;
-         i += (uint64_t)gridDim.x * kThreads) {
+    for (uint64_t i = (uint64_t)wg * kThreads + tid; i < rem_vecs; i += (uint64_t)nwg * kThreads) {
         u32x4 q = *(reinterpret_cast<const u32x4 *>(g + rem_start) + i);
         reduce_vec<WITH_NORM>(q, ovf, acc);
     }
     const uint64_t tail_start = rem_start + rem_vecs * kVec;
-    if (blockIdx.x == 0 && tail_start + tid < n) {
+    if (wg == 0 && tail_start + tid < n) {
         uint32_t h = g[tail_start + tid];
         ovf = overflow_bits(h, ovf);
         if constexpr (WITH_NORM) acc += (double)square_pair(h, 0.0f);
@@ -154,13 +154,36 @@ __global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *
             total += s_sum[w];
             f |= s_flag[w];
         }
-        if constexpr (WITH_NORM) partial_sum[blockIdx.x] = total;
-        partial_flag[blockIdx.x] = f;
+        if constexpr (WITH_NORM) partial_sum[slot] = total;
+        partial_flag[slot] = f;
     }
 }
 
-// Stage 2: one workgroup.  inv2 = (1/loss_scale)^2 in float64 turns the raw sum of squares into
-// the squared norm of the unscaled gradients.
+template <bool WITH_NORM, int UNROLL>
+__global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *__restrict__ g,
+                                                                uint64_t n,
+                                                                double *__restrict__ partial_sum,
+                                                                uint32_t *__restrict__ partial_flag)
+{
+    grad_reduce_body<WITH_NORM, UNROLL>(g, n, blockIdx.x, gridDim.x, blockIdx.x, partial_sum,
+                                        partial_flag);
+}
+
+// Several blocks in one launch: grid (workgroups per block, blocks); block b's partials occupy
+// slots [b * gridDim.x, (b + 1) * gridDim.x).
+template <bool WITH_NORM, int UNROLL>
+__global__ __launch_bounds__(kReduceThreads) void k_multi_grad_reduce(
+    MultiArgs args, double *__restrict__ partial_sum, uint32_t *__restrict__ partial_flag)
+{
+    const uint32_t b = blockIdx.y;
+    grad_reduce_body<WITH_NORM, UNROLL>(args.d[b].g, args.d[b].n, blockIdx.x, gridDim.x,
+                                        b * gridDim.x + blockIdx.x, partial_sum, partial_flag);
+}
+
+// Stage 2: one workgroup per block (blockIdx.x = b; a single-block call launches one).  Block
+// b's partials are slots [b * nparts, (b + 1) * nparts); its results go to sqnorm[b] and flag[b].
+// inv2 = (1/loss_scale)^2 in float64 turns the raw sum of squares into the squared norm of the
+// unscaled gradients.
 template <bool WITH_NORM>
 __global__ __launch_bounds__(kThreads) void k_grad_finalize(const double *__restrict__ partial_sum,
                                                             const uint32_t *__restrict__ partial_flag,
@@ -169,6 +192,9 @@ __global__ __launch_bounds__(kThreads) void k_grad_finalize(const double *__rest
                                                             uint32_t *__restrict__ flag)
 {
     const uint32_t tid = threadIdx.x;
+    const uint32_t b = blockIdx.x;
+    partial_sum += (size_t)b * nparts;
+    partial_flag += (size_t)b * nparts;
     double acc = 0.0;
     uint32_t f = 0;
     for (uint32_t i = tid; i < nparts; i += kThreads) {
@@ -197,9 +223,9 @@ __global__ __launch_bounds__(kThreads) void k_grad_finalize(const double *__rest
             r |= s_flag[w];
         }
         if constexpr (WITH_NORM) {
-            if (sqnorm != nullptr) *sqnorm = total * inv2;
+            if (sqnorm != nullptr) sqnorm[b] = total * inv2;
         }
-        if (flag != nullptr) *flag = r;
+        if (flag != nullptr) flag[b] = r;
     }
 }
 
@@ -328,21 +354,13 @@ __device__ __forceinline__ void st_stream(T *ptr, T val)
 // MODE bits: 1 = L2 regularisation instead of decoupled decay, 2 = emit the 16-bit copy as IEEE
 // binary16 instead of bfloat16.
 template <int WG, int UNROLL, int POLICY, int MODE>
-__global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
-                                                        float *__restrict__ m,
-                                                        float *__restrict__ v,
-                                                        const uint16_t *__restrict__ g,
-                                                        uint16_t *__restrict__ p16, uint64_t n,
-                                                        StepScalars s,
-                                                        const uint32_t *__restrict__ flag,
-                                                        const float *__restrict__ inv_override)
+__device__ __forceinline__ void adam_block_body(float *__restrict__ p, float *__restrict__ m,
+                                                float *__restrict__ v,
+                                                const uint16_t *__restrict__ g,
+                                                uint16_t *__restrict__ p16, uint64_t n,
+                                                const StepScalars &s)
 {
     constexpr bool L2 = (MODE & 1) != 0, HALF_OUT = (MODE & 2) != 0;
-    // Skip rule: a set overflow flag means nothing at all is written by this kernel.
-    if (*flag != 0u) return;
-    // Device-side clipping: the unscale factor then comes from k_clip_scale's output.
-    if (inv_override != nullptr) s.inv = *inv_override;
-
     constexpr uint64_t kVec = 4;                                  // elements per lane per access
     constexpr uint64_t kRow = (uint64_t)WG * kVec;                // elements per wg-wide access
     constexpr uint64_t kTile = kRow * UNROLL;
@@ -403,6 +421,44 @@ __global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
         v[tail] = ve;
         p16[tail] = (uint16_t)pack16<HALF_OUT>(pe, 0.0f);
     }
+}
+
+template <int WG, int UNROLL, int POLICY, int MODE>
+__global__ __launch_bounds__(WG) void k_adam_block_step(float *__restrict__ p,
+                                                        float *__restrict__ m,
+                                                        float *__restrict__ v,
+                                                        const uint16_t *__restrict__ g,
+                                                        uint16_t *__restrict__ p16, uint64_t n,
+                                                        StepScalars s,
+                                                        const uint32_t *__restrict__ flag,
+                                                        const float *__restrict__ inv_override)
+{
+    // Skip rule: a set overflow flag means nothing at all is written by this kernel.
+    if (*flag != 0u) return;
+    // Device-side clipping: the unscale factor then comes from k_clip_scale's output.
+    if (inv_override != nullptr) s.inv = *inv_override;
+    adam_block_body<WG, UNROLL, POLICY, MODE>(p, m, v, g, p16, n, s);
+}
+
+// Several blocks in one launch: grid (tiles of the largest block, blocks).  blockIdx.y selects
+// the block's descriptor from the kernel arguments; the hardware hands out workgroups with x
+// fastest, so the tiles in flight still form a compact window that moves through one block
+// after the other.  Each block has its own flag and, when clipping, its own unscale factor.
+template <int WG, int UNROLL, int POLICY, int MODE>
+__global__ __launch_bounds__(WG) void k_adam_multi_block_step(MultiArgs args, StepScalars s,
+                                                              const uint32_t *__restrict__ flags,
+                                                              const float *__restrict__ inv_override)
+{
+    const uint32_t b = blockIdx.y;
+    const uint64_t n = args.d[b].n;
+    constexpr uint64_t kTile = (uint64_t)WG * 4 * UNROLL;
+    // Workgroups beyond this block's tiles have nothing to do (workgroup 0 always takes the
+    // ragged end, also of a block shorter than one tile).
+    if (blockIdx.x != 0 && (uint64_t)blockIdx.x * kTile >= n) return;
+    if (flags[b] != 0u) return;
+    if (inv_override != nullptr) s.inv = inv_override[b];
+    adam_block_body<WG, UNROLL, POLICY, MODE>(args.d[b].p, args.d[b].m, args.d[b].v, args.d[b].g,
+                                              args.d[b].p16, n, s);
 }
 
 // Out-of-place form with the overflow test fused in: one pass of 28 B/element instead of the
@@ -495,16 +551,17 @@ __global__ __launch_bounds__(WG) void k_adam_block_step_oop(
 // lohan_grad_sqnorm left in device memory, compute the unscale factor of the clipped step,
 //     coef = min(1, max_norm / (sqrt(sqnorm) + 1e-6)),  S_eff = fp32(S / coef),  inv = fl(1 / S_eff),
 // in float64 until the two roundings shown -- the same formula as lohan_clip_loss_scale on the
-// host.  One lane; the result is read by every wavefront of the following k_adam_block_step.
+// host.  One lane per block; the result is read by every wavefront of the following update.
 __global__ void k_clip_scale(const double *__restrict__ sqnorm, float loss_scale, float max_norm,
-                             float *__restrict__ inv_out)
+                             float *__restrict__ inv_out, uint32_t count)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    const double norm = __builtin_sqrt(*sqnorm);
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= count) return;
+    const double norm = __builtin_sqrt(sqnorm[b]);
     double coef = (double)max_norm / (norm + 1e-6);
     if (coef > 1.0) coef = 1.0;
     const float s_eff = (float)((double)loss_scale / coef);
-    *inv_out = 1.0f / s_eff;
+    inv_out[b] = 1.0f / s_eff;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -550,10 +607,42 @@ hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm,
 }
 
 hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,
-                             float *inv_out, hipStream_t stream)
+                             float *inv_out, uint32_t count, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_clip_scale, dim3(1), dim3(64), 0, stream, sqnorm, loss_scale, max_norm,
-                       inv_out);
+    hipLaunchKernelGGL(k_clip_scale, dim3((count + 63) / 64), dim3(64), 0, stream, sqnorm,
+                       loss_scale, max_norm, inv_out, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_multi_grad_reduce(const MultiArgs &args, uint32_t num_blocks, bool with_norm,
+                                    double inv2, double *sqnorms, uint32_t *flags,
+                                    void *workspace, uint32_t max_wgs, hipStream_t stream)
+{
+    if (num_blocks == 0 || num_blocks > kMultiMaxBlocks) return hipErrorInvalidValue;
+    constexpr int kUnroll = kReduceUnroll;
+    constexpr uint64_t kTile = (uint64_t)kReduceThreads * 8 * kUnroll;
+    uint64_t longest = 0;
+    for (uint32_t b = 0; b < num_blocks; ++b)
+        if (args.d[b].n > longest) longest = args.d[b].n;
+    // The same total number of workgroups as a single-block call, split evenly over the blocks.
+    uint32_t per_block = (max_wgs + num_blocks - 1) / num_blocks;
+    if (per_block > kMaxPartials / num_blocks) per_block = kMaxPartials / num_blocks;
+    per_block = reduce_grid(longest, kTile, per_block);
+    double *psum = reinterpret_cast<double *>(workspace);
+    uint32_t *pflag = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(workspace) +
+                                                   sizeof(double) * kMaxPartials);
+    const dim3 grid(per_block, num_blocks);
+    if (with_norm) {
+        hipLaunchKernelGGL((k_multi_grad_reduce<true, kUnroll>), grid, dim3(kReduceThreads), 0,
+                           stream, args, psum, pflag);
+        hipLaunchKernelGGL((k_grad_finalize<true>), dim3(num_blocks), dim3(kThreads), 0, stream,
+                           psum, pflag, per_block, inv2, sqnorms, flags);
+    } else {
+        hipLaunchKernelGGL((k_multi_grad_reduce<false, kUnroll>), grid, dim3(kReduceThreads), 0,
+                           stream, args, psum, pflag);
+        hipLaunchKernelGGL((k_grad_finalize<false>), dim3(num_blocks), dim3(kThreads), 0, stream,
+                           psum, pflag, per_block, inv2, sqnorms, flags);
+    }
     return hipGetLastError();
 }
 
@@ -563,7 +652,9 @@ typedef void (*adam_oop_kernel_t)(const float *, const float *, const float *, c
                                   float *, float *, float *, uint16_t *, uint64_t, StepScalars,
                                   uint32_t *);
 
-// The two kernel families share the variant space; a family names the function-pointer type and
+typedef void (*adam_multi_kernel_t)(MultiArgs, StepScalars, const uint32_t *, const float *);
+
+// The kernel families share the variant space; a family names the function-pointer type and
 // the instantiation for one point of it.
 struct InPlaceFamily {
     typedef adam_kernel_t fn;
@@ -574,6 +665,12 @@ struct OutOfPlaceFamily {
     typedef adam_oop_kernel_t fn;
     template <int WG, int UNROLL, int POLICY, int MODE>
     static fn get() { return k_adam_block_step_oop<WG, UNROLL, POLICY, MODE>; }
+};
+
+struct MultiBlockFamily {
+    typedef adam_multi_kernel_t fn;
+    template <int WG, int UNROLL, int POLICY, int MODE>
+    static fn get() { return k_adam_multi_block_step<WG, UNROLL, POLICY, MODE>; }
 };
 
 template <class F, int WG, int UNROLL, int POLICY>
@@ -708,6 +805,27 @@ hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, cons
     hipLaunchKernelGGL(kernel, dim3(geo.grid), dim3(geo.wg), geo.lds, stream, p_in, m_in, v_in,
                        reinterpret_cast<const uint16_t *>(grad_fp16), p_out, m_out, v_out,
                        reinterpret_cast<uint16_t *>(p16), n, s, flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_adam_multi_block_step(const MultiArgs &args, uint32_t num_blocks,
+                                        const StepScalars &s, int mode, const uint32_t *flags,
+                                        const float *inv_override, const AdamLaunch &cfg, int cus,
+                                        hipStream_t stream)
+{
+    if (num_blocks == 0 || num_blocks > kMultiMaxBlocks) return hipErrorInvalidValue;
+    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    uint64_t longest = 0;
+    for (uint32_t b = 0; b < num_blocks; ++b)
+        if (args.d[b].n > longest) longest = args.d[b].n;
+    if (longest == 0) return hipSuccess;
+    adam_multi_kernel_t kernel = pick_kernel<MultiBlockFamily>(cfg.variant, mode);
+    if (kernel == nullptr) return hipErrorInvalidValue;
+    AdamGeometry geo;
+    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), longest, cfg, cus, geo);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kernel, dim3(geo.grid, num_blocks), dim3(geo.wg), geo.lds, stream, args, s,
+                       flags, inv_override);
     return hipGetLastError();
 }
 

@@ -154,6 +154,40 @@ def test_out_of_place_step_validation_returns_before_any_launch(lib):
     assert status(eps=math.nan) == 3 and status(weight_decay=math.inf) == 3
 
 
+def test_multi_block_step_validation_returns_before_any_launch(lib):
+    ws_bytes = lib.lohan_workspace_bytes()
+
+    def status(blocks=((A, A * 2, A * 3, A * 4, A * 5, 16), (A * 6, A * 7, A * 8, A * 9, A * 10, 0)),
+               count=None, step=1, loss_scale=1024.0, max_norm=0.0, flags_dev=A * 11,
+               norms=A * 12, flags=0, ws=A * 13, wsb=ws_bytes, **over):
+        h = dict(GOOD, **over)
+        arr = (binding.LohanBlock * max(1, len(blocks)))(*[binding.LohanBlock(*b) for b in blocks])
+        return lib.lohan_adam_multi_block_step(
+            arr if blocks is not None else None, len(blocks) if count is None else count,
+            h["lr"], h["beta1"], h["beta2"], h["eps"], h["weight_decay"], step, loss_scale,
+            max_norm, flags_dev, norms, flags, ws, wsb, None)
+
+    assert lib.lohan_adam_multi_block_step(None, 0, 1e-4, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, 0.0, None,
+                                           None, 0, None, 0, None) == 0      # nothing to do
+    assert lib.lohan_adam_multi_block_step(None, 2, 1e-4, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, 0.0,
+                                           A, None, 0, A, ws_bytes, None) == 1
+    assert status(flags_dev=None) == 1
+    for field in range(5):                       # a NULL or misaligned array in the second block
+        blk = [A * 6, A * 7, A * 8, A * 9, A * 10, 16]
+        blk[field] = None
+        assert status(blocks=((A, A * 2, A * 3, A * 4, A * 5, 16), tuple(blk))) == 1, field
+        blk[field] = A * 20 + 4
+        assert status(blocks=((A, A * 2, A * 3, A * 4, A * 5, 16), tuple(blk))) == 2, field
+    assert status(norms=A * 12 + 4) == 2
+    assert status(norms=None, ws=None) == 1
+    assert status(ws=A * 13 + 8) == 2
+    assert status(wsb=ws_bytes - 1) == 4
+    assert status(step=0) == 3 and status(flags=8) == 3 and status(loss_scale=0.0) == 3
+    for bad in (-1.0, math.inf, math.nan):
+        assert status(max_norm=bad) == 3
+    assert status(beta1=1.0) == 3 and status(lr=math.nan) == 3
+
+
 def test_offload_create_validation_touches_no_device(lib):
     handle = ctypes.c_void_p()
     need = lib.lohan_offload_slab_bytes(1000, 3)

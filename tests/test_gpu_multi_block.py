@@ -1,0 +1,214 @@
+"""GPU parity of lohan_adam_multi_block_step: several blocks of Sec. IV-C's step in a constant
+number of launches.  Every block must come out exactly as the oracle leaves it when run on that
+block alone (own flag, own norm, own skip decision), whatever mix of lengths shares a launch."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2403_06504_amd as lohan
+from paper_2403_06504_amd import synthetic_inputs as synth
+
+from gpu_util import (RTOL_SQNORM, DeviceBlock, assert_parity_given_scales, assert_state_parity,
+                      oracle_steps)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+ZERO = {"p": 0, "m": 0, "v": 0, "p16": 0}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def workload(n, S=65536.0):
+    return synth.Workload(name=f"n{n}", n=n, step=100, loss_scale=S, zero_moments=False)
+
+
+class BlockSet:
+    def __init__(self, sizes, seed0=0, S=65536.0, overflow=()):
+        self.sizes = list(sizes)
+        self.S = S
+        self.hy = workload(1, S).hyper()
+        self.blocks = []
+        for i, n in enumerate(self.sizes):
+            t = synth.make_block(workload(n, S), seed=seed0 + i, device=DEV)
+            if i in overflow and n > 0:
+                t["g"].view(torch.int16)[(n * 2) // 3] = synth.NONFINITE_FP16[i % 5] - (
+                    0x10000 if synth.NONFINITE_FP16[i % 5] >= 0x8000 else 0)
+            self.blocks.append(DeviceBlock(t))
+        nb = len(self.sizes)
+        self.flags = torch.full((max(nb, 1),), 7, dtype=torch.int32, device=DEV)
+        self.sqnorms = torch.full((max(nb, 1),), -1.0, dtype=torch.float64, device=DEV)
+        self.ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=DEV)
+        self.array = lohan.make_block_array(
+            [(b.p, b.m, b.v, b.g, b.p16, b.n) if b.n else (None, None, None, None, None, 0)
+             for b in self.blocks])
+
+    def host(self):
+        return [b.host() for b in self.blocks]
+
+    def step(self, step=None, max_norm=0.0, flags=0, want_norms=True, stream=None):
+        hy = self.hy
+        lohan.lohan_adam_multi_block_step(
+            self.array, hy["lr"], hy["beta1"], hy["beta2"], hy["eps"], hy["weight_decay"],
+            hy["step"] if step is None else step, self.S, max_norm, self.flags,
+            self.sqnorms if want_norms else None, flags, self.ws, stream=stream,
+            num_blocks=len(self.sizes))
+        torch.cuda.synchronize()
+        return [int(x) for x in self.flags.cpu().tolist()][:len(self.sizes)]
+
+
+def check_against_oracle(oracle, bs, hosts, steps_taken, l2=False, half=False, what=""):
+    """hosts: per-block host copies from before the steps; advances them with the oracle."""
+    for i, (blk, host) in enumerate(zip(bs.blocks, hosts)):
+        for t in steps_taken:
+            oracle.adam_block_step(host["p"], host["m"], host["v"], host["g"], host["p16"],
+                                   nthreads=4, l2_mode=l2, half_out=half,
+                                   **dict(bs.hy, step=t))
+        worst = assert_state_parity(blk.host(), host, what=f"{what} block {i} n={blk.n}")
+        assert worst == ZERO, (what, i, blk.n, worst)
+
+
+def test_equal_small_blocks_two_steps_one_overflow(oracle):
+    """28 equal blocks (a DiT-sized model in miniature), one of them overflowing."""
+    bs = BlockSet([300_001] * 28, overflow=(5,))
+    hosts = bs.host()
+    t0 = bs.hy["step"]
+    want_flags = [1 if i == 5 else 0 for i in range(28)]
+    assert bs.step(t0) == want_flags
+    norms = bs.sqnorms.cpu().numpy()
+    for i, h in enumerate(hosts):
+        if i != 5:
+            want = oracle.grad_sqnorm(h["g"], bs.S)
+            assert abs(norms[i] - want) <= RTOL_SQNORM * want, i
+    assert bs.step(t0 + 1) == want_flags
+    check_against_oracle(oracle, bs, hosts, (t0, t0 + 1), what="equal blocks")
+    # the skipped block: the oracle also left it alone, so the comparison above already proves
+    # bit-identity with its initial state
+    assert oracle.grad_overflow_check(hosts[5]["g"]) == 1
+
+
+def test_mixed_lengths_share_and_split_launches(oracle):
+    """Empty, tiny, ragged and long blocks in one call: the grouping rule splits them into several
+    launches, and more than 64 blocks force a split as well."""
+    sizes = [0, 1, 7, 255, 256, 257, 4099, 1_000_003, 1_000_003, 999_999, 3, 0, 65_537,
+             2_000_001, 17, 1_999_999] + [10_007] * 70 + [5, 500_000]
+    overflow = (3, 7, 20, 85, len(sizes) - 1)
+    bs = BlockSet(sizes, seed0=50, overflow=overflow)
+    hosts = bs.host()
+    want = [1 if (i in overflow and n > 0) else 0 for i, n in enumerate(sizes)]
+    t0 = bs.hy["step"]
+    assert bs.step(t0) == want
+    norms = bs.sqnorms.cpu().numpy()
+    for i, h in enumerate(hosts):
+        if not want[i]:
+            ref = oracle.grad_sqnorm(h["g"], bs.S)
+            assert abs(norms[i] - ref) <= RTOL_SQNORM * ref + 0.0, (i, norms[i], ref)
+    check_against_oracle(oracle, bs, hosts, (t0,), what="mixed lengths")
+
+
+@pytest.mark.parametrize("flags", [lohan.LOHAN_FLAG_L2_MODE, lohan.LOHAN_FLAG_P16_FP16,
+                                   lohan.LOHAN_FLAG_L2_MODE | lohan.LOHAN_FLAG_P16_FP16])
+def test_mode_flags(oracle, flags):
+    bs = BlockSet([70_001, 4_096, 123_457], seed0=7)
+    hosts = bs.host()
+    assert bs.step(flags=flags, want_norms=False) == [0, 0, 0]
+    check_against_oracle(oracle, bs, hosts, (bs.hy["step"],),
+                         l2=bool(flags & lohan.LOHAN_FLAG_L2_MODE),
+                         half=bool(flags & lohan.LOHAN_FLAG_P16_FP16), what=f"flags={flags}")
+
+
+def test_prechecked_flags_are_read_only(oracle):
+    bs = BlockSet([50_001, 50_002, 50_003], seed0=9)
+    hosts = bs.host()
+    before = bs.host()
+    bs.flags.copy_(torch.tensor([0, 1, 0], dtype=torch.int32))
+    assert bs.step(flags=lohan.LOHAN_FLAG_PRECHECKED) == [0, 1, 0]
+    after = bs.blocks[1].host()
+    for k in ("p", "m", "v", "p16"):
+        assert np.array_equal(after[k].view(np.uint8), before[1][k].view(np.uint8)), k
+    for i in (0, 2):
+        oracle_steps(oracle, hosts[i], bs.hy, 1, nthreads=4)
+        assert assert_state_parity(bs.blocks[i].host(), hosts[i], what="prechecked") == ZERO
+    # the norms are still produced on request
+    norms = bs.sqnorms.cpu().numpy()
+    for i in range(3):
+        ref = oracle.grad_sqnorm(before[i]["g"], bs.S)
+        assert abs(norms[i] - ref) <= RTOL_SQNORM * ref
+
+
+@pytest.mark.parametrize("S,max_norm", [(65536.0, 0.5), (3000.0, 0.05), (1024.0, 100.0)])
+def test_per_block_clipping(oracle, S, max_norm):
+    """Each block is clipped by its own norm; bit-identical to the single-block clipped route, and
+    against the oracle as that route is."""
+    sizes = [300_007, 70_001, 1_000_003, 257]
+    bs = BlockSet(sizes, seed0=30, S=S, overflow=(1,))
+    single = BlockSet(sizes, seed0=30, S=S, overflow=(1,))
+    hosts = bs.host()
+    assert bs.step(max_norm=max_norm, want_norms=(S != 3000.0)) == [0, 1, 0, 0]
+    hy = bs.hy
+    for i, blk in enumerate(single.blocks):
+        blk.norm(S)
+        lohan.lohan_adam_block_step_clipped(blk.p, blk.m, blk.v, blk.g, blk.p16, blk.n, hy["lr"],
+                                            hy["beta1"], hy["beta2"], hy["eps"],
+                                            hy["weight_decay"], hy["step"], S, blk.sqnorm,
+                                            max_norm, blk.flag, 0, blk.ws)
+        torch.cuda.synchronize()
+        a, b = bs.blocks[i].host(), blk.host()
+        for k in ("p", "m", "v", "p16"):
+            assert np.array_equal(a[k].view(np.uint8), b[k].view(np.uint8)), (i, k)
+        if i == 1:
+            continue
+        sq_gpu = float(blk.sqnorm.cpu().item())
+        s_eff_gpu = lohan.lohan_clip_loss_scale(sq_gpu, S, max_norm)
+        sq_orc = oracle.grad_sqnorm(hosts[i]["g"], S)
+        s_eff_orc = float(oracle.clip_loss_scale(sq_orc, S, max_norm))
+        old = {k: hosts[i][k].copy() for k in ("p", "m", "v")}
+        oracle_steps(oracle, hosts[i], dict(hy, loss_scale=s_eff_orc), 1, nthreads=4)
+        assert_parity_given_scales(a, hosts[i], old, hosts[i]["g"], s_eff_gpu, s_eff_orc,
+                                   hy["lr"], what=f"multi-block clipping block {i}")
+
+
+def test_every_kernel_variant_multi_block(oracle):
+    sizes = [100_003, 1_000_003, 100_003, 77]
+    ref = BlockSet(sizes, seed0=3)
+    hosts = ref.host()
+    for h in hosts:
+        oracle_steps(oracle, h, ref.hy, 1, nthreads=8)
+    variants = [wg | (u << 2) | (pol << 4) for pol in range(3) for u in range(2) for wg in range(3)]
+    try:
+        for variant in variants:
+            for wgs, waves in ((0, 0), (1, 8), (0, 2)):
+                say(f"[multi variant] variant={variant} wgs_per_cu={wgs} waves_per_cu={waves}")
+                lohan.lohan_set_launch_config(variant, wgs, waves, 0)
+                bs = BlockSet(sizes, seed0=3)
+                assert bs.step(want_norms=False) == [0, 0, 0, 0]
+                for i, blk in enumerate(bs.blocks):
+                    assert assert_state_parity(blk.host(), hosts[i],
+                                               what=f"variant {variant} block {i}") == ZERO
+    finally:
+        lohan.lohan_set_launch_config()
+
+
+def test_config1_blocks_as_a_twelve_layer_model(oracle):
+    """Twelve h=768 blocks (the small configuration's shape), three chained steps."""
+    n = synth.WORKLOADS["gpt_h768"].n
+    bs = BlockSet([n] * 12, seed0=200)
+    hosts = bs.host()
+    t0 = bs.hy["step"]
+    for k in range(3):
+        assert bs.step(t0 + k, want_norms=False) == [0] * 12
+    check_against_oracle(oracle, bs, hosts, (t0, t0 + 1, t0 + 2), what="12 x h768")
+
+
+def test_no_blocks_is_a_no_op():
+    ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    flags = torch.full((1,), 3, dtype=torch.int32, device=DEV)
+    lohan.lohan_adam_multi_block_step([], 1e-4, 0.9, 0.999, 1e-8, 0.01, 1, 1024.0, 0.0, flags,
+                                      None, 0, ws)
+    torch.cuda.synchronize()
+    assert int(flags.cpu().item()) == 3
