@@ -51,6 +51,22 @@ typedef struct {
 double lohan_swap_iter_time(const lohan_swap_hw_t *hw, double a_g2m, double flop_r);
 
 /*
+ * FLOP_r as a function of the swapped amount (Eq. 7) and its derivative (Eq. 8): with the layers
+ * taken by decreasing offloading benefit, a_g2m covers the first i layers and a fraction of
+ * layer i+1, whose recomputation cost is taken proportional to the fraction left behind (the
+ * paper's interpolation; no layer is really split):
+ *     FLOP_r = flop_f - sum_{m<=i} FLOP_m - FLOP_{i+1} * (a_g2m - sum_{m<=i} A_m) / A_{i+1}
+ *     dFLOP_r / dA_G2M = -OB_{i+1}
+ * At a breakpoint the derivative is the right-hand one; at or beyond the sum of all A it is 0 and
+ * FLOP_r = flop_f - sum of all FLOP.  Layers with A = 0 are swapped from the start.
+ * layers[0..n): host, in.  flop_r, dflop_r: host, out (dflop_r may be NULL).
+ * LOHAN_ERR_NULL for NULL layers (with n > 0) or flop_r; LOHAN_ERR_ARG for a negative or
+ * non-finite a_g2m, flop_f or layer entry.
+ */
+lohan_status_t lohan_swap_recompute_flops(const lohan_layer_t *layers, size_t n, double flop_f,
+                                          double a_g2m, double *flop_r, double *dflop_r);
+
+/*
  * Algorithm 1.  layers[0..n): host, in; swap_list: host, out, room for n indices (indices into
  * layers, in swapping order); n_swapped, a_g2m, flop_r, t_iter: host, out (a_g2m, flop_r, t_iter
  * describe the returned swap list).  LOHAN_ERR_NULL for NULL pointers (layers may be NULL only if

@@ -1,5 +1,6 @@
 """Oracle for the holistic traffic-aware activation swapping planner (Sec. IV-D): the iteration-
-time model of Eq. 1-5 and the greedy search of Algorithm 1, in plain python floats (float64), in
+time model of Eq. 1-5, the interpolated recomputation cost of Eq. 7-8 and the greedy search of
+Algorithm 1, in plain python floats (float64), in
 the paper's notation and step order.  TEST INFRASTRUCTURE; shares nothing with the C++ planner.
 
 Readings where the paper is silent:
@@ -35,6 +36,23 @@ def iter_time(hw: dict, a_g2m: float, flop_r: float) -> float:
 def offloading_benefit(flop: float, act_bytes: float) -> float:
     """OB_layer = FLOP_layer / A_layer (Eq. 6)."""
     return math.inf if act_bytes == 0 else flop / act_bytes
+
+
+def recompute_flops(layers, flop_f: float, a_g2m: float):
+    """FLOP_r(A_G2M) of Eq. 7 and its derivative, Eq. 8.  With the layers numbered by decreasing
+    OB, find i with sum_{k<=i} A_k <= A_G2M < sum_{k<=i+1} A_k (right-hand piece at a breakpoint);
+    beyond the last breakpoint everything is swapped and the derivative is 0."""
+    ranked = sorted(layers, key=lambda la: -offloading_benefit(*la))
+    i = 0
+    while i < len(ranked) and sum(a for _, a in ranked[:i + 1]) <= a_g2m:
+        i += 1
+    whole = sum(f for f, _ in ranked[:i])
+    if i == len(ranked):
+        return flop_f - whole, 0.0
+    flop_next, a_next = ranked[i]
+    covered = sum(a for _, a in ranked[:i])
+    flop_r = flop_f - whole - flop_next * (a_g2m - covered) / a_next
+    return flop_r, -offloading_benefit(flop_next, a_next)
 
 
 def plan(layers, hw: dict):

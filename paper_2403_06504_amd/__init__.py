@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     lohan_offload_wait_last_step,
     lohan_plan_activation_swapping,
     lohan_swap_iter_time,
+    lohan_swap_recompute_flops,
     LOHAN_FLAG_L2_MODE,
     LOHAN_FLAG_P16_FP16,
     LOHAN_FLAG_PRECHECKED,

@@ -26,7 +26,7 @@ EXPORTS = (
     "lohan_set_launch_config", "lohan_get_launch_config",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
     "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
-    "lohan_swap_iter_time", "lohan_plan_activation_swapping",
+    "lohan_swap_iter_time", "lohan_swap_recompute_flops", "lohan_plan_activation_swapping",
 )
 
 LOHAN_OFFLOAD_SERIALIZED = 0
@@ -128,6 +128,10 @@ def load_library():
     lib.lohan_swap_iter_time.argtypes = [ctypes.POINTER(LohanSwapHw), ctypes.c_double,
                                          ctypes.c_double]
     lib.lohan_swap_iter_time.restype = ctypes.c_double
+    lib.lohan_swap_recompute_flops.argtypes = [ctypes.POINTER(LohanLayer), sz, ctypes.c_double,
+                                               ctypes.c_double, ctypes.POINTER(ctypes.c_double),
+                                               ctypes.POINTER(ctypes.c_double)]
+    lib.lohan_swap_recompute_flops.restype = ctypes.c_int
     lib.lohan_plan_activation_swapping.argtypes = [
         ctypes.POINTER(LohanLayer), sz, ctypes.POINTER(LohanSwapHw),
         ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_double),
@@ -357,6 +361,17 @@ def _swap_hw(hw: dict) -> LohanSwapHw:
 def lohan_swap_iter_time(hw: dict, a_g2m, flop_r) -> float:
     h = _swap_hw(hw)
     return float(load_library().lohan_swap_iter_time(ctypes.byref(h), float(a_g2m), float(flop_r)))
+
+
+def lohan_swap_recompute_flops(layers, flop_f, a_g2m):
+    """layers: sequence of (flop, act_bytes).  Returns (FLOP_r, dFLOP_r/dA_G2M)."""
+    n = len(layers)
+    arr = (LohanLayer * max(1, n))(*[LohanLayer(float(f), float(a)) for f, a in layers])
+    fr, dfr = ctypes.c_double(), ctypes.c_double()
+    _check(load_library().lohan_swap_recompute_flops(arr if n else None, n, float(flop_f),
+                                                     float(a_g2m), ctypes.byref(fr),
+                                                     ctypes.byref(dfr)))
+    return fr.value, dfr.value
 
 
 def lohan_plan_activation_swapping(layers, hw: dict):

@@ -33,6 +33,21 @@ double iter_time(const lohan_swap_hw_t &hw, double a_g2m, double flop_r)
     return t_f + t_b;
 }
 
+// Indices of the layers by decreasing offloading benefit OB = FLOP/A (Eq. 6); ties keep the
+// caller's order, a layer without activation bytes comes first.
+std::vector<uint32_t> benefit_order(const lohan_layer_t *layers, size_t n)
+{
+    std::vector<uint32_t> order(n);
+    std::iota(order.begin(), order.end(), 0u);
+    auto benefit = [&](uint32_t i) {
+        return layers[i].act_bytes == 0.0 ? std::numeric_limits<double>::infinity()
+                                          : layers[i].flop / layers[i].act_bytes;
+    };
+    std::stable_sort(order.begin(), order.end(),
+                     [&](uint32_t a, uint32_t b) { return benefit(a) > benefit(b); });
+    return order;
+}
+
 }  // namespace
 
 extern "C" {
@@ -41,6 +56,33 @@ double lohan_swap_iter_time(const lohan_swap_hw_t *hw, double a_g2m, double flop
 {
     if (!rates_ok(hw)) return std::numeric_limits<double>::quiet_NaN();
     return iter_time(*hw, a_g2m, flop_r);
+}
+
+lohan_status_t lohan_swap_recompute_flops(const lohan_layer_t *layers, size_t n, double flop_f,
+                                          double a_g2m, double *flop_r, double *dflop_r)
+{
+    if (flop_r == nullptr || (n != 0 && layers == nullptr)) return LOHAN_ERR_NULL;
+    if (!nonneg_finite(flop_f) || !nonneg_finite(a_g2m) || n > 0xFFFFFFFFull) return LOHAN_ERR_ARG;
+    for (size_t i = 0; i < n; ++i)
+        if (!nonneg_finite(layers[i].flop) || !nonneg_finite(layers[i].act_bytes))
+            return LOHAN_ERR_ARG;
+    double left = a_g2m;             // swapped bytes not yet assigned to a layer
+    double f = flop_f;
+    double slope = 0.0;
+    for (uint32_t idx : benefit_order(layers, n)) {
+        const double a = layers[idx].act_bytes;
+        if (a <= left) {             // wholly swapped (this also takes every layer with A = 0)
+            f -= layers[idx].flop;
+            left -= a;
+            continue;
+        }
+        f -= layers[idx].flop * (left / a);      // Eq. 7: the partly swapped layer
+        slope = -(layers[idx].flop / a);         // Eq. 8
+        break;
+    }
+    *flop_r = f;
+    if (dflop_r != nullptr) *dflop_r = slope;
+    return LOHAN_OK;
 }
 
 lohan_status_t lohan_plan_activation_swapping(const lohan_layer_t *layers, size_t n,
@@ -58,15 +100,8 @@ lohan_status_t lohan_plan_activation_swapping(const lohan_layer_t *layers, size_
         if (!nonneg_finite(layers[i].flop) || !nonneg_finite(layers[i].act_bytes))
             return LOHAN_ERR_ARG;
 
-    // layer_list.sortByOffloadingBenefit(): OB = FLOP/A (Eq. 6), highest first, stable.
-    std::vector<uint32_t> order(n);
-    std::iota(order.begin(), order.end(), 0u);
-    auto benefit = [&](uint32_t i) {
-        return layers[i].act_bytes == 0.0 ? std::numeric_limits<double>::infinity()
-                                          : layers[i].flop / layers[i].act_bytes;
-    };
-    std::stable_sort(order.begin(), order.end(),
-                     [&](uint32_t a, uint32_t b) { return benefit(a) > benefit(b); });
+    // layer_list.sortByOffloadingBenefit()
+    const std::vector<uint32_t> order = benefit_order(layers, n);
 
     size_t count = 0;
     double t_min = std::numeric_limits<double>::infinity();

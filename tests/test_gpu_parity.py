@@ -163,6 +163,16 @@ def test_l2_mode_at_13b_scale(oracle):
     assert oracle_steps(oracle, host, hy, 2, l2_mode=True) == [0, 0]
     worst = assert_state_parity(blk.host(), host, what="13B block, L2 mode")
     say(f"[l2@13b] worst ulp {worst}")
+    # a third step that also emits the 16-bit copy as binary16
+    h3 = dict(hy, step=hy["step"] + 2)
+    blk.step(h3, flags=lohan.LOHAN_FLAG_L2_MODE | lohan.LOHAN_FLAG_P16_FP16)
+    torch.cuda.synchronize()
+    assert blk.flag_value() == 0
+    assert oracle.adam_block_step(host["p"], host["m"], host["v"], host["g"], host["p16"],
+                                  l2_mode=True, half_out=True, nthreads=16, **h3) == 0
+    worst = assert_state_parity(blk.host(), host, what="13B block, L2 mode + fp16 copy")
+    say(f"[l2+fp16@13b] worst ulp {worst}")
+    assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
 
 
 def test_config1_h768_block_ten_steps(oracle):

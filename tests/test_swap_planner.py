@@ -134,7 +134,82 @@ def test_three_cases_of_the_time_curve():
     assert t == pytest.approx(min(p[2] for p in pts))
 
 
+def test_recompute_flops_hand_example():
+    """Eq. 7-8 on the hand example: benefit order (300,10) OB 30, (200,20) OB 10, (100,100) OB 1."""
+    for a, want_f, want_d in ((0.0, 600.0, -30.0), (5.0, 450.0, -30.0), (10.0, 300.0, -10.0),
+                              (20.0, 200.0, -10.0), (30.0, 100.0, -1.0), (80.0, 50.0, -1.0),
+                              (130.0, 0.0, 0.0), (200.0, 0.0, 0.0)):
+        f, d = orc.recompute_flops(LAYERS, 600.0, a)
+        assert f == pytest.approx(want_f, rel=1e-15) and d == want_d, a
+
+
+def test_recompute_flops_matches_prefixes_differences_and_convexity():
+    """At every breakpoint Eq. 7 must give the discrete FLOP_r that Algorithm 1 accumulates; the
+    slope of Eq. 8 must be the finite difference inside a piece; and the slopes never decrease
+    (the convexity argument of Sec. IV-D)."""
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        layers, hw = random_instance(rng, int(rng.integers(1, 20)))
+        _, pts = prefix_times(layers, hw)
+        for a, f, _t in pts:
+            got, _ = orc.recompute_flops(layers, hw["flop_f"], a)
+            assert got == pytest.approx(f, rel=1e-9, abs=1e-3)
+        total = pts[-1][0]
+        grid = np.sort(rng.uniform(0, total, 40))
+        slopes = []
+        for a in grid:
+            f0, d0 = orc.recompute_flops(layers, hw["flop_f"], float(a))
+            h = total * 1e-9
+            f1, d1 = orc.recompute_flops(layers, hw["flop_f"], float(a) + h)
+            if d0 == d1:                                      # same piece
+                assert (f1 - f0) / h == pytest.approx(d0, rel=1e-3, abs=1e-6 * abs(d0))
+            slopes.append(d0)
+        assert all(b >= a for a, b in zip(slopes, slopes[1:]))
+        assert orc.recompute_flops(layers, hw["flop_f"], total * 2)[1] == 0.0
+
+
+def test_continuous_iteration_time_is_convex():
+    """T_iter(A_G2M) with the interpolated FLOP_r is convex: midpoints lie below chords."""
+    rng = np.random.default_rng(4)
+    for _ in range(200):
+        layers, hw = random_instance(rng, int(rng.integers(2, 20)))
+        total = sum(a for _, a in layers)
+
+        def t(a):
+            return orc.iter_time(hw, a, orc.recompute_flops(layers, hw["flop_f"], a)[0])
+
+        for _ in range(20):
+            a, b = sorted(rng.uniform(0, total, 2))
+            mid = t(0.5 * (a + b))
+            assert mid <= 0.5 * (t(a) + t(b)) * (1 + 1e-12) + 1e-15
+
+
 # ----------------------------------------------------------------------------- C++ planner
+
+def test_library_recompute_flops_matches_oracle():
+    rng = np.random.default_rng(5)
+    for trial in range(300):
+        layers, hw = random_instance(rng, int(rng.integers(1, 30)))
+        if trial % 5 == 0 and len(layers) > 2:
+            layers[1] = (layers[1][0], 0.0)                   # a layer without activation bytes
+            layers[2] = layers[0]                             # a tie
+        total = sum(a for _, a in layers)
+        prefix = np.cumsum([a for _, a in sorted(layers, key=lambda la: -orc.offloading_benefit(*la))])
+        for a in list(rng.uniform(0, 1.2 * total, 10)) + [0.0, total] + [float(x) for x in prefix[:3]]:
+            got = lohan.lohan_swap_recompute_flops(layers, hw["flop_f"], a)
+            want = orc.recompute_flops(layers, hw["flop_f"], a)
+            assert got[0] == pytest.approx(want[0], rel=1e-12, abs=1e-3), (trial, a)
+            # FLOP_r is continuous; the slope jumps at a breakpoint, where the last bit of a sum
+            # decides the side, so it is compared away from breakpoints only
+            if np.min(np.abs(prefix - a)) > 1e-9 * total:
+                assert got[1] == pytest.approx(want[1], rel=1e-14), (trial, a)
+    assert lohan.lohan_swap_recompute_flops([], 7.0, 3.0) == (7.0, 0.0)
+    for bad in ((LAYERS, -1.0, 0.0), (LAYERS, 1.0, -1.0), (LAYERS, math.nan, 0.0),
+                (LAYERS, 1.0, math.inf), ([(1.0, -2.0)], 1.0, 0.0)):
+        with pytest.raises(lohan.LohanError) as e:
+            lohan.lohan_swap_recompute_flops(*bad)
+        assert e.value.status == 3
+
 
 def test_library_planner_matches_oracle_on_random_instances():
     rng = np.random.default_rng(2)
