@@ -212,3 +212,53 @@ def test_no_blocks_is_a_no_op():
                                       None, 0, ws)
     torch.cuda.synchronize()
     assert int(flags.cpu().item()) == 3
+
+
+def test_multi_block_call_in_a_hip_graph(oracle):
+    """The descriptors are part of the captured kernel arguments, so a captured multi-block call
+    (here with per-block clipping) replays without any host-side table: three replays with eager
+    work between them, each checked against the oracle."""
+    sizes = [200_003, 4_097, 200_003]
+    S, max_norm = 65536.0, 0.25
+    bs = BlockSet(sizes, seed0=60, S=S)
+    hosts = bs.host()
+    warm = BlockSet([4_096, 100], seed0=1, S=S)
+    warm.step(max_norm=max_norm)                       # first-use initialisation outside capture
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    hy = bs.hy
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            lohan.lohan_adam_multi_block_step(
+                bs.array, hy["lr"], hy["beta1"], hy["beta2"], hy["eps"], hy["weight_decay"],
+                hy["step"], S, max_norm, bs.flags, bs.sqnorms, 0, bs.ws, stream=side,
+                num_blocks=len(sizes))
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for blk, h in zip(bs.blocks, hosts):               # capture executes nothing
+        assert np.array_equal(blk.host()["p"].view(np.uint32), h["p"].view(np.uint32))
+
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for r in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert [int(x) for x in bs.flags.cpu().tolist()] == [0, 0, 0]
+        norms = bs.sqnorms.cpu().numpy()
+        for i, (blk, h) in enumerate(zip(bs.blocks, hosts)):
+            sq_orc = oracle.grad_sqnorm(h["g"], S)
+            assert abs(norms[i] - sq_orc) <= RTOL_SQNORM * sq_orc
+            s_eff_gpu = lohan.lohan_clip_loss_scale(float(norms[i]), S, max_norm)
+            s_eff_orc = float(oracle.clip_loss_scale(sq_orc, S, max_norm))
+            old = {k: h[k].copy() for k in ("p", "m", "v")}
+            oracle_steps(oracle, h, dict(hy, loss_scale=s_eff_orc), 1, nthreads=4)
+            got = blk.host()
+            assert_parity_given_scales(got, h, old, h["g"], s_eff_gpu, s_eff_orc, hy["lr"],
+                                       what=f"graph replay {r} block {i}")
+            if np.float32(s_eff_gpu) != np.float32(s_eff_orc):
+                for k in ("p", "m", "v", "p16"):        # keep the two sides on the same state
+                    h[k][...] = got[k]
+        scratch.add_(1.0)
+        warm.step(max_norm=max_norm)
+    assert float(scratch[0].cpu()) == 3.0
