@@ -36,7 +36,8 @@ REDUCE_BYTES_PER_ELEM = 2       # one read of g16
 # (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy:
 # factor 2.000 and 1.000 on gfx950).  Summary: profiles/k_adam_block_step_gpt13b_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {"gpt13b": 8601691 * 1024,      # profiles/..._gpt13b_hbm_traffic.md
-                          "gpt175b": 49545515 * 1024}    # profiles/..._gpt175b_trace_and_traffic.md
+                          "gpt175b": 49545515 * 1024,    # profiles/..._gpt175b_trace_and_traffic.md
+                          "gpt13b_oop": 8601956 * 1024}  # profiles/k_adam_block_step_oop_gpt13b_...
 
 
 def parse_args():
@@ -224,7 +225,8 @@ def bench_block_oop(args, torch, lohan, synth):
         "step_hbm_gbps": ADAM_BYTES_PER_ELEM * n / (elapsed / args.steps) / 1e9,
         "roofline": {"kernel": "k_adam_block_step_oop (events also span the one-lane flag clear)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "avg_launch_ms": call_ms, "median_launch_ms": all_ms[len(all_ms) // 2],
                      "min_launch_ms": all_ms[0],
                      "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
