@@ -262,3 +262,32 @@ def test_multi_block_call_in_a_hip_graph(oracle):
         scratch.add_(1.0)
         warm.step(max_norm=max_norm)
     assert float(scratch[0].cpu()) == 3.0
+
+
+def test_four_13b_blocks_in_one_call_sampled(oracle):
+    """Four blocks of the benchmark's shape (20 GB resident) through one call in the automatic
+    launch configuration; block 2 overflows.  Sampled ranges of every block against the oracle,
+    whole-buffer properties for the rest."""
+    wl = synth.WORKLOADS["gpt13b"]
+    n = wl.n
+    bs = BlockSet([n] * 4, seed0=300, overflow=(2,))
+    span = 1 << 20
+    rng = np.random.default_rng(15)
+    starts = [0, n - span] + [int(x) for x in rng.integers(span, n - 2 * span, size=3)]
+    before = [{s: blk.host(s, s + span) for s in starts} for blk in bs.blocks]
+    snap2 = {k: getattr(bs.blocks[2], k).clone() for k in ("p", "m", "v", "p16")}
+    assert bs.step() == [0, 0, 1, 0]
+    norms = bs.sqnorms.cpu().numpy()
+    for i, blk in enumerate(bs.blocks):
+        if i == 2:
+            for k in ("p", "m", "v", "p16"):
+                assert torch.equal(getattr(blk, k).view(torch.int16), snap2[k].view(torch.int16)), k
+            continue
+        for s in starts:
+            host = before[i][s]
+            assert oracle_steps(oracle, host, bs.hy, 1, nthreads=8) == [0]
+            worst = assert_state_parity(blk.host(s, s + span), host, what=f"block {i} range {s}")
+            assert worst == ZERO, (i, s, worst)
+        assert torch.equal(blk.p16.view(torch.int16), blk.p.to(torch.bfloat16).view(torch.int16))
+        # expected squared norm of N(0, 1e-3) gradients: n * 1e-6 (fp16 rounding is far below 1 %)
+        assert abs(norms[i] / (n * 1e-6) - 1.0) < 0.01

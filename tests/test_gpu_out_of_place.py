@@ -172,3 +172,44 @@ def test_13b_block_full_size_out_of_place(oracle):
     assert blk.cur == live
     for k in ("p", "m", "v"):
         assert torch.equal(blk.sets[live][k].view(torch.int32), snap[k].view(torch.int32)), k
+
+
+def test_175b_block_out_of_place_sampled(oracle):
+    """n = 12*12288^2 with a second set of state (54 GB resident, byte offsets beyond 2^32):
+    sampled ranges -- head, end, seeded interior, ranges whose fp32 byte offsets cross 2^32 --
+    against the oracle, whole-buffer properties for the rest, then one NaN in the last element."""
+    wl = synth.WORKLOADS["gpt175b"]
+    say(f"[oop 175b] n={wl.n} generating")
+    blk = TwoSets(synth.make_block(wl, seed=0, device=DEV))
+    span = 1 << 21
+    rng = np.random.default_rng(14)
+    starts = [0, wl.n - span] + [int(x) for x in rng.integers(span, wl.n - 2 * span, size=4)]
+    starts += [(1 << 30) - 3, wl.n // 2 + 1]
+    src = blk.sets[0]
+
+    def sample(s, which):
+        st = blk.sets[which]
+        out = {k: synth.to_numpy_bits(st[k][s:s + span]) for k in ("p", "m", "v", "p16")}
+        out["g"] = synth.to_numpy_bits(blk.g[s:s + span])
+        return out
+
+    before = {s: sample(s, 0) for s in starts}
+    hy = wl.hyper()
+    assert blk.step(hy) == 0 and blk.cur == 1
+    for s in starts:
+        host = before[s]
+        assert oracle_steps(oracle, host, hy, 1, nthreads=8) == [0]
+        worst = assert_state_parity(sample(s, 1), host, what=f"175B out of place, range {s}")
+        assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}, (s, worst)
+    out = blk.sets[1]
+    assert bool(torch.all(out["v"] >= 0))
+    assert torch.equal(out["p16"].view(torch.int16), out["p"].to(torch.bfloat16).view(torch.int16))
+    # m' = beta1 m + (1 - beta1) g everywhere (a whole-buffer check of the first moment in
+    # float64: one fp32 rounding per operation keeps it within a few ulp)
+    g = blk.g[:1 << 26].double() / hy["loss_scale"]
+    want_m = hy["beta1"] * src["m"][:1 << 26].double() + (1.0 - hy["beta1"]) * g
+    err = (out["m"][:1 << 26].double() - want_m).abs()
+    scale = torch.maximum(src["m"][:1 << 26].abs().double(), g.abs()) * 2.0 ** -22 + 1e-30
+    assert bool(torch.all(err <= scale))
+    blk.g.view(torch.int16)[wl.n - 1] = 0x7E00
+    assert blk.step(dict(hy, step=hy["step"] + 1)) == 1 and blk.cur == 1
