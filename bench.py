@@ -53,6 +53,13 @@ def parse_args():
     ap.add_argument("--waves-per-cu", type=int, default=-1,
                     help="occupancy throttle override (0 = none, -1 = built-in default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--compare-allocator", action="store_true",
+                    help="also time the update kernel on the five separate torch allocations "
+                         "before the block is moved into the library's placement")
+    ap.add_argument("--placement", choices=["library", "allocator"], default="library",
+                    help="gpt13b/gpt175b/gpt_h768/shapes: where the block's five arrays sit -- at "
+                         "the offsets lohan_model_placement gives inside one slab (default), or "
+                         "in five separate torch allocations")
     ap.add_argument("--blocks", type=int, default=None,
                     help="stream13b: number of blocks (default 40); offload13b: default 6")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -100,11 +107,64 @@ def cpu_baseline(block, wl, sample_elems=1 << 27):
     }
 
 
+def place_block(block, n, torch, lohan):
+    """Move a block's five tensors into one slab at the offsets lohan_model_placement gives for
+    the first block of a full group of such blocks (the layout a framework holding the whole
+    model would use).  Returns (views, slab, description)."""
+    gib, mib = 1 << 30, 1 << 20
+    wide = (4 * n + 2 * mib - 1) // (2 * mib) * (2 * mib)
+    group = max(1, (4 * gib - 2 * mib) // wide) if 256 * mib <= wide <= 4 * gib - 2 * mib else 1
+    offsets, slab_bytes, align = lohan.lohan_model_placement(n, group)
+    slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=block["p"].device)
+    start = (-slab.data_ptr()) % align
+    names = {"p": "param_fp32", "m": "exp_avg", "v": "exp_avg_sq", "g": "grad_fp16",
+             "p16": "param_bf16"}
+    placed = {}
+    for k, field in names.items():
+        off = start + offsets[0][field]
+        placed[k] = slab[off: off + n * block[k].element_size()].view(block[k].dtype)
+        placed[k].copy_(block[k])
+    what = (f"block 0 of a {group}-block group laid out by lohan_model_placement "
+            f"({slab_bytes / gib:.2f} GiB slab)")
+    return placed, slab, what
+
+
+def adam_kernel_only_ms(block, wl, torch, lohan, reps):
+    """Average duration of the update kernel alone on `block` (prechecked, flag 0)."""
+    flag = torch.zeros(1, dtype=torch.int32, device=block["p"].device)
+    hy = wl.hyper()
+
+    def call(t):
+        lohan.lohan_adam_block_step(block["p"], block["m"], block["v"], block["g"], block["p16"],
+                                    wl.n, hy["lr"], hy["beta1"], hy["beta2"], hy["eps"],
+                                    hy["weight_decay"], t, hy["loss_scale"], flag,
+                                    lohan.LOHAN_FLAG_PRECHECKED, None)
+
+    for w in range(3):
+        call(hy["step"] + w)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for k in range(reps):
+        call(hy["step"] + 3 + k)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
 def bench_block(args, torch, lohan, synth):
     wl = synth.WORKLOADS[args.workload]
     dev = "cuda:0"
     block = synth.make_block(wl, seed=0, device=dev)
     n = wl.n
+    placement = "five separate allocations of torch's caching allocator"
+    allocator_ms = None
+    if args.placement == "library":
+        if args.compare_allocator:
+            allocator_ms = adam_kernel_only_ms(block, wl, torch, lohan, min(args.steps, 20))
+        original = block
+        block, slab, placement = place_block(original, n, torch, lohan)
+        del original
+        torch.cuda.empty_cache()
     flag = torch.zeros(1, dtype=torch.int32, device=dev)
     sqnorm = torch.zeros(1, dtype=torch.float64, device=dev)
     ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
@@ -160,7 +220,7 @@ def bench_block(args, torch, lohan, synth):
         "config": {"workload": f"{wl.name}: one GPT block, n={n} elements "
                                f"(fp32 p/m/v, fp16 grads x loss scale {wl.loss_scale:g}, "
                                f"bf16 copy), AdamW step {wl.step}",
-                   "elements": n, "bytes_per_element_step": 30,
+                   "elements": n, "bytes_per_element_step": 30, "placement": placement,
                    "launch_config": list(lohan.lohan_get_launch_config())},
         "step_hbm_gbps": (ADAM_BYTES_PER_ELEM + REDUCE_BYTES_PER_ELEM) * n /
                          (elapsed / args.steps) / 1e9,
@@ -174,6 +234,12 @@ def bench_block(args, torch, lohan, synth):
                           "achieved_gbps": REDUCE_BYTES_PER_ELEM * n / (reduce_ms * 1e-3) / 1e9},
         "cpu_baseline": base,
     }
+    if allocator_ms is not None:
+        gbps = ADAM_BYTES_PER_ELEM * n / (allocator_ms * 1e-3) / 1e9
+        out["allocator_placement"] = {
+            "note": "the same kernel on five separate torch allocations, measured in this run "
+                    "before the block was moved into the library's placement",
+            "avg_launch_ms": allocator_ms, "achieved": gbps, "frac": gbps / HBM_PEAK_GBPS}
     return out
 
 
@@ -418,6 +484,11 @@ def bench_shapes(args, torch, lohan, synth):
         n = wl.n
         hy = wl.hyper()
         reps = max(3, min(args.steps, int(2e10 // n)))
+        if args.placement == "library":
+            original = block
+            block, slab, _ = place_block(original, n, torch, lohan)
+            del original
+            torch.cuda.empty_cache()
 
         def one_step(t, ev=None):
             lohan.lohan_grad_sqnorm(block["g"], n, wl.loss_scale, sqnorm, flag, ws)
@@ -449,6 +520,7 @@ def bench_shapes(args, torch, lohan, synth):
                      "adam_kernel_frac_of_peak": ADAM_BYTES_PER_ELEM * n / adam_ms / 1e6 /
                                                  HBM_PEAK_GBPS})
         del block
+        slab = None
         torch.cuda.empty_cache()
     total = sum(r["elements"] for r in rows)
     total_s = sum(r["ms_per_step"] for r in rows) / 1e3

@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     lohan_adam_block_step_clipped,
     lohan_adam_block_step_out_of_place,
     lohan_adam_multi_block_step,
+    lohan_model_placement,
     make_block_array,
     LohanBlock,
     lohan_clip_loss_scale,

@@ -22,7 +22,8 @@ LOHAN_FLAG_P16_FP16 = 4
 EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
     "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
-    "lohan_adam_block_step_out_of_place", "lohan_adam_multi_block_step", "lohan_clip_loss_scale",
+    "lohan_adam_block_step_out_of_place", "lohan_adam_multi_block_step", "lohan_model_placement",
+    "lohan_clip_loss_scale",
     "lohan_set_launch_config", "lohan_get_launch_config",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
     "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
@@ -57,6 +58,12 @@ class LohanBlock(ctypes.Structure):
     _fields_ = [("param_fp32", ctypes.c_void_p), ("exp_avg", ctypes.c_void_p),
                 ("exp_avg_sq", ctypes.c_void_p), ("grad_fp16", ctypes.c_void_p),
                 ("param_bf16_out", ctypes.c_void_p), ("n", ctypes.c_uint64)]
+
+
+class LohanBlockOffsets(ctypes.Structure):
+    """Mirror of lohan_block_offsets_t."""
+    _fields_ = [(k, ctypes.c_size_t) for k in ("param_fp32", "exp_avg", "exp_avg_sq", "grad_fp16",
+                                               "param_bf16")]
 
 
 class LohanError(RuntimeError):
@@ -105,6 +112,9 @@ def load_library():
                                                 f32, f32, f32, f32, ctypes.c_int64, f32, f32, vp,
                                                 vp, ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_multi_block_step.restype = ctypes.c_int
+    lib.lohan_model_placement.argtypes = [u64, ctypes.c_uint32, ctypes.POINTER(LohanBlockOffsets),
+                                          ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.lohan_model_placement.restype = ctypes.c_int
     lib.lohan_clip_loss_scale.argtypes = [ctypes.c_double, f32, f32]
     lib.lohan_clip_loss_scale.restype = f32
     lib.lohan_set_launch_config.argtypes = [ctypes.c_int] * 4
@@ -290,6 +300,18 @@ def lohan_adam_multi_block_step(blocks, lr, beta1, beta2, eps, weight_decay, ste
         float(weight_decay), int(step), float(loss_scale), float(max_norm),
         _addr(overflow_flags, num_blocks, _U32, "overflow_flags"),
         _addr(sqnorms, num_blocks, _F64, "sqnorms"), int(flags), ws, ws_bytes, _stream(stream)))
+
+
+def lohan_model_placement(n, num_blocks):
+    """Returns (offsets, slab_bytes, slab_alignment); offsets is a list of dicts with the byte
+    offsets of param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16 for each block."""
+    arr = (LohanBlockOffsets * max(1, num_blocks))()
+    total, align = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load_library().lohan_model_placement(int(n), int(num_blocks), arr, ctypes.byref(total),
+                                                ctypes.byref(align)))
+    fields = [f for f, _ in LohanBlockOffsets._fields_]
+    return ([{f: getattr(arr[b], f) for f in fields} for b in range(num_blocks)], total.value,
+            align.value)
 
 
 def lohan_clip_loss_scale(sqnorm, loss_scale, max_norm) -> float:

@@ -363,6 +363,65 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
     return LOHAN_OK;
 }
 
+lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
+                                     lohan_block_offsets_t *offsets, size_t *slab_bytes,
+                                     size_t *slab_alignment)
+{
+    constexpr size_t kGranule = 2ull << 20;       // array sizes are rounded up to this
+    constexpr size_t kPeriod = 4ull << 30;        // lanes are one period apart ...
+    constexpr size_t kSkew = 1ull << 20;          // ... plus this shift per lane
+    if (slab_bytes == nullptr || slab_alignment == nullptr ||
+        (offsets == nullptr && num_blocks != 0))
+        return LOHAN_ERR_NULL;
+    if (n > (1ull << 40)) return LOHAN_ERR_ARG;
+    auto round_up = [](size_t x, size_t a) { return (x + a - 1) / a * a; };
+    const size_t wide = round_up((size_t)n * 4, kGranule);      // one fp32 array
+    const size_t narrow = round_up((size_t)n * 2, kGranule);    // one 16-bit array
+    *slab_alignment = kGranule;
+
+    constexpr size_t kSmallest = 256ull << 20;    // below this the placement gains under 1 %
+    if (wide > kPeriod - kGranule || wide < kSmallest) {      // plain block-major packing
+        const size_t block_bytes = 3 * wide + 2 * narrow;
+        for (uint32_t b = 0; b < num_blocks; ++b) {
+            const size_t base = (size_t)b * block_bytes;
+            offsets[b] = lohan_block_offsets_t{base, base + wide, base + 2 * wide,
+                                               base + 3 * wide, base + 3 * wide + narrow};
+        }
+        *slab_bytes = (size_t)num_blocks * block_bytes;
+        return LOHAN_OK;
+    }
+
+    const size_t per_group = (kPeriod - kGranule) / wide;
+    size_t group_base = 0;
+    for (uint32_t first = 0; first < num_blocks; first += (uint32_t)per_group) {
+        const size_t count = num_blocks - first < per_group ? num_blocks - first : per_group;
+        const size_t lane_used = count * wide;
+        const size_t lane[3] = {0, kPeriod + kSkew, 2 * (kPeriod + kSkew)};
+        // Free room behind the fp32 arrays of lanes 0 and 1 (up to the next lane's start) takes
+        // 16-bit arrays; whatever does not fit follows lane 2.
+        size_t room_at[3] = {lane[0] + lane_used, lane[1] + lane_used, lane[2] + lane_used};
+        const size_t room_end[2] = {lane[1], lane[2]};
+        size_t which = 0;
+        auto take_narrow = [&]() {
+            while (which < 2 && room_at[which] + narrow > room_end[which]) ++which;
+            const size_t at = room_at[which];
+            room_at[which] += narrow;
+            return at;
+        };
+        for (size_t j = 0; j < count; ++j) {
+            lohan_block_offsets_t &o = offsets[first + j];
+            o.param_fp32 = group_base + lane[0] + j * wide;
+            o.exp_avg = group_base + lane[1] + j * wide;
+            o.exp_avg_sq = group_base + lane[2] + j * wide;
+            o.grad_fp16 = group_base + take_narrow();
+            o.param_bf16 = group_base + take_narrow();
+        }
+        group_base += room_at[2];                 // lane 2 and what follows it end the group
+    }
+    *slab_bytes = group_base;
+    return LOHAN_OK;
+}
+
 float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm)
 {
     if (!(sqnorm >= 0.0) || !std::isfinite(sqnorm) || !finite_pos(loss_scale) ||

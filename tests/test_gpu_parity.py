@@ -657,3 +657,49 @@ def test_step_can_be_captured_in_a_hip_graph(oracle):
         warm.norm(wl.loss_scale)
         torch.cuda.synchronize()
     assert float(scratch[0].cpu()) == 3.0
+
+
+def test_13b_blocks_in_the_library_placement(oracle):
+    """The layout bench.py times: a full group of 13B-shaped blocks inside one slab at the offsets
+    lohan_model_placement gives (fp32 arrays in three lanes one 4 GiB period + 1 MiB apart).  All
+    blocks are stepped; block 0 is compared with the oracle over every element, the others on
+    sampled ranges -- an overlap between any two arrays would corrupt one of them."""
+    wl = synth.WORKLOADS["gpt13b"]
+    n = wl.n
+    group = 3
+    offsets, slab_bytes, align = lohan.lohan_model_placement(n, group)
+    slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=DEV)
+    start = (-slab.data_ptr()) % align
+    fields = {"p": "param_fp32", "m": "exp_avg", "v": "exp_avg_sq", "g": "grad_fp16",
+              "p16": "param_bf16"}
+    blocks = []
+    for b in range(group):
+        src = synth.make_block(wl, seed=40 + b, device=DEV)
+        placed = {}
+        for k, field in fields.items():
+            off = start + offsets[b][field]
+            placed[k] = slab[off: off + n * src[k].element_size()].view(src[k].dtype)
+            placed[k].copy_(src[k])
+        blocks.append(DeviceBlock(placed))
+        del src
+    assert blocks[0].m.data_ptr() - blocks[0].p.data_ptr() == (4 << 30) + (1 << 20)
+    assert blocks[0].v.data_ptr() - blocks[0].m.data_ptr() == (4 << 30) + (1 << 20)
+    span = 1 << 21
+    rng = np.random.default_rng(17)
+    starts = [0, n - span] + [int(x) for x in rng.integers(span, n - 2 * span, size=2)]
+    full0 = blocks[0].host()
+    before = [None] + [{s: blk.host(s, s + span) for s in starts} for blk in blocks[1:]]
+    hy = wl.hyper()
+    for blk in blocks:
+        assert gpu_steps(blk, hy, 2) == [0, 0]
+    say("[placement] oracle on block 0")
+    assert oracle_steps(oracle, full0, hy, 2) == [0, 0]
+    worst = assert_state_parity(blocks[0].host(), full0, what="library placement, block 0")
+    assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
+    for b in (1, 2):
+        for s in starts:
+            host = before[b][s]
+            assert oracle_steps(oracle, host, hy, 2, nthreads=8) == [0, 0]
+            worst = assert_state_parity(blocks[b].host(s, s + span), host,
+                                        what=f"library placement, block {b} range {s}")
+            assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
