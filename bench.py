@@ -107,26 +107,29 @@ def cpu_baseline(block, wl, sample_elems=1 << 27):
     }
 
 
-def place_block(block, n, torch, lohan):
-    """Move a block's five tensors into one slab at the offsets lohan_model_placement gives for
-    the first block of a full group of such blocks (the layout a framework holding the whole
-    model would use).  Returns (views, slab, description)."""
+def placed_views(n, torch, lohan, dev):
+    """One slab with room for a full group of n-element blocks at the offsets
+    lohan_model_placement gives (the layout a framework holding the whole model would use), and
+    views of block 0's five arrays in it.  Allocate it before anything else, as a framework
+    would: a slab carved out of fresh memory keeps the lanes' relative position physically.
+    Returns (views, slab, description)."""
     gib, mib = 1 << 30, 1 << 20
     wide = (4 * n + 2 * mib - 1) // (2 * mib) * (2 * mib)
     group = max(1, (4 * gib - 2 * mib) // wide) if 256 * mib <= wide <= 4 * gib - 2 * mib else 1
     offsets, slab_bytes, align = lohan.lohan_model_placement(n, group)
-    slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=block["p"].device)
+    slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=dev)
     start = (-slab.data_ptr()) % align
-    names = {"p": "param_fp32", "m": "exp_avg", "v": "exp_avg_sq", "g": "grad_fp16",
-             "p16": "param_bf16"}
-    placed = {}
-    for k, field in names.items():
+    spec = {"p": ("param_fp32", torch.float32), "m": ("exp_avg", torch.float32),
+            "v": ("exp_avg_sq", torch.float32), "g": ("grad_fp16", torch.float16),
+            "p16": ("param_bf16", torch.bfloat16)}
+    views = {}
+    for k, (field, dtype) in spec.items():
         off = start + offsets[0][field]
-        placed[k] = slab[off: off + n * block[k].element_size()].view(block[k].dtype)
-        placed[k].copy_(block[k])
+        nbytes = n * torch.empty(0, dtype=dtype).element_size()
+        views[k] = slab[off: off + nbytes].view(dtype)
     what = (f"block 0 of a {group}-block group laid out by lohan_model_placement "
             f"({slab_bytes / gib:.2f} GiB slab)")
-    return placed, slab, what
+    return views, slab, what
 
 
 def adam_kernel_only_ms(block, wl, torch, lohan, reps):
@@ -154,16 +157,18 @@ def adam_kernel_only_ms(block, wl, torch, lohan, reps):
 def bench_block(args, torch, lohan, synth):
     wl = synth.WORKLOADS[args.workload]
     dev = "cuda:0"
-    block = synth.make_block(wl, seed=0, device=dev)
     n = wl.n
     placement = "five separate allocations of torch's caching allocator"
     allocator_ms = None
     if args.placement == "library":
+        views, slab, placement = placed_views(n, torch, lohan, dev)
+    block = synth.make_block(wl, seed=0, device=dev)
+    if args.placement == "library":
         if args.compare_allocator:
             allocator_ms = adam_kernel_only_ms(block, wl, torch, lohan, min(args.steps, 20))
-        original = block
-        block, slab, placement = place_block(original, n, torch, lohan)
-        del original
+        for k in views:
+            views[k].copy_(block[k])
+        block = views
         torch.cuda.empty_cache()
     flag = torch.zeros(1, dtype=torch.int32, device=dev)
     sqnorm = torch.zeros(1, dtype=torch.float64, device=dev)
@@ -480,14 +485,16 @@ def bench_shapes(args, torch, lohan, synth):
     ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
     rows = []
     for wl in synth.shape_workloads():
-        block = synth.make_block(wl, seed=0, device=dev)
         n = wl.n
+        if args.placement == "library":
+            views, slab, _ = placed_views(n, torch, lohan, dev)
+        block = synth.make_block(wl, seed=0, device=dev)
         hy = wl.hyper()
         reps = max(3, min(args.steps, int(2e10 // n)))
         if args.placement == "library":
-            original = block
-            block, slab, _ = place_block(original, n, torch, lohan)
-            del original
+            for k in views:
+                views[k].copy_(block[k])
+            block = views
             torch.cuda.empty_cache()
 
         def one_step(t, ev=None):
@@ -520,7 +527,7 @@ def bench_shapes(args, torch, lohan, synth):
                      "adam_kernel_frac_of_peak": ADAM_BYTES_PER_ELEM * n / adam_ms / 1e6 /
                                                  HBM_PEAK_GBPS})
         del block
-        slab = None
+        views = slab = None
         torch.cuda.empty_cache()
     total = sum(r["elements"] for r in rows)
     total_s = sum(r["ms_per_step"] for r in rows) / 1e3
