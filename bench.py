@@ -57,7 +57,7 @@ def parse_args():
                     help="also time the update kernel on the five separate torch allocations "
                          "before the block is moved into the library's placement")
     ap.add_argument("--placement", choices=["library", "allocator"], default="library",
-                    help="gpt13b/gpt175b/gpt_h768/shapes: where the block's five arrays sit -- at "
+                    help="gpt13b/gpt175b/gpt_h768/shapes/models: where the blocks' arrays sit -- at "
                          "the offsets lohan_model_placement gives inside one slab (default), or "
                          "in five separate torch allocations")
     ap.add_argument("--blocks", type=int, default=None,
@@ -560,7 +560,27 @@ def bench_models(args, torch, lohan, synth):
     for name, layers, n in models:
         wl = synth.Workload(name, n, 100, 65536.0, False)
         hy = wl.hyper()
-        blocks = [synth.make_block(wl, seed=i, device=dev) for i in range(layers)]
+        if args.placement == "library":
+            # the whole model in one slab, every block where lohan_model_placement puts it
+            offsets, slab_bytes, align = lohan.lohan_model_placement(n, layers)
+            slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=dev)
+            start = (-slab.data_ptr()) % align
+            spec = {"p": ("param_fp32", torch.float32, 4), "m": ("exp_avg", torch.float32, 4),
+                    "v": ("exp_avg_sq", torch.float32, 4), "g": ("grad_fp16", torch.float16, 2),
+                    "p16": ("param_bf16", torch.bfloat16, 2)}
+            blocks = []
+            for i in range(layers):
+                src = synth.make_block(wl, seed=i, device=dev)
+                views = {}
+                for k, (field, dtype, width) in spec.items():
+                    off = start + offsets[i][field]
+                    views[k] = slab[off: off + n * width].view(dtype)
+                    views[k].copy_(src[k])
+                blocks.append(views)
+                del src
+        else:
+            slab = None
+            blocks = [synth.make_block(wl, seed=i, device=dev) for i in range(layers)]
         flags = torch.zeros(layers, dtype=torch.int32, device=dev)
         norms = torch.zeros(layers, dtype=torch.float64, device=dev)
         ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
@@ -603,7 +623,7 @@ def bench_models(args, torch, lohan, synth):
                      "multi_block_call_step_hbm_gbps":
                          (ADAM_BYTES_PER_ELEM + REDUCE_BYTES_PER_ELEM) * total / t_multi / 1e9,
                      "speedup": t_blk / t_multi})
-        del blocks, array
+        del blocks, array, slab
         torch.cuda.empty_cache()
     total = sum(r["blocks"] * r["elements_per_block"] for r in rows)
     total_s = sum(r["multi_block_call_ms"] for r in rows) / 1e3
