@@ -113,10 +113,8 @@ def placed_views(n, torch, lohan, dev):
     views of block 0's five arrays in it.  Allocate it before anything else, as a framework
     would: a slab carved out of fresh memory keeps the lanes' relative position physically.
     Returns (views, slab, description)."""
-    gib, mib = 1 << 30, 1 << 20
-    wide = (4 * n + 2 * mib - 1) // (2 * mib) * (2 * mib)
-    group = max(1, (4 * gib - 2 * mib) // wide) if 256 * mib <= wide <= 4 * gib - 2 * mib else 1
-    offsets, slab_bytes, align = lohan.lohan_model_placement(n, group)
+    gib = 1 << 30
+    offsets, slab_bytes, align, group = lohan.lohan_model_placement(n)     # one full group
     slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=dev)
     start = (-slab.data_ptr()) % align
     spec = {"p": ("param_fp32", torch.float32), "m": ("exp_avg", torch.float32),
@@ -562,7 +560,7 @@ def bench_models(args, torch, lohan, synth):
         hy = wl.hyper()
         if args.placement == "library":
             # the whole model in one slab, every block where lohan_model_placement puts it
-            offsets, slab_bytes, align = lohan.lohan_model_placement(n, layers)
+            offsets, slab_bytes, align, _ = lohan.lohan_model_placement(n, layers)
             slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=dev)
             start = (-slab.data_ptr()) % align
             spec = {"p": ("param_fp32", torch.float32, 4), "m": ("exp_avg", torch.float32, 4),

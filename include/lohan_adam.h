@@ -228,24 +228,28 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
  * Host-only placement advice (pure arithmetic, touches no device).  Where the fp32 arrays of a
  * block sit relative to each other moves the update kernel by several percent on MI355X: p, m
  * and v advance at the same rate, so their relative position is fixed for a whole launch, and
- * the measured best is "same offset within consecutive 4 GiB periods, shifted by 1 MiB each";
- * the allocator's placement is a lottery between -4 % and 0 % of that (measurements in the
- * design notes).  This function lays out the tensors of Table II for num_blocks equal blocks of
- * n elements inside ONE caller-allocated slab accordingly:
- *   - groups of G = floor((4 GiB - 2 MiB) / bytes(p)) consecutive blocks share three "lanes":
- *     lane 0 holds their p arrays back to back, lane 1 (at +4 GiB + 1 MiB) their m arrays, lane 2
- *     (at +8 GiB + 2 MiB) their v arrays, block j of the group at the same offset in each lane;
+ * the measured best is "same offset within consecutive periods of 4 GiB (or 12 GiB), shifted by
+ * 1 MiB each"; the allocator's placement is a lottery between -4 % and 0 % of that (measurements
+ * in the design notes).  This function lays out the tensors of Table II for num_blocks equal
+ * blocks of n elements inside ONE caller-allocated slab accordingly:
+ *   - the period P is 4 GiB if one fp32 array fits into 4 GiB - 2 MiB, else 12 GiB if it fits
+ *     into 12 GiB - 2 MiB;
+ *   - groups of G = floor((P - 2 MiB) / bytes(p)) consecutive blocks share three "lanes":
+ *     lane 0 holds their p arrays back to back, lane 1 (at +P + 1 MiB) their m arrays, lane 2
+ *     (at +2P + 2 MiB) their v arrays, block j of the group at the same offset in each lane;
  *   - the 16-bit arrays (which advance at half the rate and may sit anywhere) fill what is left
  *     of lanes 0 and 1 where they fit and otherwise follow lane 2;
- *   - blocks whose fp32 arrays exceed one period (more than ~1.07e9 elements) or stay below
+ *   - blocks whose fp32 arrays fit neither period (3.2e9 elements and more) or stay below
  *     256 MiB (fewer than 2^26 elements) are simply packed block by block: p, m, v, g, p16 back
- *     to back (no placement measured better for the former; under 1 % to gain for the latter).
+ *     to back (nothing measured better for the former; under 1 % to gain for the latter).
  * Every array starts on a 1 MiB boundary relative to the slab base; the base itself needs
  * *slab_alignment (2 MiB).  The price is unused space in lanes 0 and 1: per full group 3 % of the
- * slab for 6B-shaped blocks, 7 % for 13B, 12 % for 30B, 17 % for 70B, and more for a last group
- * that is not full -- compare *slab_bytes with 16 * n * num_blocks and decide.
+ * slab for 6B-shaped blocks, 7 % for 13B, 12 % for 30B, 17 % for 70B, 4 % for 135B, 14 % for 175B,
+ * 15 % for 276B, and more for a last group that is not full -- compare *slab_bytes with
+ * 16 * n * num_blocks and decide.
  *   offsets        host, out: num_blocks entries of byte offsets from the slab base
  *   slab_bytes, slab_alignment   host, out
+ *   blocks_per_group   host, out, may be NULL: G (1 when the blocks are packed)
  * LOHAN_ERR_NULL for NULL outputs (offsets may be NULL only if num_blocks == 0), LOHAN_ERR_ARG
  * if n exceeds 2^40.
  */
@@ -255,7 +259,7 @@ typedef struct {
 
 lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
                                      lohan_block_offsets_t *offsets, size_t *slab_bytes,
-                                     size_t *slab_alignment);
+                                     size_t *slab_alignment, uint32_t *blocks_per_group);
 
 /*
  * Host-only helper for per-block gradient-norm clipping: returns the loss scale to hand to

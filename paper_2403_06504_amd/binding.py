@@ -113,7 +113,8 @@ def load_library():
                                                 vp, ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_multi_block_step.restype = ctypes.c_int
     lib.lohan_model_placement.argtypes = [u64, ctypes.c_uint32, ctypes.POINTER(LohanBlockOffsets),
-                                          ctypes.POINTER(sz), ctypes.POINTER(sz)]
+                                          ctypes.POINTER(sz), ctypes.POINTER(sz),
+                                          ctypes.POINTER(ctypes.c_uint32)]
     lib.lohan_model_placement.restype = ctypes.c_int
     lib.lohan_clip_loss_scale.argtypes = [ctypes.c_double, f32, f32]
     lib.lohan_clip_loss_scale.restype = f32
@@ -302,16 +303,23 @@ def lohan_adam_multi_block_step(blocks, lr, beta1, beta2, eps, weight_decay, ste
         _addr(sqnorms, num_blocks, _F64, "sqnorms"), int(flags), ws, ws_bytes, _stream(stream)))
 
 
-def lohan_model_placement(n, num_blocks):
-    """Returns (offsets, slab_bytes, slab_alignment); offsets is a list of dicts with the byte
-    offsets of param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16 for each block."""
-    arr = (LohanBlockOffsets * max(1, num_blocks))()
+def lohan_model_placement(n, num_blocks=None):
+    """Returns (offsets, slab_bytes, slab_alignment, blocks_per_group); offsets is a list of dicts
+    with the byte offsets of param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16 for each
+    block.  num_blocks=None lays out exactly one full group."""
+    lib = load_library()
+    group = ctypes.c_uint32()
     total, align = ctypes.c_size_t(), ctypes.c_size_t()
-    _check(load_library().lohan_model_placement(int(n), int(num_blocks), arr, ctypes.byref(total),
-                                                ctypes.byref(align)))
+    if num_blocks is None:
+        _check(lib.lohan_model_placement(int(n), 0, None, ctypes.byref(total),
+                                         ctypes.byref(align), ctypes.byref(group)))
+        num_blocks = group.value
+    arr = (LohanBlockOffsets * max(1, num_blocks))()
+    _check(lib.lohan_model_placement(int(n), int(num_blocks), arr, ctypes.byref(total),
+                                     ctypes.byref(align), ctypes.byref(group)))
     fields = [f for f, _ in LohanBlockOffsets._fields_]
     return ([{f: getattr(arr[b], f) for f in fields} for b in range(num_blocks)], total.value,
-            align.value)
+            align.value, group.value)
 
 
 def lohan_clip_loss_scale(sqnorm, loss_scale, max_norm) -> float:

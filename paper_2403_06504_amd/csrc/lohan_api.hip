@@ -365,11 +365,13 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
 
 lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
                                      lohan_block_offsets_t *offsets, size_t *slab_bytes,
-                                     size_t *slab_alignment)
+                                     size_t *slab_alignment, uint32_t *blocks_per_group)
 {
     constexpr size_t kGranule = 2ull << 20;       // array sizes are rounded up to this
-    constexpr size_t kPeriod = 4ull << 30;        // lanes are one period apart ...
-    constexpr size_t kSkew = 1ull << 20;          // ... plus this shift per lane
+    constexpr size_t kSkew = 1ull << 20;          // lanes are one period plus this apart
+    constexpr size_t kSmallest = 256ull << 20;    // below this the placement gains under 1 %
+    // Lane periods that measured well; a block uses the first one its fp32 arrays fit into.
+    constexpr size_t kPeriods[2] = {4ull << 30, 12ull << 30};
     if (slab_bytes == nullptr || slab_alignment == nullptr ||
         (offsets == nullptr && num_blocks != 0))
         return LOHAN_ERR_NULL;
@@ -379,8 +381,12 @@ lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
     const size_t narrow = round_up((size_t)n * 2, kGranule);    // one 16-bit array
     *slab_alignment = kGranule;
 
-    constexpr size_t kSmallest = 256ull << 20;    // below this the placement gains under 1 %
-    if (wide > kPeriod - kGranule || wide < kSmallest) {      // plain block-major packing
+    size_t period = 0;
+    if (wide >= kSmallest)
+        for (size_t candidate : kPeriods)
+            if (period == 0 && wide <= candidate - kGranule) period = candidate;
+
+    if (period == 0) {                            // plain block-major packing
         const size_t block_bytes = 3 * wide + 2 * narrow;
         for (uint32_t b = 0; b < num_blocks; ++b) {
             const size_t base = (size_t)b * block_bytes;
@@ -388,15 +394,17 @@ lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
                                                base + 3 * wide, base + 3 * wide + narrow};
         }
         *slab_bytes = (size_t)num_blocks * block_bytes;
+        if (blocks_per_group != nullptr) *blocks_per_group = 1;
         return LOHAN_OK;
     }
 
-    const size_t per_group = (kPeriod - kGranule) / wide;
+    const size_t per_group = (period - kGranule) / wide;
+    if (blocks_per_group != nullptr) *blocks_per_group = (uint32_t)per_group;
     size_t group_base = 0;
     for (uint32_t first = 0; first < num_blocks; first += (uint32_t)per_group) {
         const size_t count = num_blocks - first < per_group ? num_blocks - first : per_group;
         const size_t lane_used = count * wide;
-        const size_t lane[3] = {0, kPeriod + kSkew, 2 * (kPeriod + kSkew)};
+        const size_t lane[3] = {0, period + kSkew, 2 * (period + kSkew)};
         // Free room behind the fp32 arrays of lanes 0 and 1 (up to the next lane's start) takes
         // 16-bit arrays; whatever does not fit follows lane 2.
         size_t room_at[3] = {lane[0] + lane_used, lane[1] + lane_used, lane[2] + lane_used};

@@ -190,14 +190,16 @@ def test_multi_block_step_validation_returns_before_any_launch(lib):
 
 def test_model_placement_properties(lib):
     """No two arrays overlap, every array starts on a 1 MiB boundary inside the slab, and for
-    blocks between 256 MiB and one 4 GiB period per fp32 array the three fp32 arrays of a block
-    sit at the same offset in consecutive periods, 1 MiB apart."""
+    blocks whose fp32 arrays fit a 4 GiB (else a 12 GiB) period and are not below 256 MiB the
+    three fp32 arrays of a block sit at the same offset in consecutive periods, 1 MiB apart."""
     gib, mib = 1 << 30, 1 << 20
     cases = [(12 * 5120 ** 2, 40), (12 * 5120 ** 2, 4), (12 * 4096 ** 2, 7), (12 * 7168 ** 2, 2),
-             (12 * 8192 ** 2, 1), (12 * 12288 ** 2, 2), (18 * 1536 ** 2, 30), (7, 3), (0, 2),
-             (1 << 26, 5), ((1 << 26) - 1, 5), ((1 << 30) - (1 << 19), 2), ((1 << 30), 2)]
+             (12 * 8192 ** 2, 1), (12 * 11264 ** 2, 3), (12 * 12288 ** 2, 2), (12 * 14336 ** 2, 2),
+             (12 * 16384 ** 2, 2), (18 * 1536 ** 2, 30), (7, 3), (0, 2), (1 << 26, 5),
+             ((1 << 26) - 1, 5), ((1 << 30) - (1 << 19), 2), ((1 << 30), 2),
+             (3 * (1 << 30) - (1 << 19), 2), (3 * (1 << 30), 2)]
     for n, nb in cases:
-        offs, total, align = lohan.lohan_model_placement(n, nb)
+        offs, total, align, per_group = lohan.lohan_model_placement(n, nb)
         assert align == 2 * mib and len(offs) == nb
         spans = []
         for o in offs:
@@ -210,28 +212,38 @@ def test_model_placement_properties(lib):
         for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
             assert a1 <= b0, (n, nb, a0, a1, b0, b1)
         wide = (4 * n + 2 * mib - 1) // (2 * mib) * (2 * mib)
-        phased = 256 * mib <= wide <= 4 * gib - 2 * mib
+        narrow = (2 * n + 2 * mib - 1) // (2 * mib) * (2 * mib)
+        period = 0
+        if wide >= 256 * mib:
+            period = 4 * gib if wide <= 4 * gib - 2 * mib else \
+                12 * gib if wide <= 12 * gib - 2 * mib else 0
         for o in offs:
-            if phased:
-                assert o["exp_avg"] - o["param_fp32"] == 4 * gib + mib
-                assert o["exp_avg_sq"] - o["exp_avg"] == 4 * gib + mib
-            else:
-                assert o["exp_avg"] - o["param_fp32"] == wide
-                assert o["exp_avg_sq"] - o["exp_avg"] == wide
-        if not phased:
-            assert total == nb * (3 * wide + 2 * ((2 * n + 2 * mib - 1) // (2 * mib) * (2 * mib)))
+            lane = period + mib if period else wide
+            assert o["exp_avg"] - o["param_fp32"] == lane
+            assert o["exp_avg_sq"] - o["exp_avg"] == lane
+        if period:
+            assert per_group == (period - 2 * mib) // wide >= 1
+            first = offs[0]["param_fp32"]
+            for j, o in enumerate(offs[:per_group]):          # block j at j arrays into lane 0
+                assert o["param_fp32"] - first == j * wide
+        else:
+            assert per_group == 1 and total == nb * (3 * wide + 2 * narrow)
     # the documented price of full groups
-    for n, per_group, worst in ((12 * 4096 ** 2, 5, 1.04), (12 * 5120 ** 2, 3, 1.07),
-                                (12 * 7168 ** 2, 1, 1.13), (12 * 8192 ** 2, 1, 1.17)):
-        _, total, _ = lohan.lohan_model_placement(n, per_group)
-        assert 1.0 <= total / (16 * n * per_group) <= worst
+    for n, worst in ((12 * 4096 ** 2, 1.04), (12 * 5120 ** 2, 1.07), (12 * 7168 ** 2, 1.13),
+                     (12 * 8192 ** 2, 1.17), (12 * 11264 ** 2, 1.05), (12 * 12288 ** 2, 1.14),
+                     (12 * 14336 ** 2, 1.16)):
+        offs, total, _, per_group = lohan.lohan_model_placement(n)
+        assert len(offs) == per_group
+        assert 1.0 <= total / (16 * n * per_group) <= worst, (n, total / (16 * n * per_group))
     assert lohan.lohan_model_placement(5, 0)[1] == 0
     total, align = ctypes.c_size_t(), ctypes.c_size_t()
-    assert lib.lohan_model_placement(8, 1, None, ctypes.byref(total), ctypes.byref(align)) == 1
+    assert lib.lohan_model_placement(8, 1, None, ctypes.byref(total), ctypes.byref(align),
+                                     None) == 1
     one = (binding.LohanBlockOffsets * 1)()
-    assert lib.lohan_model_placement(8, 1, one, None, ctypes.byref(align)) == 1
+    assert lib.lohan_model_placement(8, 1, one, None, ctypes.byref(align), None) == 1
+    assert lib.lohan_model_placement(8, 1, one, ctypes.byref(total), None, None) == 1
     assert lib.lohan_model_placement((1 << 40) + 1, 1, one, ctypes.byref(total),
-                                     ctypes.byref(align)) == 3
+                                     ctypes.byref(align), None) == 3
 
 
 def test_offload_create_validation_touches_no_device(lib):

@@ -666,8 +666,8 @@ def test_13b_blocks_in_the_library_placement(oracle):
     sampled ranges -- an overlap between any two arrays would corrupt one of them."""
     wl = synth.WORKLOADS["gpt13b"]
     n = wl.n
-    group = 3
-    offsets, slab_bytes, align = lohan.lohan_model_placement(n, group)
+    offsets, slab_bytes, align, group = lohan.lohan_model_placement(n)
+    assert group == 3
     slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=DEV)
     start = (-slab.data_ptr()) % align
     fields = {"p": "param_fp32", "m": "exp_avg", "v": "exp_avg_sq", "g": "grad_fp16",
