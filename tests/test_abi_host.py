@@ -263,6 +263,31 @@ def test_offload_create_validation_touches_no_device(lib):
     assert lib.lohan_offload_submit(None, None, 0, 0, 0, 0, 0, 1, 1, 0, 0, None) == 1
 
 
+def test_plain_c_client_builds_and_runs(lib, tmp_path):
+    """Both headers compile as C11 with -Wall -Wextra -Werror, and a C program linked against the
+    library gets the documented answers from the host-only entry points."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    exe = tmp_path / "c_abi_client"
+    libdir = os.path.dirname(lohan.library_path())
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
+                    "-I/opt/rocm/include", "-I" + os.path.join(ROOT, "include"), "-o", str(exe),
+                    os.path.join(ROOT, "tests", "c_abi_client.c"), "-L" + libdir,
+                    "-l:" + os.path.basename(lohan.library_path()), "-Wl,-rpath," + libdir,
+                    "-Wl,-rpath,/opt/rocm/lib", "-lm"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    lines = dict(line.split(" ", 1) for line in out.strip().splitlines())
+    assert int(lines["workspace_bytes"]) == lohan.lohan_workspace_bytes()
+    assert lines["status_3"] == lohan.lohan_status_string(3)
+    assert lines["clip"] == "2346.2798"
+    assert lines["placement"] == f"0 group 3 lane {(4 << 30) + (1 << 20)} align {2 << 20}"
+    assert lines["null_step"] == "1"
+    assert lines["plan"] == "0 n 2 first 1 a 30.0 f 100.0 t 19.00"
+    assert lines["flops"] == "0 200.0 -10.0"
+
+
 def test_binding_raises_with_status(lib):
     with pytest.raises(lohan.LohanError) as e:
         lohan.lohan_adam_block_step(A, A * 2, A * 3, A * 4, A * 5, 16, 1e-4, 0.9, 0.999, 1e-8,
