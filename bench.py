@@ -10,7 +10,7 @@ Adam-updated elements per second; the roofline object prices the dominant kernel
 recorded on the launch stream inside the timed region.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt13b|gpt175b|gpt_h768|
-                     stream13b|offload13b|shapes|models|gpt13b_oop|gpt175b_oop]
+                     stream13b|offload13b|shapes|models|gpt13b_oop|gpt175b_oop|ring13b]
 
 The *_oop workloads time lohan_adam_block_step_out_of_place instead: the overflow test fused into
 a single 28 B/element pass between two sets of state (not the default: it doubles the state).
@@ -47,7 +47,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="gpt13b",
                     choices=["gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b", "shapes",
-                             "gpt13b_oop", "gpt175b_oop", "models"])
+                             "gpt13b_oop", "gpt175b_oop", "models", "ring13b"])
     ap.add_argument("--variant", type=int, default=None, help="kernel launch-shape override")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--waves-per-cu", type=int, default=-1,
@@ -61,7 +61,8 @@ def parse_args():
                          "the offsets lohan_model_placement gives inside one slab (default), or "
                          "in five separate torch allocations")
     ap.add_argument("--blocks", type=int, default=None,
-                    help="stream13b: number of blocks (default 40); offload13b: default 6")
+                    help="stream13b: number of blocks (default 40); offload13b: default 6; "
+                         "ring13b: default 8")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the steps, so that a "
                          "rocprofv3 --pmc run of this command holds a kernel of known traffic")
@@ -296,6 +297,85 @@ def bench_block_oop(args, torch, lohan, synth):
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "avg_launch_ms": call_ms, "median_launch_ms": all_ms[len(all_ms) // 2],
+                     "min_launch_ms": all_ms[0],
+                     "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
+        "cpu_baseline": None,
+    }
+
+
+def bench_ring(args, torch, lohan, synth):
+    """Eight 13B-shaped blocks in nine slots (lohan_ring_*): every step is one single-pass
+    out-of-place update from the block's slot into the spare slot, committed on the device.  A
+    "step" is one block; the blocks are taken round robin, highest index first."""
+    wl = synth.WORKLOADS["gpt13b"]
+    dev = "cuda:0"
+    n, nblocks = wl.n, args.blocks or 8
+    offsets, slab_bytes, align, _ = lohan.lohan_model_placement(n, nblocks + 1)
+    slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=dev)
+    start = (-slab.data_ptr()) % align
+
+    def view(slot, field, dtype, width):
+        off = start + offsets[slot][field]
+        return slab[off: off + n * width].view(dtype)
+
+    slots, grads = [], []
+    for s_ in range(nblocks + 1):
+        slot = (view(s_, "param_fp32", torch.float32, 4), view(s_, "exp_avg", torch.float32, 4),
+                view(s_, "exp_avg_sq", torch.float32, 4), view(s_, "param_bf16", torch.bfloat16, 2))
+        slots.append(slot)
+        if s_ < nblocks:
+            src = synth.make_block(wl, seed=s_, device=dev)
+            for dst, k in zip(slot, ("p", "m", "v", "p16")):
+                dst.copy_(src[k])
+            g = view(s_, "grad_fp16", torch.float16, 2)
+            g.copy_(src["g"])
+            grads.append(g)
+            del src
+    ring = torch.empty(lohan.lohan_ring_bytes(nblocks), dtype=torch.uint8, device=dev)
+    lohan.lohan_ring_init(ring, slots, n)
+    hy = wl.hyper()
+
+    def one_step(k):
+        b = nblocks - 1 - (k % nblocks)
+        lohan.lohan_ring_adam_block_step(ring, nblocks, b, grads[b], n, hy["lr"], hy["beta1"],
+                                         hy["beta2"], hy["eps"], hy["weight_decay"],
+                                         hy["step"] + k // nblocks, hy["loss_scale"], 0)
+
+    for w in range(args.warmup):
+        one_step(w)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        events[k][0].record()
+        one_step(args.warmup + k)
+        events[k][1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    slot_of, spare, skipped = lohan.lohan_ring_read(ring, nblocks)
+    assert skipped == [0] * nblocks, "synthetic gradients must not overflow"
+    assert sorted(slot_of + [spare]) == list(range(nblocks + 1))
+    all_ms = sorted(e[0].elapsed_time(e[1]) for e in events)
+    call_ms = sum(all_ms) / args.steps
+    achieved = ADAM_BYTES_PER_ELEM * n / (call_ms * 1e-3) / 1e9
+    return {
+        "metric": "adam_updated_elements_per_sec",
+        "value": n / (elapsed / args.steps), "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"ring13b: {nblocks} blocks of n={n} elements in {nblocks + 1} "
+                               "slots, single-pass out-of-place steps committed on the device",
+                   "elements": n, "bytes_per_element_step": 28,
+                   "extra_state_fraction": 1.0 / nblocks,
+                   "launch_config": list(lohan.lohan_get_launch_config())},
+        "step_hbm_gbps": ADAM_BYTES_PER_ELEM * n / (elapsed / args.steps) / 1e9,
+        "roofline": {"kernel": "k_adam_ring_step (events also span the one-lane commit)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "avg_launch_ms": call_ms, "median_launch_ms": all_ms[len(all_ms) // 2],
                      "min_launch_ms": all_ms[0],
                      "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
@@ -671,6 +751,8 @@ def main():
         out = bench_shapes(args, torch, lohan, synth)
     elif args.workload == "models":
         out = bench_models(args, torch, lohan, synth)
+    elif args.workload == "ring13b":
+        out = bench_ring(args, torch, lohan, synth)
     elif args.workload.endswith("_oop"):
         out = bench_block_oop(args, torch, lohan, synth)
     else:

@@ -184,6 +184,51 @@ lohan_status_t lohan_adam_block_step_out_of_place(
     hipStream_t stream);
 
 /*
+ * Ring form of the out-of-place step: single-pass (28 bytes per element) updates for a whole
+ * model at the price of ONE spare block of state instead of a second copy of everything.
+ * A model of B equal blocks lives in B + 1 slots; a slot holds the P32, the two OS32 moments and
+ * the P16 copy of one block (Table II).  The step of block b (the "CPU Compute" step of
+ * Sec. IV-C, with lohan_adam_block_step's arithmetic) reads the slot that currently holds b,
+ * writes the spare slot, and a one-lane kernel then makes the spare b's slot and b's old slot the
+ * new spare -- unless b's gradients held inf/NaN, in which case nothing changes hands and the old
+ * slot stays b's state, bit-identical.  Which slot holds which block is a table in DEVICE memory
+ * (the ring), read by the kernels themselves, so no host decision and no host synchronisation
+ * sits between the blocks of a backward pass.
+ *   ring        device memory of lohan_ring_bytes(B) bytes, 16-byte aligned, owned by the caller,
+ *               initialised once by lohan_ring_init and from then on changed only by the steps.
+ *               All steps of one ring must be enqueued on one stream (or otherwise ordered).
+ *   lohan_ring_init   copies the B + 1 slot descriptors (HOST array; block b starts in slot b,
+ *               slot B is the spare) into the ring with a synchronous copy.  Slot arrays: n
+ *               elements each, 16-byte aligned, not overlapping; LOHAN_ERR_NULL / _ALIGN per
+ *               slot, LOHAN_ERR_WORKSPACE if ring_bytes is too small, LOHAN_ERR_ARG if B is 0.
+ *   lohan_ring_adam_block_step   enqueues the step of `block` and its commit on `stream`;
+ *               allocates nothing, never synchronises.  Arguments as lohan_adam_block_step
+ *               (flags: LOHAN_FLAG_L2_MODE, LOHAN_FLAG_P16_FP16); block >= B -> LOHAN_ERR_ARG.
+ *               n == 0 does nothing.
+ *   lohan_ring_read   synchronises `stream`, then copies to the host (each output may be NULL):
+ *               slot_of[b] = the slot that holds block b, *spare = the spare slot, and
+ *               skipped[b] = 1 if the most recent step of block b found inf/NaN gradients and
+ *               was skipped, else 0 -- the overflow flag of lohan_adam_block_step: the caller
+ *               does not advance that block's step count.  The forward pass finds block b's P16
+ *               in slot slot_of[b].
+ */
+typedef struct {
+    float *param_fp32, *exp_avg, *exp_avg_sq;   /* device: n floats each */
+    void *param_16;                             /* device: n 16-bit values */
+} lohan_ring_slot_t;
+
+size_t lohan_ring_bytes(uint32_t num_blocks);
+lohan_status_t lohan_ring_init(void *ring, size_t ring_bytes, const lohan_ring_slot_t *slots,
+                               uint32_t num_blocks);
+lohan_status_t lohan_ring_adam_block_step(void *ring, uint32_t num_blocks, uint32_t block,
+                                          const void *grad_fp16, uint64_t n, float lr,
+                                          float beta1, float beta2, float eps,
+                                          float weight_decay, int64_t step, float loss_scale,
+                                          uint32_t flags, hipStream_t stream);
+lohan_status_t lohan_ring_read(const void *ring, uint32_t num_blocks, uint32_t *slot_of,
+                               uint32_t *spare, uint32_t *skipped, hipStream_t stream);
+
+/*
  * One block of a multi-block call: the tensors of Table II for that block, as the arguments of
  * lohan_adam_block_step (same layout, alignment and aliasing rules).
  */

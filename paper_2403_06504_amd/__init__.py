@@ -28,6 +28,10 @@ from .binding import (  # noqa: F401
     lohan_adam_block_step_out_of_place,
     lohan_adam_multi_block_step,
     lohan_model_placement,
+    lohan_ring_adam_block_step,
+    lohan_ring_bytes,
+    lohan_ring_init,
+    lohan_ring_read,
     make_block_array,
     LohanBlock,
     lohan_clip_loss_scale,

@@ -23,6 +23,7 @@ EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
     "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
     "lohan_adam_block_step_out_of_place", "lohan_adam_multi_block_step", "lohan_model_placement",
+    "lohan_ring_bytes", "lohan_ring_init", "lohan_ring_adam_block_step", "lohan_ring_read",
     "lohan_clip_loss_scale",
     "lohan_set_launch_config", "lohan_get_launch_config",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
@@ -58,6 +59,12 @@ class LohanBlock(ctypes.Structure):
     _fields_ = [("param_fp32", ctypes.c_void_p), ("exp_avg", ctypes.c_void_p),
                 ("exp_avg_sq", ctypes.c_void_p), ("grad_fp16", ctypes.c_void_p),
                 ("param_bf16_out", ctypes.c_void_p), ("n", ctypes.c_uint64)]
+
+
+class LohanRingSlot(ctypes.Structure):
+    """Mirror of lohan_ring_slot_t."""
+    _fields_ = [("param_fp32", ctypes.c_void_p), ("exp_avg", ctypes.c_void_p),
+                ("exp_avg_sq", ctypes.c_void_p), ("param_16", ctypes.c_void_p)]
 
 
 class LohanBlockOffsets(ctypes.Structure):
@@ -112,6 +119,18 @@ def load_library():
                                                 f32, f32, f32, f32, ctypes.c_int64, f32, f32, vp,
                                                 vp, ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_multi_block_step.restype = ctypes.c_int
+    lib.lohan_ring_bytes.argtypes = [ctypes.c_uint32]
+    lib.lohan_ring_bytes.restype = sz
+    lib.lohan_ring_init.argtypes = [vp, sz, ctypes.POINTER(LohanRingSlot), ctypes.c_uint32]
+    lib.lohan_ring_init.restype = ctypes.c_int
+    lib.lohan_ring_adam_block_step.argtypes = [vp, ctypes.c_uint32, ctypes.c_uint32, vp, u64, f32,
+                                               f32, f32, f32, f32, ctypes.c_int64, f32,
+                                               ctypes.c_uint32, vp]
+    lib.lohan_ring_adam_block_step.restype = ctypes.c_int
+    lib.lohan_ring_read.argtypes = [vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32),
+                                    ctypes.POINTER(ctypes.c_uint32),
+                                    ctypes.POINTER(ctypes.c_uint32), vp]
+    lib.lohan_ring_read.restype = ctypes.c_int
     lib.lohan_model_placement.argtypes = [u64, ctypes.c_uint32, ctypes.POINTER(LohanBlockOffsets),
                                           ctypes.POINTER(sz), ctypes.POINTER(sz),
                                           ctypes.POINTER(ctypes.c_uint32)]
@@ -301,6 +320,43 @@ def lohan_adam_multi_block_step(blocks, lr, beta1, beta2, eps, weight_decay, ste
         float(weight_decay), int(step), float(loss_scale), float(max_norm),
         _addr(overflow_flags, num_blocks, _U32, "overflow_flags"),
         _addr(sqnorms, num_blocks, _F64, "sqnorms"), int(flags), ws, ws_bytes, _stream(stream)))
+
+
+def lohan_ring_bytes(num_blocks) -> int:
+    return int(load_library().lohan_ring_bytes(int(num_blocks)))
+
+
+def lohan_ring_init(ring, slots, n, ring_bytes=None):
+    """slots: sequence of num_blocks + 1 tuples (param_fp32, exp_avg, exp_avg_sq, param_16) of
+    tensors / addresses holding n elements each; `ring`: uint8 device tensor or address."""
+    num_blocks = len(slots) - 1
+    arr = (LohanRingSlot * len(slots))()
+    for i, (p, m, v, h) in enumerate(slots):
+        arr[i] = LohanRingSlot(_addr(p, n, _F32, "param_fp32"), _addr(m, n, _F32, "exp_avg"),
+                               _addr(v, n, _F32, "exp_avg_sq"), _addr(h, n, _BF16, "param_16"))
+    if ring_bytes is None:
+        ring_bytes = ring.numel() * ring.element_size() if hasattr(ring, "numel") else 0
+    _check(load_library().lohan_ring_init(_addr(ring, what="ring"), int(ring_bytes), arr,
+                                          int(num_blocks)))
+
+
+def lohan_ring_adam_block_step(ring, num_blocks, block, grad_fp16, n, lr, beta1, beta2, eps,
+                               weight_decay, step, loss_scale, flags=0, stream=None):
+    _check(load_library().lohan_ring_adam_block_step(
+        _addr(ring, what="ring"), int(num_blocks), int(block),
+        _addr(grad_fp16, n, _F16, "grad_fp16"), int(n), float(lr), float(beta1), float(beta2),
+        float(eps), float(weight_decay), int(step), float(loss_scale), int(flags),
+        _stream(stream)))
+
+
+def lohan_ring_read(ring, num_blocks, stream=None):
+    """Synchronises the stream.  Returns (slot_of list, spare, skipped list of 0/1)."""
+    slot_of = (ctypes.c_uint32 * num_blocks)()
+    last = (ctypes.c_uint32 * num_blocks)()
+    spare = ctypes.c_uint32()
+    _check(load_library().lohan_ring_read(_addr(ring, what="ring"), int(num_blocks), slot_of,
+                                          ctypes.byref(spare), last, _stream(stream)))
+    return list(slot_of), spare.value, list(last)
 
 
 def lohan_model_placement(n, num_blocks=None):

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdint>
 #include <limits>
+#include <vector>
 
 #include "lohan_adam.h"
 #include "lohan_kernels.h"
@@ -361,6 +362,91 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
         first += count;
     }
     return LOHAN_OK;
+}
+
+size_t lohan_ring_bytes(uint32_t num_blocks) { return lohan::ring_bytes(num_blocks); }
+
+lohan_status_t lohan_ring_init(void *ring, size_t ring_bytes, const lohan_ring_slot_t *slots,
+                               uint32_t num_blocks)
+{
+    if (ring == nullptr || slots == nullptr) return LOHAN_ERR_NULL;
+    if (misaligned(ring, 16)) return LOHAN_ERR_ALIGN;
+    if (num_blocks == 0 || num_blocks > (1u << 20)) return LOHAN_ERR_ARG;
+    if (ring_bytes < lohan::ring_bytes(num_blocks)) return LOHAN_ERR_WORKSPACE;
+    for (uint32_t i = 0; i <= num_blocks; ++i) {
+        const lohan_ring_slot_t &slot = slots[i];
+        if (slot.param_fp32 == nullptr || slot.exp_avg == nullptr || slot.exp_avg_sq == nullptr ||
+            slot.param_16 == nullptr)
+            return LOHAN_ERR_NULL;
+        if (misaligned(slot.param_fp32, 16) || misaligned(slot.exp_avg, 16) ||
+            misaligned(slot.exp_avg_sq, 16) || misaligned(slot.param_16, 16))
+            return LOHAN_ERR_ALIGN;
+    }
+    // Host image of the table: block b starts in slot b, the last slot is the spare.
+    const size_t bytes = lohan::ring_bytes(num_blocks);
+    std::vector<char> image(bytes, 0);
+    lohan::RingView view = lohan::ring_view(image.data(), num_blocks);
+    for (uint32_t i = 0; i <= num_blocks; ++i)
+        view.slots[i] = lohan::RingSlot{slots[i].param_fp32, slots[i].exp_avg,
+                                        slots[i].exp_avg_sq,
+                                        reinterpret_cast<uint16_t *>(slots[i].param_16)};
+    for (uint32_t b = 0; b < num_blocks; ++b) view.slot_of[b] = b;
+    *view.spare = num_blocks;
+    return hipMemcpy(ring, image.data(), bytes, hipMemcpyHostToDevice) == hipSuccess
+               ? LOHAN_OK
+               : LOHAN_ERR_HIP;
+}
+
+lohan_status_t lohan_ring_read(const void *ring, uint32_t num_blocks, uint32_t *slot_of,
+                               uint32_t *spare, uint32_t *skipped, hipStream_t stream)
+{
+    if (ring == nullptr) return LOHAN_ERR_NULL;
+    if (misaligned(ring, 16)) return LOHAN_ERR_ALIGN;
+    if (num_blocks == 0 || num_blocks > (1u << 20)) return LOHAN_ERR_ARG;
+    if (hipStreamSynchronize(stream) != hipSuccess) return LOHAN_ERR_HIP;
+    const lohan::RingView view = lohan::ring_view(const_cast<void *>(ring), num_blocks);
+    if (slot_of != nullptr &&
+        hipMemcpy(slot_of, view.slot_of, sizeof(uint32_t) * num_blocks, hipMemcpyDeviceToHost) !=
+            hipSuccess)
+        return LOHAN_ERR_HIP;
+    if (spare != nullptr &&
+        hipMemcpy(spare, view.spare, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return LOHAN_ERR_HIP;
+    if (skipped != nullptr) {
+        // The two counter arrays are adjacent in the ring: one copy brings both.
+        std::vector<uint64_t> counters(2 * lohan::ring_pad16(sizeof(uint64_t) * num_blocks) / 8);
+        if (hipMemcpy(counters.data(), view.attempts, counters.size() * sizeof(uint64_t),
+                      hipMemcpyDeviceToHost) != hipSuccess)
+            return LOHAN_ERR_HIP;
+        const uint64_t *attempts = counters.data();
+        const uint64_t *overflow_attempt = counters.data() + counters.size() / 2;
+        for (uint32_t b = 0; b < num_blocks; ++b)
+            skipped[b] = attempts[b] != 0 && overflow_attempt[b] == attempts[b] ? 1u : 0u;
+    }
+    return LOHAN_OK;
+}
+
+lohan_status_t lohan_ring_adam_block_step(void *ring, uint32_t num_blocks, uint32_t block,
+                                          const void *grad_fp16, uint64_t n, float lr,
+                                          float beta1, float beta2, float eps,
+                                          float weight_decay, int64_t step, float loss_scale,
+                                          uint32_t flags, hipStream_t stream)
+{
+    if (ring == nullptr || (grad_fp16 == nullptr && n != 0)) return LOHAN_ERR_NULL;
+    if (misaligned(ring, 16) || misaligned(grad_fp16, 16)) return LOHAN_ERR_ALIGN;
+    if (num_blocks == 0 || num_blocks > (1u << 20) || block >= num_blocks) return LOHAN_ERR_ARG;
+    if ((flags & ~(uint32_t)(LOHAN_FLAG_L2_MODE | LOHAN_FLAG_P16_FP16)) != 0) return LOHAN_ERR_ARG;
+    if (step < 1 || !finite_pos(loss_scale) || !finite_nonneg(lr) || !finite_nonneg(eps) ||
+        !finite_nonneg(weight_decay) || !unit_interval(beta1) || !unit_interval(beta2))
+        return LOHAN_ERR_ARG;
+    const int cus = current_cu_count();
+    if (cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::StepScalars s =
+        make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
+    hipError_t e = lohan::launch_adam_ring_step(lohan::ring_view(ring, num_blocks), block,
+                                                grad_fp16, n, s, kernel_mode(flags),
+                                                adam_launch_for(n), cus, stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
 lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,

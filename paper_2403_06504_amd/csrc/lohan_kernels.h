@@ -35,6 +35,44 @@ struct MultiArgs {
     MultiDesc d[kMultiMaxBlocks];
 };
 
+// Ring of slots (see k_adam_ring_step).  Device memory layout of a ring for B blocks, all parts
+// 16-byte aligned: B + 1 RingSlot entries, then B uint64 attempt counters, then B uint64
+// "attempt that last overflowed" values, then B uint32 slot indices (slot_of), then one uint32
+// (the spare slot).
+struct RingSlot {
+    float *p, *m, *v;
+    uint16_t *p16;
+};
+struct RingView {
+    RingSlot *slots;
+    uint64_t *attempts;
+    uint64_t *overflow_attempt;
+    uint32_t *slot_of;
+    uint32_t *spare;
+};
+inline size_t ring_pad16(size_t x) { return (x + 15) / 16 * 16; }
+inline size_t ring_bytes(uint32_t num_blocks)
+{
+    return ring_pad16(sizeof(RingSlot) * ((size_t)num_blocks + 1)) +
+           2 * ring_pad16(sizeof(uint64_t) * (size_t)num_blocks) +
+           ring_pad16(sizeof(uint32_t) * (size_t)num_blocks) + 16;
+}
+inline RingView ring_view(void *ring, uint32_t num_blocks)
+{
+    char *base = reinterpret_cast<char *>(ring);
+    RingView view;
+    view.slots = reinterpret_cast<RingSlot *>(base);
+    base += ring_pad16(sizeof(RingSlot) * ((size_t)num_blocks + 1));
+    view.attempts = reinterpret_cast<uint64_t *>(base);
+    base += ring_pad16(sizeof(uint64_t) * (size_t)num_blocks);
+    view.overflow_attempt = reinterpret_cast<uint64_t *>(base);
+    base += ring_pad16(sizeof(uint64_t) * (size_t)num_blocks);
+    view.slot_of = reinterpret_cast<uint32_t *>(base);
+    base += ring_pad16(sizeof(uint32_t) * (size_t)num_blocks);
+    view.spare = reinterpret_cast<uint32_t *>(base);
+    return view;
+}
+
 // Workspace layout: kMaxPartials doubles, then kMaxPartials uint32 flags, then the per-call
 // scalars: kMultiMaxBlocks unscale factors (float; a single-block clipped step uses the first),
 // then kMultiMaxBlocks squared norms (double) for multi-block calls whose caller wants none.
@@ -73,6 +111,11 @@ hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, cons
                                       float *v_out, void *p16, uint64_t n, const StepScalars &s,
                                       int mode, uint32_t *flag, const AdamLaunch &cfg, int cus,
                                       hipStream_t stream);
+
+// Ring form: the step of `block` from its current slot into the spare, then the commit.
+hipError_t launch_adam_ring_step(const RingView &ring, uint32_t block, const void *grad_fp16,
+                                 uint64_t n, const StepScalars &s, int mode,
+                                 const AdamLaunch &cfg, int cus, hipStream_t stream);
 
 // sqnorm[0..count) -> inv_out[0..count)
 hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,

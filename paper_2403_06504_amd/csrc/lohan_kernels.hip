@@ -468,11 +468,11 @@ __global__ __launch_bounds__(WG) void k_adam_multi_block_step(MultiArgs args, St
 // gradient bits it has loaded anyway; only a wavefront that found a non-finite value touches
 // *flag, with a vector atomic OR.
 template <int WG, int UNROLL, int POLICY, int MODE>
-__global__ __launch_bounds__(WG) void k_adam_block_step_oop(
+__device__ __forceinline__ void adam_oop_body(
     const float *__restrict__ pi, const float *__restrict__ mi, const float *__restrict__ vi,
     const uint16_t *__restrict__ g, float *__restrict__ po, float *__restrict__ mo,
-    float *__restrict__ vo, uint16_t *__restrict__ p16, uint64_t n, StepScalars s,
-    uint32_t *__restrict__ flag)
+    float *__restrict__ vo, uint16_t *__restrict__ p16, uint64_t n, const StepScalars &s,
+    uint32_t &ovf)
 {
     constexpr bool L2 = (MODE & 1) != 0, HALF_OUT = (MODE & 2) != 0;
     constexpr uint64_t kVec = 4;
@@ -480,7 +480,6 @@ __global__ __launch_bounds__(WG) void k_adam_block_step_oop(
     constexpr uint64_t kTile = kRow * UNROLL;
     const uint32_t tid = threadIdx.x;
     const uint64_t ntiles = n / kTile;
-    uint32_t ovf = 0;
 
     for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const uint64_t base = tile * kTile + (uint64_t)tid * kVec;
@@ -543,8 +542,58 @@ __global__ __launch_bounds__(WG) void k_adam_block_step_oop(
         vo[tail] = ve;
         p16[tail] = (uint16_t)pack16<HALF_OUT>(pe, 0.0f);
     }
+}
 
-    if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0 && (tid & 63u) == 0) atomicOr(flag, 1u);
+template <int WG, int UNROLL, int POLICY, int MODE>
+__global__ __launch_bounds__(WG) void k_adam_block_step_oop(
+    const float *__restrict__ pi, const float *__restrict__ mi, const float *__restrict__ vi,
+    const uint16_t *__restrict__ g, float *__restrict__ po, float *__restrict__ mo,
+    float *__restrict__ vo, uint16_t *__restrict__ p16, uint64_t n, StepScalars s,
+    uint32_t *__restrict__ flag)
+{
+    uint32_t ovf = 0;
+    adam_oop_body<WG, UNROLL, POLICY, MODE>(pi, mi, vi, g, po, mo, vo, p16, n, s, ovf);
+    if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0 && (threadIdx.x & 63u) == 0)
+        atomicOr(flag, 1u);
+}
+
+// Ring form of the out-of-place step: a model of B equal blocks lives in B + 1 slots (each slot
+// holds p, m, v and the 16-bit copy of one block), one of them spare.  The step of block b reads
+// the slot that holds b and writes the spare; k_ring_commit then makes the spare b's slot and b's
+// old slot the spare -- unless the gradients overflowed, in which case nothing changes.  Which
+// slot holds which block is a table in device memory, so no host decision (and no host
+// synchronisation) sits between the blocks of a backward pass.  Every block counts its attempts
+// (steps enqueued so far); an overflowing step records its attempt number with an atomic max,
+// which needs no clearing and tells "the latest attempt overflowed" from any older one.
+template <int WG, int UNROLL, int POLICY, int MODE>
+__global__ __launch_bounds__(WG) void k_adam_ring_step(
+    const RingSlot *__restrict__ slots, const uint32_t *__restrict__ slot_of,
+    const uint32_t *__restrict__ spare, const unsigned long long *__restrict__ attempts,
+    unsigned long long *__restrict__ overflow_attempt, uint32_t block,
+    const uint16_t *__restrict__ g, uint64_t n, StepScalars s)
+{
+    const RingSlot in = slots[slot_of[block]];
+    const RingSlot out = slots[*spare];
+    const unsigned long long attempt = attempts[block] + 1;
+    uint32_t ovf = 0;
+    adam_oop_body<WG, UNROLL, POLICY, MODE>(in.p, in.m, in.v, g, out.p, out.m, out.v, out.p16, n,
+                                            s, ovf);
+    if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0 && (threadIdx.x & 63u) == 0)
+        atomicMax(overflow_attempt + block, attempt);
+}
+
+__global__ void k_ring_commit(uint32_t *__restrict__ slot_of, uint32_t *__restrict__ spare,
+                              unsigned long long *__restrict__ attempts,
+                              const unsigned long long *__restrict__ overflow_attempt,
+                              uint32_t block)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const unsigned long long attempt = attempts[block] + 1;
+    attempts[block] = attempt;
+    if (overflow_attempt[block] == attempt) return;    // skipped: the inputs stay the state
+    const uint32_t old_slot = slot_of[block];
+    slot_of[block] = *spare;
+    *spare = old_slot;
 }
 
 // Per-block norm clipping without a host round trip: from the squared norm that
@@ -653,6 +702,9 @@ typedef void (*adam_oop_kernel_t)(const float *, const float *, const float *, c
                                   uint32_t *);
 
 typedef void (*adam_multi_kernel_t)(MultiArgs, StepScalars, const uint32_t *, const float *);
+typedef void (*adam_ring_kernel_t)(const RingSlot *, const uint32_t *, const uint32_t *,
+                                   const unsigned long long *, unsigned long long *, uint32_t,
+                                   const uint16_t *, uint64_t, StepScalars);
 
 // The kernel families share the variant space; a family names the function-pointer type and
 // the instantiation for one point of it.
@@ -665,6 +717,12 @@ struct OutOfPlaceFamily {
     typedef adam_oop_kernel_t fn;
     template <int WG, int UNROLL, int POLICY, int MODE>
     static fn get() { return k_adam_block_step_oop<WG, UNROLL, POLICY, MODE>; }
+};
+
+struct RingFamily {
+    typedef adam_ring_kernel_t fn;
+    template <int WG, int UNROLL, int POLICY, int MODE>
+    static fn get() { return k_adam_ring_step<WG, UNROLL, POLICY, MODE>; }
 };
 
 struct MultiBlockFamily {
@@ -826,6 +884,30 @@ hipError_t launch_adam_multi_block_step(const MultiArgs &args, uint32_t num_bloc
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(geo.grid, num_blocks), dim3(geo.wg), geo.lds, stream, args, s,
                        flags, inv_override);
+    return hipGetLastError();
+}
+
+hipError_t launch_adam_ring_step(const RingView &ring, uint32_t block, const void *grad_fp16,
+                                 uint64_t n, const StepScalars &s, int mode,
+                                 const AdamLaunch &cfg, int cus, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    adam_ring_kernel_t kernel = pick_kernel<RingFamily>(cfg.variant, mode);
+    if (kernel == nullptr) return hipErrorInvalidValue;
+    AdamGeometry geo;
+    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, cus, geo);
+    if (e != hipSuccess) return e;
+    unsigned long long *attempts = reinterpret_cast<unsigned long long *>(ring.attempts);
+    unsigned long long *overflow_attempt =
+        reinterpret_cast<unsigned long long *>(ring.overflow_attempt);
+    hipLaunchKernelGGL(kernel, dim3(geo.grid), dim3(geo.wg), geo.lds, stream, ring.slots,
+                       ring.slot_of, ring.spare, attempts, overflow_attempt, block,
+                       reinterpret_cast<const uint16_t *>(grad_fp16), n, s);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_ring_commit, dim3(1), dim3(64), 0, stream, ring.slot_of, ring.spare,
+                       attempts, overflow_attempt, block);
     return hipGetLastError();
 }
 

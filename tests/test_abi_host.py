@@ -246,6 +246,41 @@ def test_model_placement_properties(lib):
                                      ctypes.byref(align), None) == 3
 
 
+def test_ring_validation_returns_before_any_device_call(lib):
+    need = lib.lohan_ring_bytes(4)
+    assert need >= 5 * 32 + 2 * 4 * 8 + 4 * 4 + 4 and need % 16 == 0
+    assert lib.lohan_ring_bytes(40) > need
+    good = (binding.LohanRingSlot * 5)(*[binding.LohanRingSlot(A * (4 * i + 1), A * (4 * i + 2),
+                                                               A * (4 * i + 3), A * (4 * i + 4))
+                                         for i in range(5)])
+    assert lib.lohan_ring_init(None, need, good, 4) == 1
+    assert lib.lohan_ring_init(A, need, None, 4) == 1
+    assert lib.lohan_ring_init(A + 8, need, good, 4) == 2
+    assert lib.lohan_ring_init(A, need, good, 0) == 3
+    assert lib.lohan_ring_init(A, need - 1, good, 4) == 4
+    for field in ("param_fp32", "exp_avg", "exp_avg_sq", "param_16"):
+        bad = (binding.LohanRingSlot * 5)(*good)
+        setattr(bad[4], field, None)                             # the spare slot counts too
+        assert lib.lohan_ring_init(A, need, bad, 4) == 1, field
+        setattr(bad[4], field, A * 50 + 4)
+        assert lib.lohan_ring_init(A, need, bad, 4) == 2, field
+
+    def step(ring=A, nb=4, block=1, g=A * 2, n=16, step=1, loss_scale=1024.0, flags=0, **over):
+        h = dict(GOOD, **over)
+        return lib.lohan_ring_adam_block_step(ring, nb, block, g, n, h["lr"], h["beta1"],
+                                              h["beta2"], h["eps"], h["weight_decay"], step,
+                                              loss_scale, flags, None)
+
+    assert step(ring=None) == 1 and step(g=None) == 1
+    assert step(ring=A + 4) == 2 and step(g=A * 2 + 2) == 2
+    assert step(block=4) == 3 and step(nb=0) == 3
+    assert step(flags=2) == 3 and step(flags=8) == 3            # no prechecked form
+    assert step(step=0) == 3 and step(loss_scale=math.nan) == 3 and step(beta2=1.0) == 3
+    assert lib.lohan_ring_read(None, 4, None, None, None, None) == 1
+    assert lib.lohan_ring_read(A + 4, 4, None, None, None, None) == 2
+    assert lib.lohan_ring_read(A, 0, None, None, None, None) == 3
+
+
 def test_offload_create_validation_touches_no_device(lib):
     handle = ctypes.c_void_p()
     need = lib.lohan_offload_slab_bytes(1000, 3)
