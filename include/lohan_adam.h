@@ -15,9 +15,11 @@
  *   - Every data pointer is DEVICE memory owned by the caller, valid on `stream`'s device, and
  *     16-byte aligned (4 KiB or better for full bandwidth: bases aligned only to 256 bytes cost
  *     about 4 % on MI355X).  Buffers of one call must not overlap each other.
- *   - The library allocates nothing, keeps no per-call state, and never synchronises: kernels are
- *     enqueued on `stream` and the call returns.  Results (state, flag, squared norm) are valid
- *     once the work enqueued on `stream` has completed.
+ *   - The library allocates no device memory, keeps no per-call state, and does not synchronise:
+ *     kernels are enqueued on `stream` and the call returns.  Results (state, flag, squared norm)
+ *     are valid once the work enqueued on `stream` has completed.  The exceptions say so in their
+ *     own comments: lohan_ring_init and lohan_ring_read (synchronous copies), the lohan_offload_*
+ *     handle (owns streams and events) and the host-only helpers (no device involved at all).
  *   - `workspace` is device scratch of at least lohan_workspace_bytes() bytes, 16-byte aligned,
  *     private to the call until its kernels complete (calls that may run concurrently on different
  *     streams need different workspaces).
