@@ -443,6 +443,37 @@ def bench_stream(args, torch, lohan, synth):
     elapsed = (time.perf_counter() - t0) / args.steps
     assert all(int(f.cpu().item()) == 0 for f in flags)
     total = n * nblocks
+
+    # The same pass with the ring form: the blocks' own arrays are slots 0..B-1, one more slot
+    # is the spare; every step is the single-pass out-of-place update, committed on the device.
+    # A ring's steps must be ordered, so they all go to one side stream.
+    spare = {k: torch.empty_like(blocks[0][k]) for k in ("p", "m", "v", "p16")}
+    slot_list = [(blk["p"], blk["m"], blk["v"], blk["p16"]) for blk in blocks]
+    slot_list.append((spare["p"], spare["m"], spare["v"], spare["p16"]))
+    ring = torch.empty(lohan.lohan_ring_bytes(nblocks), dtype=torch.uint8, device=dev)
+    lohan.lohan_ring_init(ring, slot_list, n)
+
+    def ring_pass(t):
+        s = side[0]
+        for i in reversed(range(nblocks)):
+            torch.matmul(a, b)
+            ev = torch.cuda.Event()
+            ev.record(main)
+            s.wait_event(ev)
+            lohan.lohan_ring_adam_block_step(ring, nblocks, i, blocks[i]["g"], n, hy["lr"],
+                                             hy["beta1"], hy["beta2"], hy["eps"],
+                                             hy["weight_decay"], t, hy["loss_scale"], 0, stream=s)
+        main.wait_stream(s)
+
+    t_ring0 = hy["step"] + args.warmup + 2 * args.steps
+    ring_pass(t_ring0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ring_pass(t_ring0 + 1 + k)
+    torch.cuda.synchronize()
+    ring_elapsed = (time.perf_counter() - t0) / args.steps
+    assert lohan.lohan_ring_read(ring, nblocks)[2] == [0] * nblocks
     return {
         "metric": "adam_updated_elements_per_sec", "value": total / elapsed,
         "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -455,6 +486,10 @@ def bench_stream(args, torch, lohan, synth):
         "ms_per_block": elapsed * 1e3 / nblocks,
         "gemm_only_ms": gemm_s * 1e3, "steps_only_ms": steps_only_s * 1e3,
         "pass_over_sum_of_parts": elapsed / (gemm_s + steps_only_s),
+        "ring_form": {"note": "same pass with lohan_ring_adam_block_step (one spare slot, "
+                              "single-pass steps on one side stream)",
+                      "ms_per_step": ring_elapsed * 1e3, "value": total / ring_elapsed,
+                      "over_in_place": elapsed / ring_elapsed},
         "roofline": {"kernel": "k_adam_block_step", "bound": "hbm",
                      "achieved": 28 * total / elapsed / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": 28 * total / elapsed / 1e9 / HBM_PEAK_GBPS,
