@@ -703,3 +703,85 @@ def test_13b_blocks_in_the_library_placement(oracle):
             worst = assert_state_parity(blocks[b].host(s, s + span), host,
                                         what=f"library placement, block {b} range {s}")
             assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
+
+
+def nan_aware_equal(got: np.ndarray, want: np.ndarray, nan_mask_fn) -> bool:
+    """Bit equality, except that a NaN on one side only has to be a NaN on the other (payload and
+    sign of a NaN are not part of the contract)."""
+    gn, wn = nan_mask_fn(got), nan_mask_fn(want)
+    return bool(np.array_equal(gn, wn) and np.array_equal(got[~gn], want[~wn]))
+
+
+def test_random_bit_patterns_and_hyperparameters(oracle):
+    """Seeded differential test far outside the training regime: p and m are arbitrary finite
+    float32 bit patterns, v arbitrary non-negative ones, g arbitrary finite binary16 patterns, the
+    hyper-parameters log-uniform over many decades -- so squares overflow, sums cancel, quotients
+    underflow and inf - inf appears.  In place and out of place; every non-NaN result must match
+    the oracle bit for bit, and NaNs must appear in the same places."""
+    rng = np.random.default_rng(2403)
+    n = 50_003
+
+    def finite32(count):
+        bits = rng.integers(0, 1 << 32, size=count, dtype=np.uint64).astype(np.uint32)
+        bits = np.where((bits & 0x7F800000) == 0x7F800000, bits & 0xBFFFFFFF, bits)
+        return bits
+
+    f32nan = lambda a: np.isnan(a.view(np.float32))
+    bf16nan = lambda a: ((a & 0x7F80) == 0x7F80) & ((a & 0x007F) != 0)
+    f16nan = lambda a: ((a & 0x7C00) == 0x7C00) & ((a & 0x03FF) != 0)
+    for case in range(24):
+        p = finite32(n)
+        m = finite32(n)
+        v = finite32(n) & 0x7FFFFFFF
+        g = rng.integers(0, 1 << 16, size=n, dtype=np.uint32).astype(np.uint16)
+        g = np.where((g & 0x7C00) == 0x7C00, g & 0xBFFF, g).astype(np.uint16)
+        hy = dict(lr=float(np.float32(10 ** rng.uniform(-6, -1))),
+                  beta1=float(np.float32(rng.uniform(0, 0.999))),
+                  beta2=float(np.float32(rng.uniform(0.5, 0.9999))),
+                  eps=float(np.float32(10 ** rng.uniform(-10, -3))),
+                  weight_decay=float(np.float32(rng.uniform(0, 0.3))),
+                  step=int(rng.integers(1, 1_000_000)),
+                  loss_scale=float(np.float32(2.0 ** rng.integers(0, 17) if case % 2 else
+                                              10 ** rng.uniform(0, 5))))
+        l2, half = bool(case & 1), bool(case & 2)
+        flags = (lohan.LOHAN_FLAG_L2_MODE if l2 else 0) | (lohan.LOHAN_FLAG_P16_FP16 if half else 0)
+        host = {"p": p.view(np.float32).copy(), "m": m.view(np.float32).copy(),
+                "v": v.view(np.float32).copy(), "g": g.copy(),
+                "p16": np.zeros(n, dtype=np.uint16)}
+        dev = {k: torch.from_numpy(host[k].copy()).to(DEV) for k in ("p", "m", "v")}
+        dev["g"] = torch.from_numpy(g.view(np.int16).copy()).to(DEV).view(torch.float16)
+        dev["p16"] = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+        out = {k: torch.empty_like(dev[k]) for k in ("p", "m", "v", "p16")}
+        flag = torch.full((1,), 3, dtype=torch.int32, device=DEV)
+        lohan.lohan_adam_block_step_out_of_place(
+            dev["p"], dev["m"], dev["v"], dev["g"], out["p"], out["m"], out["v"], out["p16"], n,
+            hy["lr"], hy["beta1"], hy["beta2"], hy["eps"], hy["weight_decay"], hy["step"],
+            hy["loss_scale"], flag, flags)
+        blk = DeviceBlock(dev)
+        blk.step(hy, flags=flags)
+        torch.cuda.synchronize()
+        assert blk.flag_value() == 0 and int(flag.cpu().item()) == 0
+        assert oracle.adam_block_step(host["p"], host["m"], host["v"], host["g"], host["p16"],
+                                      nthreads=4, l2_mode=l2, half_out=half, **hy) == 0
+        in_place = blk.host()
+        oop = {k: synth.to_numpy_bits(out[k]) for k in ("p", "m", "v", "p16")}
+        nan16 = f16nan if half else bf16nan
+        for name, got in (("in place", in_place), ("out of place", oop)):
+            for k in ("p", "m", "v"):
+                assert nan_aware_equal(got[k].view(np.uint32), host[k].view(np.uint32),
+                                       f32nan), (case, name, k, hy)
+            assert nan_aware_equal(got["p16"], host["p16"], nan16), (case, name, "p16", hy)
+        # a second step in place on the state the first one left (now holding infinities):
+        # inf / inf and inf - inf turn up, and must turn up in the same elements
+        hy2 = dict(hy, step=hy["step"] + 1)
+        blk.step(hy2, flags=flags)
+        torch.cuda.synchronize()
+        assert oracle.adam_block_step(host["p"], host["m"], host["v"], host["g"], host["p16"],
+                                      nthreads=4, l2_mode=l2, half_out=half, **hy2) == 0
+        got = blk.host()
+        for k in ("p", "m", "v"):
+            assert nan_aware_equal(got[k].view(np.uint32), host[k].view(np.uint32),
+                                   f32nan), (case, "second step", k, hy)
+        assert nan_aware_equal(got["p16"], host["p16"], nan16), (case, "second step", "p16", hy)
+        say(f"[random] case {case}: {int(np.isnan(host['p']).sum())} NaN, "
+            f"{int(np.isinf(host['p']).sum())} inf of {n} parameters after two steps")
