@@ -276,9 +276,10 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
  * block sit relative to each other moves the update kernel by several percent on MI355X: p, m
  * and v advance at the same rate, so their relative position is fixed for a whole launch, and
  * the measured best is "same offset within consecutive periods of 4 GiB (or 12 GiB), shifted by
- * 1 MiB each"; the allocator's placement is a lottery between -4 % and 0 % of that (measurements
- * in the design notes).  This function lays out the tensors of Table II for num_blocks equal
- * blocks of n elements inside ONE caller-allocated slab accordingly:
+ * 1 MiB each" (6.80-6.90 TB/s for a 13B-shaped block); the allocator's placement is a lottery
+ * between -4 % and 0 % of that, and all three arrays at the same offset modulo 4 GiB is the worst
+ * case.  This function lays out the tensors of Table II for num_blocks equal blocks of n
+ * elements inside ONE caller-allocated slab accordingly:
  *   - the period P is 4 GiB if one fp32 array fits into 4 GiB - 2 MiB, else 12 GiB if it fits
  *     into 12 GiB - 2 MiB;
  *   - groups of G = floor((P - 2 MiB) / bytes(p)) consecutive blocks share three "lanes":
