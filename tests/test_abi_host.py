@@ -323,6 +323,37 @@ def test_plain_c_client_builds_and_runs(lib, tmp_path):
     assert lines["flops"] == "0 200.0 -10.0"
 
 
+def test_host_code_under_address_and_undefined_sanitizers(lib, tmp_path):
+    """The host side of the library (C ABI layer, offload handle, planner) rebuilt with
+    AddressSanitizer + UBSan (host code only; the kernels come from the regular library), driven
+    by a C client through many planner instances, placements and validation paths."""
+    import shutil
+    import subprocess
+    from paper_2403_06504_amd import build
+    clang = "/opt/rocm/llvm/bin/clang"
+    if not (os.path.exists(build.HIPCC) and os.path.exists(clang)):
+        pytest.skip("no ROCm toolchain")
+    libdir = os.path.dirname(lohan.library_path())
+    san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"]
+    host_san = [x for flag in san for x in ("-Xarch_host", flag)]
+    sources = [f for f in build.SOURCES if not f.endswith("lohan_kernels.hip")]
+    so = tmp_path / "liblohan_hostsan.so"
+    subprocess.run([build.HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC",
+                    "-shared", *host_san, "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
+                    "-o", str(so), *sources, "-L" + libdir,
+                    "-l:" + os.path.basename(lohan.library_path()), "-Wl,-rpath," + libdir],
+                   check=True, capture_output=True)
+    exe = tmp_path / "stress"
+    subprocess.run([clang, "-std=c11", "-g", "-Wall", "-Wextra", "-Werror", *san,
+                    "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+                    "-I" + os.path.join(ROOT, "include"), "-o", str(exe),
+                    os.path.join(ROOT, "tests", "c_abi_host_stress.c"), "-L" + str(tmp_path),
+                    "-l:" + so.name, "-Wl,-rpath," + str(tmp_path), "-Wl,-rpath,/opt/rocm/lib",
+                    "-Wl,-rpath," + libdir, "-lm"], check=True, capture_output=True)
+    run = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert run.returncode == 0 and run.stdout.startswith("ok "), (run.stdout, run.stderr[-2000:])
+
+
 def test_binding_raises_with_status(lib):
     with pytest.raises(lohan.LohanError) as e:
         lohan.lohan_adam_block_step(A, A * 2, A * 3, A * 4, A * 5, 16, 1e-4, 0.9, 0.999, 1e-8,
