@@ -452,9 +452,9 @@ __global__ __launch_bounds__(WG) void k_adam_multi_block_step(MultiArgs args, St
     const uint32_t b = blockIdx.y;
     const uint64_t n = args.d[b].n;
     constexpr uint64_t kTile = (uint64_t)WG * 4 * UNROLL;
-    // Workgroups beyond this block's tiles have nothing to do (workgroup 0 always takes the
-    // ragged end, also of a block shorter than one tile).
-    if (blockIdx.x != 0 && (uint64_t)blockIdx.x * kTile >= n) return;
+    // Workgroups beyond this block's tiles have nothing to do, except that the ragged end (fewer
+    // than UNROLL * WG vectors) is spread over the first UNROLL workgroups.
+    if (blockIdx.x >= UNROLL && (uint64_t)blockIdx.x * kTile >= n) return;
     if (flags[b] != 0u) return;
     if (inv_override != nullptr) s.inv = inv_override[b];
     adam_block_body<WG, UNROLL, POLICY, MODE>(args.d[b].p, args.d[b].m, args.d[b].v, args.d[b].g,

@@ -174,7 +174,7 @@ def test_per_block_clipping(oracle, S, max_norm):
 
 
 def test_every_kernel_variant_multi_block(oracle):
-    sizes = [100_003, 1_000_003, 100_003, 77]
+    sizes = [100_003, 1_000_003, 100_003, 77, 300, 511, 1_023, 2_047]   # incl. shorter than a tile
     ref = BlockSet(sizes, seed0=3)
     hosts = ref.host()
     for h in hosts:
@@ -186,7 +186,7 @@ def test_every_kernel_variant_multi_block(oracle):
                 say(f"[multi variant] variant={variant} wgs_per_cu={wgs} waves_per_cu={waves}")
                 lohan.lohan_set_launch_config(variant, wgs, waves, 0)
                 bs = BlockSet(sizes, seed0=3)
-                assert bs.step(want_norms=False) == [0, 0, 0, 0]
+                assert bs.step(want_norms=False) == [0] * len(sizes)
                 for i, blk in enumerate(bs.blocks):
                     assert assert_state_parity(blk.host(), hosts[i],
                                                what=f"variant {variant} block {i}") == ZERO
