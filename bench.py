@@ -171,7 +171,7 @@ def bench_block(args, torch, lohan, synth):
         torch.cuda.empty_cache()
     flag = torch.zeros(1, dtype=torch.int32, device=dev)
     sqnorm = torch.zeros(1, dtype=torch.float64, device=dev)
-    ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+    ws = lohan.new_workspace(dev)
     hy = wl.hyper()
 
     base = None if args.no_cpu_baseline else cpu_baseline(block, wl)
@@ -225,7 +225,7 @@ def bench_block(args, torch, lohan, synth):
                                f"(fp32 p/m/v, fp16 grads x loss scale {wl.loss_scale:g}, "
                                f"bf16 copy), AdamW step {wl.step}",
                    "elements": n, "bytes_per_element_step": 30, "placement": placement,
-                   "launch_config": list(lohan.lohan_get_launch_config())},
+                   "launch_config": list(lohan.lohan_tuning_get_launch_config())},
         "step_hbm_gbps": (ADAM_BYTES_PER_ELEM + REDUCE_BYTES_PER_ELEM) * n /
                          (elapsed / args.steps) / 1e9,
         "roofline": {"kernel": "k_adam_block_step", "bound": "hbm", "achieved": achieved,
@@ -291,7 +291,7 @@ def bench_block_oop(args, torch, lohan, synth):
         "config": {"workload": f"{wl.name}, out-of-place step with the overflow test fused in: "
                                f"n={n} elements, two sets of fp32 p/m/v and of the bf16 copy",
                    "elements": n, "bytes_per_element_step": 28,
-                   "launch_config": list(lohan.lohan_get_launch_config())},
+                   "launch_config": list(lohan.lohan_tuning_get_launch_config())},
         "step_hbm_gbps": ADAM_BYTES_PER_ELEM * n / (elapsed / args.steps) / 1e9,
         "roofline": {"kernel": "k_adam_block_step_oop (events also span the one-lane flag clear)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
@@ -371,7 +371,7 @@ def bench_ring(args, torch, lohan, synth):
                                "slots, single-pass out-of-place steps committed on the device",
                    "elements": n, "bytes_per_element_step": 28,
                    "extra_state_fraction": 1.0 / nblocks,
-                   "launch_config": list(lohan.lohan_get_launch_config())},
+                   "launch_config": list(lohan.lohan_tuning_get_launch_config())},
         "step_hbm_gbps": ADAM_BYTES_PER_ELEM * n / (elapsed / args.steps) / 1e9,
         "roofline": {"kernel": "k_adam_ring_step (events also span the one-lane commit)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
@@ -393,7 +393,7 @@ def bench_stream(args, torch, lohan, synth):
     blocks = [synth.make_block(wl, seed=i, device=dev) for i in range(nblocks)]
     flags = [torch.zeros(1, dtype=torch.int32, device=dev) for _ in range(nblocks)]
     norms = [torch.zeros(1, dtype=torch.float64, device=dev) for _ in range(nblocks)]
-    wss = [torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+    wss = [lohan.new_workspace(dev)
            for _ in range(2)]
     side = [torch.cuda.Stream(), torch.cuda.Stream()]
     a = torch.randn(2048, 5120, device=dev, dtype=torch.bfloat16)
@@ -548,7 +548,7 @@ def bench_offload(args, torch, lohan, synth):
 
     # Zero-copy alternative: pinned host memory is device-accessible, so the same two calls can
     # run with p, m, v left in host memory; every access of the kernel then crosses PCIe.
-    ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+    ws = lohan.new_workspace(dev)
 
     def zero_copy_pass(t):
         for i in reversed(range(nblocks)):
@@ -595,7 +595,7 @@ def bench_shapes(args, torch, lohan, synth):
     dev = "cuda:0"
     flag = torch.zeros(1, dtype=torch.int32, device=dev)
     sqnorm = torch.zeros(1, dtype=torch.float64, device=dev)
-    ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+    ws = lohan.new_workspace(dev)
     rows = []
     for wl in synth.shape_workloads():
         n = wl.n
@@ -696,7 +696,7 @@ def bench_models(args, torch, lohan, synth):
             blocks = [synth.make_block(wl, seed=i, device=dev) for i in range(layers)]
         flags = torch.zeros(layers, dtype=torch.int32, device=dev)
         norms = torch.zeros(layers, dtype=torch.float64, device=dev)
-        ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=dev)
+        ws = lohan.new_workspace(dev)
         array = lohan.make_block_array([(b["p"], b["m"], b["v"], b["g"], b["p16"], n)
                                         for b in blocks])
         reps = max(3, min(args.steps, int(4e10 // (n * layers))))
@@ -776,7 +776,7 @@ def main():
     torch.cuda.set_device(0)
     lohan.load_library()
     if args.variant is not None or args.wgs_per_cu or args.waves_per_cu >= 0:
-        lohan.lohan_set_launch_config(-1 if args.variant is None else args.variant,
+        lohan.lohan_tuning_set_launch_config(-1 if args.variant is None else args.variant,
                                       args.wgs_per_cu, args.waves_per_cu, 0)
     if args.workload == "stream13b":
         out = bench_stream(args, torch, lohan, synth)

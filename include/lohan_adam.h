@@ -22,7 +22,9 @@
  *     handle (owns streams and events) and the host-only helpers (no device involved at all).
  *   - `workspace` is device scratch of at least lohan_workspace_bytes() bytes, 16-byte aligned,
  *     private to the call until its kernels complete (calls that may run concurrently on different
- *     streams need different workspaces).
+ *     streams need different workspaces).  It must have been prepared ONCE with
+ *     lohan_workspace_init (or be zero-filled) before its first use; every call leaves it ready
+ *     for the next one, so nothing needs clearing between calls.
  *   - n is the element count of the flat block; any n >= 0 is accepted (n == 0: flag = 0,
  *     squared norm = 0, nothing else is touched).
  *   - Errors are reported by return code only.  For codes LOHAN_ERR_NULL .. LOHAN_ERR_WORKSPACE no
@@ -63,6 +65,17 @@ enum {
 
 /* Device scratch bytes one call needs (a constant of the build; a few tens of KiB). */
 size_t lohan_workspace_bytes(void);
+
+/*
+ * Prepare a freshly allocated workspace: the gradient reduction finishes inside its one launch
+ * (the workgroup that publishes the last partial result combines them all), which needs a few
+ * ticket counters in the workspace to read zero when a call starts.  This enqueues a small fill
+ * kernel on `stream` that zeroes them; every later call puts them back to zero itself.  Call it
+ * once per workspace (and again after an LOHAN_ERR_HIP, when the contents are unspecified).  A
+ * workspace whose counters are not zero makes the calls that use it leave their outputs
+ * unwritten.  Errors: LOHAN_ERR_NULL / _ALIGN / _WORKSPACE as for any workspace argument.
+ */
+lohan_status_t lohan_workspace_init(void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 /* Static text for a status code (host memory owned by the library). */
 const char *lohan_status_string(lohan_status_t status);
@@ -387,27 +400,6 @@ lohan_status_t lohan_offload_drain(lohan_offload_t *handle);
 
 /* Drain, then release the streams, events and the handle. */
 lohan_status_t lohan_offload_destroy(lohan_offload_t *handle);
-
-/*
- * Launch-shape override for benchmarking and tuning sweeps (process-wide; do not change it while
- * calls are in flight on other threads).
- *   adam_variant            bits [1:0] workgroup size (64, 128, 256 lanes), bits [3:2]
- *                           vectors per lane per tile (1, 2), bits [5:4] cache policy (0 default,
- *                           1 nontemporal, 2 nontemporal loads + write-through streaming stores);
- *                           negative = automatic (64 lanes, 1 vector; default policy for blocks
- *                           that fit the 256 MiB memory-side cache, policy 2 above that; reported
- *                           as -1 by lohan_get_launch_config); other values -> LOHAN_ERR_ARG
- *   adam_workgroups_per_cu  0 = one tile per workgroup (grid = number of tiles); > 0 caps the
- *                           grid at that many workgroups per compute unit; negative = default
- *   adam_waves_per_cu       occupancy throttle: at most this many wavefronts of the Adam kernel
- *                           resident per compute unit (0 or 32 = no throttle); negative = default
- *   reduce_workgroups_per_cu  grid of the gradient reduction per compute unit (<= 16);
- *                           <= 0 = default
- */
-lohan_status_t lohan_set_launch_config(int adam_variant, int adam_workgroups_per_cu,
-                                       int adam_waves_per_cu, int reduce_workgroups_per_cu);
-void lohan_get_launch_config(int *adam_variant, int *adam_workgroups_per_cu,
-                             int *adam_waves_per_cu, int *reduce_workgroups_per_cu);
 
 #ifdef __cplusplus
 }

@@ -24,8 +24,9 @@ EXPORTS = (
     "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
     "lohan_adam_block_step_out_of_place", "lohan_adam_multi_block_step", "lohan_model_placement",
     "lohan_ring_bytes", "lohan_ring_init", "lohan_ring_adam_block_step", "lohan_ring_read",
-    "lohan_clip_loss_scale",
-    "lohan_set_launch_config", "lohan_get_launch_config",
+    "lohan_clip_loss_scale", "lohan_workspace_init",
+    "lohan_tuning_set_launch_config", "lohan_tuning_get_launch_config",
+    "lohan_tuning_device_info", "lohan_tuning_probe",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
     "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
     "lohan_swap_iter_time", "lohan_swap_recompute_flops", "lohan_plan_activation_swapping",
@@ -137,10 +138,16 @@ def load_library():
     lib.lohan_model_placement.restype = ctypes.c_int
     lib.lohan_clip_loss_scale.argtypes = [ctypes.c_double, f32, f32]
     lib.lohan_clip_loss_scale.restype = f32
-    lib.lohan_set_launch_config.argtypes = [ctypes.c_int] * 4
-    lib.lohan_set_launch_config.restype = ctypes.c_int
-    lib.lohan_get_launch_config.argtypes = [ctypes.POINTER(ctypes.c_int)] * 4
-    lib.lohan_get_launch_config.restype = None
+    lib.lohan_workspace_init.argtypes = [vp, sz, vp]
+    lib.lohan_workspace_init.restype = ctypes.c_int
+    lib.lohan_tuning_set_launch_config.argtypes = [ctypes.c_int] * 5
+    lib.lohan_tuning_set_launch_config.restype = ctypes.c_int
+    lib.lohan_tuning_get_launch_config.argtypes = [ctypes.POINTER(ctypes.c_int)] * 5
+    lib.lohan_tuning_get_launch_config.restype = None
+    lib.lohan_tuning_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(sz)]
+    lib.lohan_tuning_device_info.restype = ctypes.c_int
+    lib.lohan_tuning_probe.argtypes = [ctypes.c_int, vp, vp, vp, vp, vp, u64, ctypes.c_int, vp]
+    lib.lohan_tuning_probe.restype = ctypes.c_int
     lib.lohan_offload_slab_bytes.argtypes = [u64, ctypes.c_int]
     lib.lohan_offload_slab_bytes.restype = sz
     lib.lohan_offload_create.argtypes = [ctypes.POINTER(vp), vp, sz, u64, ctypes.c_int,
@@ -229,6 +236,22 @@ def lohan_workspace_bytes() -> int:
 
 def lohan_status_string(status: int) -> str:
     return load_library().lohan_status_string(int(status)).decode()
+
+
+def lohan_workspace_init(workspace, workspace_bytes=None, stream=None):
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_workspace_init(ws, ws_bytes, _stream(stream)))
+
+
+def new_workspace(device, stream=None):
+    """A torch uint8 tensor of lohan_workspace_bytes() on `device`, prepared with
+    lohan_workspace_init on `stream` and ready for use on ANY stream when this returns (the
+    preparation is waited for; torch supplies the memory, the library the contents)."""
+    import torch
+    ws = torch.empty(lohan_workspace_bytes(), dtype=torch.uint8, device=device)
+    lohan_workspace_init(ws, stream=stream)
+    torch.cuda.synchronize()
+    return ws
 
 
 def lohan_grad_overflow_check(grad_fp16, n, overflow_flag, workspace, workspace_bytes=None,
@@ -383,19 +406,38 @@ def lohan_clip_loss_scale(sqnorm, loss_scale, max_norm) -> float:
                                                       float(max_norm)))
 
 
-def lohan_set_launch_config(adam_variant=-1, adam_workgroups_per_cu=-1, adam_waves_per_cu=-1,
-                            reduce_workgroups_per_cu=0):
-    """Negative (or, for the last, non-positive) arguments select the built-in defaults."""
-    _check(load_library().lohan_set_launch_config(int(adam_variant), int(adam_workgroups_per_cu),
-                                                  int(adam_waves_per_cu),
-                                                  int(reduce_workgroups_per_cu)))
+def lohan_tuning_set_launch_config(adam_variant=-1, adam_workgroups_per_cu=-1,
+                                   adam_waves_per_cu=-1, reduce_workgroups_per_cu=0,
+                                   reduce_policy=-1):
+    """Bench-only (include/lohan_adam_tuning.h); affects the calling thread's later calls.
+    Negative (for reduce_workgroups_per_cu: non-positive) arguments select the defaults."""
+    _check(load_library().lohan_tuning_set_launch_config(
+        int(adam_variant), int(adam_workgroups_per_cu), int(adam_waves_per_cu),
+        int(reduce_workgroups_per_cu), int(reduce_policy)))
 
 
-def lohan_get_launch_config():
-    a, b, c, d = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    load_library().lohan_get_launch_config(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
-                                           ctypes.byref(d))
-    return a.value, b.value, c.value, d.value
+def lohan_tuning_get_launch_config():
+    vals = [ctypes.c_int() for _ in range(5)]
+    load_library().lohan_tuning_get_launch_config(*[ctypes.byref(v) for v in vals])
+    return tuple(v.value for v in vals)
+
+
+def lohan_tuning_device_info():
+    """(compute units, LDS bytes per compute unit) as the library read them."""
+    cus, lds = ctypes.c_int(), ctypes.c_size_t()
+    _check(load_library().lohan_tuning_device_info(ctypes.byref(cus), ctypes.byref(lds)))
+    return cus.value, lds.value
+
+
+LOHAN_PROBE_READ, LOHAN_PROBE_WRITE, LOHAN_PROBE_COPY = 0, 1, 2
+LOHAN_PROBE_FIVE_STREAM, LOHAN_PROBE_MEMCPY = 3, 4
+
+
+def lohan_tuning_probe(pattern, a, b, c, g16, h16, n, waves_per_cu=0, stream=None):
+    _check(load_library().lohan_tuning_probe(
+        int(pattern), _addr(a, n, _F32, "a"), _addr(b, n, _F32, "b"), _addr(c, n, _F32, "c"),
+        _addr(g16, n, _F16, "g16"), _addr(h16, n, _BF16, "h16"), int(n), int(waves_per_cu),
+        _stream(stream)))
 
 
 def lohan_offload_slab_bytes(max_block_elems, num_slots) -> int:

@@ -13,8 +13,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblohan_adam.so")
 SOURCES = [os.path.join(CSRC, "lohan_kernels.hip"), os.path.join(CSRC, "lohan_api.hip"),
-           os.path.join(CSRC, "lohan_offload.hip"), os.path.join(CSRC, "lohan_swap_planner.hip")]
+           os.path.join(CSRC, "lohan_offload.hip"), os.path.join(CSRC, "lohan_swap_planner.hip"),
+           os.path.join(CSRC, "lohan_ceiling_probe.hip")]
 HEADERS = [os.path.join(CSRC, "lohan_kernels.h"), os.path.join(ROOT, "include", "lohan_adam.h"),
+           os.path.join(ROOT, "include", "lohan_adam_tuning.h"),
            os.path.join(ROOT, "include", "lohan_swap_planner.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

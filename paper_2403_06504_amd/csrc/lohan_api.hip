@@ -10,44 +10,84 @@
 #include <vector>
 
 #include "lohan_adam.h"
+#include "lohan_adam_tuning.h"
 #include "lohan_kernels.h"
 
 namespace {
 
+// Per-device facts, read once from the device attributes.
 constexpr int kMaxDevices = 64;
-std::atomic<int> g_cu_count[kMaxDevices];
+struct DeviceSlot {
+    std::atomic<int> cus{0};
+    std::atomic<size_t> lds_per_cu{0};
+};
+DeviceSlot g_device[kMaxDevices];
 
-// Launch shape (overridable through lohan_set_launch_config for tuning sweeps).
-// Automatic variant (-1): 64-lane workgroups, 1 vector per lane; the cache policy follows the
-// block's resident size (16 B/element): blocks that fit the 256 MiB memory-side cache keep the
-// default policy (measured +5 % there), everything larger streams past the caches.
+// Launch shape.  Automatic variant (-1): 64-lane workgroups, 1 vector per lane; the cache policy
+// follows the block's resident size (16 B/element): blocks that fit the memory-side cache keep
+// the default policy (measured +5 % there), everything larger streams past the caches.  The
+// reduction's loads follow the same rule, so that for a block that fits, the update's read of the
+// gradients hits what the reduction left behind.  HIP has no attribute for the size of the
+// memory-side cache (hipDeviceAttributeL2CacheSize is the per-XCD L2), so MI355X's 256 MiB is a
+// constant here.
 constexpr int kAutoAdamVariant = -1;
 constexpr int kStreamingVariant = 0 | (0 << 2) | (2 << 4);
 constexpr int kCacheResidentVariant = 0 | (0 << 2) | (0 << 4);
-constexpr uint64_t kCacheResidentBytes = 256ull << 20;
+constexpr uint64_t kMemorySideCacheBytes = 256ull << 20;
 constexpr int kDefaultAdamWgsPerCu = 0;                       // one tile per workgroup
 constexpr int kDefaultAdamWavesPerCu = 11;                    // occupancy throttle
 constexpr int kDefaultReduceWgsPerCu = 4;
-std::atomic<int> g_adam_variant{kAutoAdamVariant};
-std::atomic<int> g_adam_wgs_per_cu{kDefaultAdamWgsPerCu};
-std::atomic<int> g_adam_waves_per_cu{kDefaultAdamWavesPerCu};
-std::atomic<int> g_reduce_wgs_per_cu{kDefaultReduceWgsPerCu};
+constexpr int kAutoReducePolicy = -1;
 
-// Compute units of the current device (the device `stream` must belong to).  Returns 0 on error.
-int current_cu_count()
+// Tuning override (lohan_adam_tuning.h): per calling thread, so that a sweep on one thread never
+// changes the launch shape under calls made by another.
+struct LaunchOverride {
+    int adam_variant = kAutoAdamVariant;
+    int adam_wgs_per_cu = kDefaultAdamWgsPerCu;
+    int adam_waves_per_cu = kDefaultAdamWavesPerCu;
+    int reduce_wgs_per_cu = kDefaultReduceWgsPerCu;
+    int reduce_policy = kAutoReducePolicy;
+};
+thread_local LaunchOverride t_launch;
+
+// Facts about the current device (the device `stream` must belong to).  cus == 0 on error.
+lohan::DeviceInfo current_device()
 {
+    lohan::DeviceInfo info{0, 0};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (dev >= 0 && dev < kMaxDevices) {
-        int cached = g_cu_count[dev].load(std::memory_order_relaxed);
-        if (cached > 0) return cached;
+    if (hipGetDevice(&dev) != hipSuccess) return info;
+    const bool cacheable = dev >= 0 && dev < kMaxDevices;
+    if (cacheable) {
+        info.cus = g_device[dev].cus.load(std::memory_order_acquire);
+        info.lds_per_cu = g_device[dev].lds_per_cu.load(std::memory_order_relaxed);
+        if (info.cus > 0 && info.lds_per_cu > 0) return info;
     }
-    int cus = 0;
+    int cus = 0, lds = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        cus <= 0)
-        return 0;
-    if (dev >= 0 && dev < kMaxDevices) g_cu_count[dev].store(cus, std::memory_order_relaxed);
-    return cus;
+        cus <= 0 ||
+        hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) !=
+            hipSuccess ||
+        lds <= 0)
+        return lohan::DeviceInfo{0, 0};
+    info.cus = cus;
+    info.lds_per_cu = (size_t)lds;
+    if (cacheable) {
+        g_device[dev].lds_per_cu.store(info.lds_per_cu, std::memory_order_relaxed);
+        g_device[dev].cus.store(info.cus, std::memory_order_release);
+    }
+    return info;
+}
+
+uint32_t reduce_workgroups(const lohan::DeviceInfo &dev)
+{
+    return (uint32_t)dev.cus * (uint32_t)t_launch.reduce_wgs_per_cu;
+}
+
+// Whether the reduction over a block of n elements streams past the caches.
+bool reduce_streams(uint64_t n)
+{
+    if (t_launch.reduce_policy >= 0) return t_launch.reduce_policy != 0;
+    return n * 16 > kMemorySideCacheBytes;
 }
 
 inline bool misaligned(const void *ptr, uintptr_t align)
@@ -94,11 +134,11 @@ lohan_status_t lohan_grad_overflow_check(const void *grad_fp16, uint64_t n,
     if (misaligned(grad_fp16, 16) || misaligned(overflow_flag, 4)) return LOHAN_ERR_ALIGN;
     lohan_status_t ws = check_workspace(workspace, workspace_bytes);
     if (ws != LOHAN_OK) return ws;
-    const int cus = current_cu_count();
-    if (cus <= 0) return LOHAN_ERR_HIP;
-    const uint32_t max_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
     hipError_t e = lohan::launch_grad_reduce(grad_fp16, n, false, 0.0, nullptr, overflow_flag,
-                                             workspace, max_wgs, stream);
+                                             workspace, reduce_workgroups(dev), reduce_streams(n),
+                                             stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -112,12 +152,12 @@ lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_s
     if (!finite_pos(loss_scale)) return LOHAN_ERR_ARG;
     lohan_status_t ws = check_workspace(workspace, workspace_bytes);
     if (ws != LOHAN_OK) return ws;
-    const int cus = current_cu_count();
-    if (cus <= 0) return LOHAN_ERR_HIP;
-    const uint32_t max_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
     const double inv = 1.0 / (double)loss_scale;
     hipError_t e = lohan::launch_grad_reduce(grad_fp16, n, true, inv * inv, sqnorm, overflow_flag,
-                                             workspace, max_wgs, stream);
+                                             workspace, reduce_workgroups(dev), reduce_streams(n),
+                                             stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -175,10 +215,10 @@ int kernel_mode(uint32_t flags)
 
 lohan::AdamLaunch adam_launch_for(uint64_t n)
 {
-    int variant = g_adam_variant.load();
+    int variant = t_launch.adam_variant;
     if (variant < 0)
-        variant = n * 16 <= kCacheResidentBytes ? kCacheResidentVariant : kStreamingVariant;
-    return lohan::AdamLaunch{variant, g_adam_wgs_per_cu.load(), g_adam_waves_per_cu.load()};
+        variant = n * 16 <= kMemorySideCacheBytes ? kCacheResidentVariant : kStreamingVariant;
+    return lohan::AdamLaunch{variant, t_launch.adam_wgs_per_cu, t_launch.adam_waves_per_cu};
 }
 
 }  // namespace
@@ -199,19 +239,19 @@ lohan_status_t lohan_adam_block_step(float *param_fp32, float *exp_avg, float *e
         st = check_workspace(workspace, workspace_bytes);
         if (st != LOHAN_OK) return st;
     }
-    const int cus = current_cu_count();
-    if (cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
     const lohan::StepScalars s =
         make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
     if (!prechecked) {
-        const uint32_t red_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
         hipError_t e = lohan::launch_grad_reduce(grad_fp16, n, false, 0.0, nullptr, overflow_flag,
-                                                 workspace, red_wgs, stream);
+                                                 workspace, reduce_workgroups(dev),
+                                                 reduce_streams(n), stream);
         if (e != hipSuccess) return LOHAN_ERR_HIP;
     }
     hipError_t e = lohan::launch_adam_block_step(
         param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n, s,
-        kernel_mode(flags), overflow_flag, nullptr, adam_launch_for(n), cus, stream);
+        kernel_mode(flags), overflow_flag, nullptr, adam_launch_for(n), dev, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -233,8 +273,8 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
     if (!finite_pos(max_norm)) return LOHAN_ERR_ARG;
     st = check_workspace(workspace, workspace_bytes);
     if (st != LOHAN_OK) return st;
-    const int cus = current_cu_count();
-    if (cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
     if (n == 0) return LOHAN_OK;
     const lohan::StepScalars s =
         make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
@@ -244,7 +284,7 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
     if (e != hipSuccess) return LOHAN_ERR_HIP;
     e = lohan::launch_adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out,
                                       n, s, kernel_mode(flags), overflow_flag, inv_dev,
-                                      adam_launch_for(n), cus, stream);
+                                      adam_launch_for(n), dev, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -269,14 +309,14 @@ lohan_status_t lohan_adam_block_step_out_of_place(
     if (n != 0 && (param_fp32_out == param_fp32_in || exp_avg_out == exp_avg_in ||
                    exp_avg_sq_out == exp_avg_sq_in))
         return LOHAN_ERR_ARG;
-    const int cus = current_cu_count();
-    if (cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
     const lohan::StepScalars s =
         make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
     hipError_t e = lohan::launch_adam_block_step_oop(
         param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16, param_fp32_out, exp_avg_out,
         exp_avg_sq_out, param_bf16_out, n, s, kernel_mode(flags), overflow_flag,
-        adam_launch_for(n), cus, stream);
+        adam_launch_for(n), dev, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -302,14 +342,14 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
     if (clip && !finite_pos(max_norm)) return LOHAN_ERR_ARG;
     lohan_status_t st = check_workspace(workspace, workspace_bytes);
     if (st != LOHAN_OK) return st;
-    const int cus = current_cu_count();
-    if (cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
 
     const bool prechecked = (flags & LOHAN_FLAG_PRECHECKED) != 0;
     const bool want_norm = clip || sqnorms != nullptr;
     const lohan::StepScalars s =
         make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
-    const uint32_t red_wgs = (uint32_t)cus * (uint32_t)g_reduce_wgs_per_cu.load();
+    const uint32_t red_wgs = reduce_workgroups(dev);
     const double inv = 1.0 / (double)loss_scale;
     char *ws = reinterpret_cast<char *>(workspace);
     float *inv_dev = reinterpret_cast<float *>(ws + lohan::kScalarsOffset);
@@ -347,7 +387,8 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
         if (!prechecked || want_norm) {
             hipError_t e = lohan::launch_multi_grad_reduce(
                 args, count, want_norm, inv * inv, want_norm ? norms_dev : nullptr,
-                prechecked ? nullptr : flags_dev, workspace, red_wgs, stream);
+                prechecked ? nullptr : flags_dev, workspace, red_wgs, reduce_streams(total),
+                stream);
             if (e != hipSuccess) return LOHAN_ERR_HIP;
         }
         if (clip) {
@@ -357,7 +398,7 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
         }
         hipError_t e = lohan::launch_adam_multi_block_step(
             args, count, s, kernel_mode(flags), flags_dev, clip ? inv_dev : nullptr,
-            adam_launch_for(total), cus, stream);
+            adam_launch_for(total), dev, stream);
         if (e != hipSuccess) return LOHAN_ERR_HIP;
         first += count;
     }
@@ -439,13 +480,13 @@ lohan_status_t lohan_ring_adam_block_step(void *ring, uint32_t num_blocks, uint3
     if (step < 1 || !finite_pos(loss_scale) || !finite_nonneg(lr) || !finite_nonneg(eps) ||
         !finite_nonneg(weight_decay) || !unit_interval(beta1) || !unit_interval(beta2))
         return LOHAN_ERR_ARG;
-    const int cus = current_cu_count();
-    if (cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
     const lohan::StepScalars s =
         make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
     hipError_t e = lohan::launch_adam_ring_step(lohan::ring_view(ring, num_blocks), block,
                                                 grad_fp16, n, s, kernel_mode(flags),
-                                                adam_launch_for(n), cus, stream);
+                                                adam_launch_for(n), dev, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -527,29 +568,52 @@ float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm)
     return (float)((double)loss_scale / coef);
 }
 
-lohan_status_t lohan_set_launch_config(int adam_variant, int adam_workgroups_per_cu,
-                                       int adam_waves_per_cu, int reduce_workgroups_per_cu)
+lohan_status_t lohan_workspace_init(void *workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    lohan_status_t ws = check_workspace(workspace, workspace_bytes);
+    if (ws != LOHAN_OK) return ws;
+    return lohan::launch_workspace_init(workspace, stream) == hipSuccess ? LOHAN_OK
+                                                                         : LOHAN_ERR_HIP;
+}
+
+lohan_status_t lohan_tuning_set_launch_config(int adam_variant, int adam_workgroups_per_cu,
+                                              int adam_waves_per_cu, int reduce_workgroups_per_cu,
+                                              int reduce_policy)
 {
     if (adam_variant < 0) adam_variant = kAutoAdamVariant;
     else if (!lohan::adam_variant_valid(adam_variant)) return LOHAN_ERR_ARG;
-    if (adam_workgroups_per_cu > 4096 || adam_waves_per_cu > 32 || reduce_workgroups_per_cu > 16)
+    if (adam_workgroups_per_cu > 4096 || adam_waves_per_cu > 32 || reduce_workgroups_per_cu > 16 ||
+        reduce_policy > 1)
         return LOHAN_ERR_ARG;
-    g_adam_variant.store(adam_variant);
-    g_adam_wgs_per_cu.store(adam_workgroups_per_cu < 0 ? kDefaultAdamWgsPerCu
-                                                       : adam_workgroups_per_cu);
-    g_adam_waves_per_cu.store(adam_waves_per_cu < 0 ? kDefaultAdamWavesPerCu : adam_waves_per_cu);
-    g_reduce_wgs_per_cu.store(reduce_workgroups_per_cu <= 0 ? kDefaultReduceWgsPerCu
-                                                            : reduce_workgroups_per_cu);
+    t_launch.adam_variant = adam_variant;
+    t_launch.adam_wgs_per_cu = adam_workgroups_per_cu < 0 ? kDefaultAdamWgsPerCu
+                                                          : adam_workgroups_per_cu;
+    t_launch.adam_waves_per_cu = adam_waves_per_cu < 0 ? kDefaultAdamWavesPerCu
+                                                       : adam_waves_per_cu;
+    t_launch.reduce_wgs_per_cu = reduce_workgroups_per_cu <= 0 ? kDefaultReduceWgsPerCu
+                                                               : reduce_workgroups_per_cu;
+    t_launch.reduce_policy = reduce_policy < 0 ? kAutoReducePolicy : reduce_policy;
     return LOHAN_OK;
 }
 
-void lohan_get_launch_config(int *adam_variant, int *adam_workgroups_per_cu,
-                             int *adam_waves_per_cu, int *reduce_workgroups_per_cu)
+lohan_status_t lohan_tuning_device_info(int *compute_units, size_t *lds_bytes_per_cu)
 {
-    if (adam_variant) *adam_variant = g_adam_variant.load();
-    if (adam_workgroups_per_cu) *adam_workgroups_per_cu = g_adam_wgs_per_cu.load();
-    if (adam_waves_per_cu) *adam_waves_per_cu = g_adam_waves_per_cu.load();
-    if (reduce_workgroups_per_cu) *reduce_workgroups_per_cu = g_reduce_wgs_per_cu.load();
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
+    if (compute_units) *compute_units = dev.cus;
+    if (lds_bytes_per_cu) *lds_bytes_per_cu = dev.lds_per_cu;
+    return LOHAN_OK;
+}
+
+void lohan_tuning_get_launch_config(int *adam_variant, int *adam_workgroups_per_cu,
+                                    int *adam_waves_per_cu, int *reduce_workgroups_per_cu,
+                                    int *reduce_policy)
+{
+    if (adam_variant) *adam_variant = t_launch.adam_variant;
+    if (adam_workgroups_per_cu) *adam_workgroups_per_cu = t_launch.adam_wgs_per_cu;
+    if (adam_waves_per_cu) *adam_waves_per_cu = t_launch.adam_waves_per_cu;
+    if (reduce_workgroups_per_cu) *reduce_workgroups_per_cu = t_launch.reduce_wgs_per_cu;
+    if (reduce_policy) *reduce_policy = t_launch.reduce_policy;
 }
 
 }  // extern "C"

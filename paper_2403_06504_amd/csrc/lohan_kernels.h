@@ -75,19 +75,31 @@ inline RingView ring_view(void *ring, uint32_t num_blocks)
 
 // Workspace layout: kMaxPartials doubles, then kMaxPartials uint32 flags, then the per-call
 // scalars: kMultiMaxBlocks unscale factors (float; a single-block clipped step uses the first),
-// then kMultiMaxBlocks squared norms (double) for multi-block calls whose caller wants none.
+// then kMultiMaxBlocks squared norms (double) for multi-block calls whose caller wants none,
+// then kMultiMaxBlocks uint32 ticket counters of the gradient reduction (a single-block call uses
+// the first).  The counters are the only part with an invariant: zero between calls
+// (launch_workspace_init sets it up, every reduction restores it).
 constexpr uint32_t kMaxPartials = 4096;
 constexpr size_t kScalarsOffset = (size_t)kMaxPartials * (sizeof(double) + sizeof(uint32_t));
 constexpr size_t kNormsOffset = kScalarsOffset + 256;
-constexpr size_t kWorkspaceBytes = kNormsOffset + kMultiMaxBlocks * sizeof(double);
+constexpr size_t kCountersOffset = kNormsOffset + kMultiMaxBlocks * sizeof(double);
+constexpr size_t kWorkspaceBytes = kCountersOffset + kMultiMaxBlocks * sizeof(uint32_t);
 static_assert(kMultiMaxBlocks * sizeof(float) <= 256, "unscale factors must fit their area");
 
+// What the launchers need to know about the device the stream belongs to.
+struct DeviceInfo {
+    int cus;             // compute units
+    size_t lds_per_cu;   // bytes of LDS per compute unit (sizes the occupancy throttle)
+};
+
+// Zero the ticket counters of a workspace (a one-workgroup fill kernel).
+hipError_t launch_workspace_init(void *workspace, hipStream_t stream);
+
+// stream_past_caches: nontemporal loads (blocks far larger than the memory-side cache) instead
+// of the default policy (blocks that fit it, so that the update's read of the gradients hits).
 hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm, double inv2,
                               double *sqnorm, uint32_t *flag, void *workspace, uint32_t max_wgs,
-                              hipStream_t stream);
-
-// LDS per compute unit on gfx950; used only to size the occupancy throttle.
-constexpr size_t kLdsBytesPerCu = 160 * 1024;
+                              bool stream_past_caches, hipStream_t stream);
 
 // Launch shape of the Adam kernel.
 struct AdamLaunch {
@@ -103,19 +115,19 @@ bool adam_variant_valid(int variant);
 hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
                                   void *p16, uint64_t n, const StepScalars &s, int mode,
                                   const uint32_t *flag, const float *inv_override,
-                                  const AdamLaunch &cfg, int cus, hipStream_t stream);
+                                  const AdamLaunch &cfg, const DeviceInfo &dev, hipStream_t stream);
 
 // Out-of-place form with the overflow test fused in (clears *flag, then one 28 B/element pass).
 hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, const float *v_in,
                                       const void *grad_fp16, float *p_out, float *m_out,
                                       float *v_out, void *p16, uint64_t n, const StepScalars &s,
-                                      int mode, uint32_t *flag, const AdamLaunch &cfg, int cus,
-                                      hipStream_t stream);
+                                      int mode, uint32_t *flag, const AdamLaunch &cfg,
+                                      const DeviceInfo &dev, hipStream_t stream);
 
 // Ring form: the step of `block` from its current slot into the spare, then the commit.
 hipError_t launch_adam_ring_step(const RingView &ring, uint32_t block, const void *grad_fp16,
                                  uint64_t n, const StepScalars &s, int mode,
-                                 const AdamLaunch &cfg, int cus, hipStream_t stream);
+                                 const AdamLaunch &cfg, const DeviceInfo &dev, hipStream_t stream);
 
 // sqnorm[0..count) -> inv_out[0..count)
 hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,
@@ -125,11 +137,12 @@ hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_n
 // arrays indexed by block.
 hipError_t launch_multi_grad_reduce(const MultiArgs &args, uint32_t num_blocks, bool with_norm,
                                     double inv2, double *sqnorms, uint32_t *flags,
-                                    void *workspace, uint32_t max_wgs, hipStream_t stream);
+                                    void *workspace, uint32_t max_wgs, bool stream_past_caches,
+                                    hipStream_t stream);
 hipError_t launch_adam_multi_block_step(const MultiArgs &args, uint32_t num_blocks,
                                         const StepScalars &s, int mode, const uint32_t *flags,
-                                        const float *inv_override, const AdamLaunch &cfg, int cus,
-                                        hipStream_t stream);
+                                        const float *inv_override, const AdamLaunch &cfg,
+                                        const DeviceInfo &dev, hipStream_t stream);
 
 }  // namespace lohan
 

@@ -27,9 +27,6 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;            // 4 wavefronts of 64 lanes
-constexpr int kWaves = kThreads / 64;
-
 template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T *ptr)
 {
@@ -46,8 +43,11 @@ __device__ __forceinline__ void st(T *ptr, T val)
 
 // ------------------------------------------------------------------------------------------------
 // Gradient reduction: overflow flag (integer test on the raw fp16 bits) and, optionally, the sum
-// of squares.  Stage 1 writes one partial per workgroup; stage 2 (one workgroup) combines the
-// partials in a fixed order, so the result does not depend on scheduling.
+// of squares, in ONE launch.  Every workgroup publishes one partial and takes a ticket from a
+// counter in the workspace; the workgroup that draws the last ticket combines all partials in a
+// fixed order (so the result does not depend on scheduling or on which workgroup came last),
+// writes the outputs and puts the counter back to zero for the next call.  Nobody waits for
+// anybody: a workgroup that is not last simply ends.
 // ------------------------------------------------------------------------------------------------
 
 // Both halves of a packed pair at once: (h & 0x7FFF) + 0x0400 carries into bit 15 exactly when
@@ -87,20 +87,73 @@ __device__ __forceinline__ void reduce_vec(u32x4 q, uint32_t &ovf, double &acc)
     }
 }
 
-// Stage 1: kReduceThreads-lane workgroups (one wavefront each: measured best with eight 128-bit
-// loads in flight per lane and four such workgroups per CU), persistent over interleaved tiles.
+// kReduceThreads-lane workgroups (one wavefront each: measured best with eight 128-bit loads in
+// flight per lane and four such workgroups per CU), persistent over interleaved tiles.
 constexpr int kReduceThreads = 64;
 constexpr int kReduceUnroll = 8;
+constexpr int kReduceWaves = kReduceThreads / 64;
 
-// Workgroup `wg` of `nwg` reduces its interleaved share of g[0, n) and writes partial `slot`.
-template <bool WITH_NORM, int UNROLL>
+// Device-scope accesses to the partials and the ticket counter: they are written by one
+// workgroup and read by another within the same launch, so they must not be served from a
+// cache that is private to a CU or to an XCD.
+template <typename T>
+__device__ __forceinline__ T ld_device_scope(const T *ptr)
+{
+    return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void st_device_scope(T *ptr, T val)
+{
+    __hip_atomic_store(ptr, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Sum / OR over the workgroup: wavefront butterfly over the 64 lanes (fixed pairing), then LDS
+// across the wavefronts in index order.  The totals are valid in thread 0.
+template <bool WITH_NORM>
+__device__ __forceinline__ void workgroup_combine(uint32_t tid, double &acc, uint32_t &any)
+{
+    any = __builtin_amdgcn_ballot_w64(any != 0) != 0 ? 1u : 0u;
+    if constexpr (WITH_NORM) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    }
+    if constexpr (kReduceWaves > 1) {
+        __shared__ double s_sum[kReduceWaves];
+        __shared__ uint32_t s_flag[kReduceWaves];
+        const uint32_t wave = tid >> 6, lane = tid & 63u;
+        if (lane == 0) {
+            s_sum[wave] = acc;
+            s_flag[wave] = any;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            acc = 0.0;
+            any = 0;
+#pragma unroll
+            for (int w = 0; w < kReduceWaves; ++w) {
+                acc += s_sum[w];
+                any |= s_flag[w];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Workgroup `wg` of `nwg` reduces its interleaved share of g[0, n), publishes partial
+// `slot_base + wg`, and -- if it is the last of the nwg to do so -- combines the nwg partials
+// into sqnorm_out / flag_out (either may be NULL).  NT: stream the gradients past the caches
+// (blocks far larger than the memory-side cache) or leave them cached for the update that
+// follows (blocks that fit it).  inv2 = (1/loss_scale)^2 in float64 turns the raw sum of squares
+// into the squared norm of the unscaled gradients.
+template <bool WITH_NORM, int UNROLL, bool NT>
 __device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g, uint64_t n,
-                                                 uint32_t wg, uint32_t nwg, uint32_t slot,
-                                                 double *__restrict__ partial_sum,
-                                                 uint32_t *__restrict__ partial_flag)
+                                                 uint32_t wg, uint32_t nwg, uint32_t slot_base,
+                                                 double *partial_sum, uint32_t *partial_flag,
+                                                 uint32_t *counter, double inv2,
+                                                 double *__restrict__ sqnorm_out,
+                                                 uint32_t *__restrict__ flag_out)
 {
     constexpr int kThreads = kReduceThreads;
-    constexpr int kWaves = kThreads / 64;
     constexpr uint64_t kVec = 8;                               // halves per 128-bit load
     constexpr uint64_t kTile = (uint64_t)kThreads * kVec * UNROLL;
     const uint32_t tid = threadIdx.x;
@@ -113,7 +166,7 @@ __device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g,
         const u32x4 *src = reinterpret_cast<const u32x4 *>(g + tile * kTile) + tid;
         u32x4 q[UNROLL];
 #pragma unroll
-        for (int j = 0; j < UNROLL; ++j) q[j] = ld<true>(src + j * kThreads);
+        for (int j = 0; j < UNROLL; ++j) q[j] = ld<NT>(src + j * kThreads);
 #pragma unroll
         for (int j = 0; j < UNROLL; ++j) reduce_vec<WITH_NORM>(q[j], ovf, acc);
     }
@@ -132,101 +185,72 @@ __device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g,
         if constexpr (WITH_NORM) acc += (double)square_pair(h, 0.0f);
     }
 
-    // Wavefront level: butterfly over the 64 lanes (fixed pairing), then LDS across the waves.
-    uint32_t any = __builtin_amdgcn_ballot_w64(ovf != 0) != 0 ? 1u : 0u;
-    if constexpr (WITH_NORM) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    }
-    __shared__ double s_sum[kWaves];
-    __shared__ uint32_t s_flag[kWaves];
-    const uint32_t wave = tid >> 6, lane = tid & 63u;
-    if (lane == 0) {
-        s_sum[wave] = acc;
-        s_flag[wave] = any;
+    workgroup_combine<WITH_NORM>(tid, acc, ovf);
+
+    // Publish this workgroup's partial, then take a ticket.  The release half of the ticket's
+    // ordering makes the partial visible device-wide before the ticket is.
+    __shared__ uint32_t s_is_last;
+    if (tid == 0) {
+        if constexpr (WITH_NORM) st_device_scope(partial_sum + slot_base + wg, acc);
+        st_device_scope(partial_flag + slot_base + wg, ovf);
+        const uint32_t ticket =
+            __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        s_is_last = ticket == nwg - 1 ? 1u : 0u;
     }
     __syncthreads();
+    if (s_is_last == 0u) return;
+
+    // Last arrival: every partial has been published.  Combine them in a fixed order (lane l takes
+    // partials l, l + kThreads, ... in turn; then the same butterfly as above).
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    double total = 0.0;
+    uint32_t any = 0;
+    for (uint32_t i = tid; i < nwg; i += kThreads) {
+        if constexpr (WITH_NORM) total += ld_device_scope(partial_sum + slot_base + i);
+        any |= ld_device_scope(partial_flag + slot_base + i);
+    }
+    workgroup_combine<WITH_NORM>(tid, total, any);
     if (tid == 0) {
-        double total = 0.0;
-        uint32_t f = 0;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            total += s_sum[w];
-            f |= s_flag[w];
+        if constexpr (WITH_NORM) {
+            if (sqnorm_out != nullptr) *sqnorm_out = total * inv2;
         }
-        if constexpr (WITH_NORM) partial_sum[slot] = total;
-        partial_flag[slot] = f;
+        if (flag_out != nullptr) *flag_out = any;
+        st_device_scope(counter, 0u);                       // ready for the next call
     }
 }
 
-template <bool WITH_NORM, int UNROLL>
+template <bool WITH_NORM, int UNROLL, bool NT>
 __global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *__restrict__ g,
-                                                                uint64_t n,
-                                                                double *__restrict__ partial_sum,
-                                                                uint32_t *__restrict__ partial_flag)
+                                                                uint64_t n, double *partial_sum,
+                                                                uint32_t *partial_flag,
+                                                                uint32_t *counter, double inv2,
+                                                                double *__restrict__ sqnorm,
+                                                                uint32_t *__restrict__ flag)
 {
-    grad_reduce_body<WITH_NORM, UNROLL>(g, n, blockIdx.x, gridDim.x, blockIdx.x, partial_sum,
-                                        partial_flag);
+    grad_reduce_body<WITH_NORM, UNROLL, NT>(g, n, blockIdx.x, gridDim.x, 0u, partial_sum,
+                                            partial_flag, counter, inv2, sqnorm, flag);
 }
 
 // Several blocks in one launch: grid (workgroups per block, blocks); block b's partials occupy
-// slots [b * gridDim.x, (b + 1) * gridDim.x).
-template <bool WITH_NORM, int UNROLL>
+// slots [b * gridDim.x, (b + 1) * gridDim.x), its ticket counter is counters[b] and its results go
+// to sqnorms[b] and flags[b].
+template <bool WITH_NORM, int UNROLL, bool NT>
 __global__ __launch_bounds__(kReduceThreads) void k_multi_grad_reduce(
-    MultiArgs args, double *__restrict__ partial_sum, uint32_t *__restrict__ partial_flag)
+    MultiArgs args, double *partial_sum, uint32_t *partial_flag, uint32_t *counters, double inv2,
+    double *__restrict__ sqnorms, uint32_t *__restrict__ flags)
 {
     const uint32_t b = blockIdx.y;
-    grad_reduce_body<WITH_NORM, UNROLL>(args.d[b].g, args.d[b].n, blockIdx.x, gridDim.x,
-                                        b * gridDim.x + blockIdx.x, partial_sum, partial_flag);
+    grad_reduce_body<WITH_NORM, UNROLL, NT>(args.d[b].g, args.d[b].n, blockIdx.x, gridDim.x,
+                                            b * gridDim.x, partial_sum, partial_flag, counters + b,
+                                            inv2, sqnorms != nullptr ? sqnorms + b : nullptr,
+                                            flags != nullptr ? flags + b : nullptr);
 }
 
-// Stage 2: one workgroup per block (blockIdx.x = b; a single-block call launches one).  Block
-// b's partials are slots [b * nparts, (b + 1) * nparts); its results go to sqnorm[b] and flag[b].
-// inv2 = (1/loss_scale)^2 in float64 turns the raw sum of squares into the squared norm of the
-// unscaled gradients.
-template <bool WITH_NORM>
-__global__ __launch_bounds__(kThreads) void k_grad_finalize(const double *__restrict__ partial_sum,
-                                                            const uint32_t *__restrict__ partial_flag,
-                                                            uint32_t nparts, double inv2,
-                                                            double *__restrict__ sqnorm,
-                                                            uint32_t *__restrict__ flag)
+// Ticket counters start at zero; afterwards every reduction leaves them at zero.
+__global__ void k_workspace_init(uint32_t *counters, uint32_t count)
 {
-    const uint32_t tid = threadIdx.x;
-    const uint32_t b = blockIdx.x;
-    partial_sum += (size_t)b * nparts;
-    partial_flag += (size_t)b * nparts;
-    double acc = 0.0;
-    uint32_t f = 0;
-    for (uint32_t i = tid; i < nparts; i += kThreads) {
-        if constexpr (WITH_NORM) acc += partial_sum[i];
-        f |= partial_flag[i];
-    }
-    uint32_t any = __builtin_amdgcn_ballot_w64(f != 0) != 0 ? 1u : 0u;
-    if constexpr (WITH_NORM) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    }
-    __shared__ double s_sum[kWaves];
-    __shared__ uint32_t s_flag[kWaves];
-    const uint32_t wave = tid >> 6, lane = tid & 63u;
-    if (lane == 0) {
-        s_sum[wave] = acc;
-        s_flag[wave] = any;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        double total = 0.0;
-        uint32_t r = 0;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            total += s_sum[w];
-            r |= s_flag[w];
-        }
-        if constexpr (WITH_NORM) {
-            if (sqnorm != nullptr) sqnorm[b] = total * inv2;
-        }
-        if (flag != nullptr) flag[b] = r;
-    }
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) counters[i] = 0u;
 }
 
 // n == 0: nothing to reduce, but the outputs are still defined.
@@ -624,34 +648,62 @@ static uint32_t reduce_grid(uint64_t n, uint64_t tile, uint32_t max_wgs)
     return (uint32_t)(want < max_wgs ? want : max_wgs);
 }
 
+// The parts of a workspace (layout in lohan_kernels.h).
+struct WorkspaceView {
+    double *partial_sum;
+    uint32_t *partial_flag;
+    uint32_t *counters;
+};
+
+static WorkspaceView workspace_view(void *workspace)
+{
+    char *base = reinterpret_cast<char *>(workspace);
+    return WorkspaceView{reinterpret_cast<double *>(base),
+                         reinterpret_cast<uint32_t *>(base + sizeof(double) * kMaxPartials),
+                         reinterpret_cast<uint32_t *>(base + kCountersOffset)};
+}
+
+hipError_t launch_workspace_init(void *workspace, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_workspace_init, dim3(1), dim3(64), 0, stream,
+                       workspace_view(workspace).counters, kMultiMaxBlocks);
+    return hipGetLastError();
+}
+
+template <bool WITH_NORM>
+static void launch_reduce_policy(bool stream_past_caches, uint32_t grid, hipStream_t stream,
+                                 const uint16_t *g, uint64_t n, const WorkspaceView &ws,
+                                 double inv2, double *sqnorm, uint32_t *flag)
+{
+    constexpr int kUnroll = kReduceUnroll;
+    if (stream_past_caches)
+        hipLaunchKernelGGL((k_grad_reduce<WITH_NORM, kUnroll, true>), dim3(grid),
+                           dim3(kReduceThreads), 0, stream, g, n, ws.partial_sum, ws.partial_flag,
+                           ws.counters, inv2, sqnorm, flag);
+    else
+        hipLaunchKernelGGL((k_grad_reduce<WITH_NORM, kUnroll, false>), dim3(grid),
+                           dim3(kReduceThreads), 0, stream, g, n, ws.partial_sum, ws.partial_flag,
+                           ws.counters, inv2, sqnorm, flag);
+}
+
 hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm, double inv2,
                               double *sqnorm, uint32_t *flag, void *workspace, uint32_t max_wgs,
-                              hipStream_t stream)
+                              bool stream_past_caches, hipStream_t stream)
 {
     if (n == 0) {
         hipLaunchKernelGGL(k_grad_empty, dim3(1), dim3(64), 0, stream, sqnorm, flag);
         return hipGetLastError();
     }
-    constexpr int kUnroll = kReduceUnroll;
     if (max_wgs > kMaxPartials) max_wgs = kMaxPartials;
-    const uint32_t grid = reduce_grid(n, (uint64_t)kReduceThreads * 8 * kUnroll, max_wgs);
-    double *psum = reinterpret_cast<double *>(workspace);
-    uint32_t *pflag = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(workspace) +
-                                                   sizeof(double) * kMaxPartials);
+    const uint32_t grid =
+        reduce_grid(n, (uint64_t)kReduceThreads * 8 * kReduceUnroll, max_wgs);
+    const WorkspaceView ws = workspace_view(workspace);
     const uint16_t *g = reinterpret_cast<const uint16_t *>(grad_fp16);
-    if (with_norm) {
-        hipLaunchKernelGGL((k_grad_reduce<true, kUnroll>), dim3(grid), dim3(kReduceThreads), 0,
-                           stream,
-                           g, n, psum, pflag);
-        hipLaunchKernelGGL((k_grad_finalize<true>), dim3(1), dim3(kThreads), 0, stream, psum,
-                           pflag, grid, inv2, sqnorm, flag);
-    } else {
-        hipLaunchKernelGGL((k_grad_reduce<false, kUnroll>), dim3(grid), dim3(kReduceThreads), 0,
-                           stream,
-                           g, n, psum, pflag);
-        hipLaunchKernelGGL((k_grad_finalize<false>), dim3(1), dim3(kThreads), 0, stream, psum,
-                           pflag, grid, inv2, sqnorm, flag);
-    }
+    if (with_norm)
+        launch_reduce_policy<true>(stream_past_caches, grid, stream, g, n, ws, inv2, sqnorm, flag);
+    else
+        launch_reduce_policy<false>(stream_past_caches, grid, stream, g, n, ws, inv2, sqnorm,
+                                    flag);
     return hipGetLastError();
 }
 
@@ -663,13 +715,29 @@ hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_n
     return hipGetLastError();
 }
 
+template <bool WITH_NORM>
+static void launch_multi_reduce_policy(bool stream_past_caches, dim3 grid, hipStream_t stream,
+                                       const MultiArgs &args, const WorkspaceView &ws,
+                                       double inv2, double *sqnorms, uint32_t *flags)
+{
+    constexpr int kUnroll = kReduceUnroll;
+    if (stream_past_caches)
+        hipLaunchKernelGGL((k_multi_grad_reduce<WITH_NORM, kUnroll, true>), grid,
+                           dim3(kReduceThreads), 0, stream, args, ws.partial_sum, ws.partial_flag,
+                           ws.counters, inv2, sqnorms, flags);
+    else
+        hipLaunchKernelGGL((k_multi_grad_reduce<WITH_NORM, kUnroll, false>), grid,
+                           dim3(kReduceThreads), 0, stream, args, ws.partial_sum, ws.partial_flag,
+                           ws.counters, inv2, sqnorms, flags);
+}
+
 hipError_t launch_multi_grad_reduce(const MultiArgs &args, uint32_t num_blocks, bool with_norm,
                                     double inv2, double *sqnorms, uint32_t *flags,
-                                    void *workspace, uint32_t max_wgs, hipStream_t stream)
+                                    void *workspace, uint32_t max_wgs, bool stream_past_caches,
+                                    hipStream_t stream)
 {
     if (num_blocks == 0 || num_blocks > kMultiMaxBlocks) return hipErrorInvalidValue;
-    constexpr int kUnroll = kReduceUnroll;
-    constexpr uint64_t kTile = (uint64_t)kReduceThreads * 8 * kUnroll;
+    constexpr uint64_t kTile = (uint64_t)kReduceThreads * 8 * kReduceUnroll;
     uint64_t longest = 0;
     for (uint32_t b = 0; b < num_blocks; ++b)
         if (args.d[b].n > longest) longest = args.d[b].n;
@@ -677,21 +745,14 @@ hipError_t launch_multi_grad_reduce(const MultiArgs &args, uint32_t num_blocks, 
     uint32_t per_block = (max_wgs + num_blocks - 1) / num_blocks;
     if (per_block > kMaxPartials / num_blocks) per_block = kMaxPartials / num_blocks;
     per_block = reduce_grid(longest, kTile, per_block);
-    double *psum = reinterpret_cast<double *>(workspace);
-    uint32_t *pflag = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(workspace) +
-                                                   sizeof(double) * kMaxPartials);
+    const WorkspaceView ws = workspace_view(workspace);
     const dim3 grid(per_block, num_blocks);
-    if (with_norm) {
-        hipLaunchKernelGGL((k_multi_grad_reduce<true, kUnroll>), grid, dim3(kReduceThreads), 0,
-                           stream, args, psum, pflag);
-        hipLaunchKernelGGL((k_grad_finalize<true>), dim3(num_blocks), dim3(kThreads), 0, stream,
-                           psum, pflag, per_block, inv2, sqnorms, flags);
-    } else {
-        hipLaunchKernelGGL((k_multi_grad_reduce<false, kUnroll>), grid, dim3(kReduceThreads), 0,
-                           stream, args, psum, pflag);
-        hipLaunchKernelGGL((k_grad_finalize<false>), dim3(num_blocks), dim3(kThreads), 0, stream,
-                           psum, pflag, per_block, inv2, sqnorms, flags);
-    }
+    if (with_norm)
+        launch_multi_reduce_policy<true>(stream_past_caches, grid, stream, args, ws, inv2, sqnorms,
+                                         flags);
+    else
+        launch_multi_reduce_policy<false>(stream_past_caches, grid, stream, args, ws, inv2,
+                                          sqnorms, flags);
     return hipGetLastError();
 }
 
@@ -791,8 +852,8 @@ struct AdamGeometry {
     size_t lds;
 };
 
-static hipError_t adam_geometry(const void *kernel, uint64_t n, const AdamLaunch &cfg, int cus,
-                                AdamGeometry &out)
+static hipError_t adam_geometry(const void *kernel, uint64_t n, const AdamLaunch &cfg,
+                                const DeviceInfo &dev, AdamGeometry &out)
 {
     const int wg_index = cfg.variant & 3, unroll_index = (cfg.variant >> 2) & 3;
     const int wg = 64 << wg_index, unroll = 1 << unroll_index;
@@ -800,20 +861,20 @@ static hipError_t adam_geometry(const void *kernel, uint64_t n, const AdamLaunch
     uint64_t want = n / tile;
     if (want < 1) want = 1;
     if (cfg.max_wgs_per_cu > 0) {
-        const uint64_t cap = (uint64_t)cus * (uint64_t)cfg.max_wgs_per_cu;
+        const uint64_t cap = (uint64_t)dev.cus * (uint64_t)cfg.max_wgs_per_cu;
         if (want > cap) want = cap;
     }
     if (want > 0x7FFFFFFFull) want = 0x7FFFFFFFull;      // grid-stride loop covers the rest
 
     // Occupancy throttle: the kernels use no LDS, so a dynamic LDS request per workgroup sized
-    // as a fraction of the CU's 160 KB bounds how many workgroups (hence wavefronts, hence bytes
-    // in flight) a CU holds at once.
+    // as a fraction of the CU's LDS bounds how many workgroups (hence wavefronts, hence bytes in
+    // flight) a CU holds at once.
     size_t lds = 0;
     const int waves_per_wg = wg / 64;
     if (cfg.waves_per_cu > 0 && cfg.waves_per_cu < 32) {
         int wgs = cfg.waves_per_cu / waves_per_wg;
         if (wgs < 1) wgs = 1;
-        lds = (size_t)(kLdsBytesPerCu / wgs) / 256 * 256;
+        lds = (size_t)(dev.lds_per_cu / wgs) / 256 * 256;
         if (lds > 64 * 1024) {
             hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)lds);
@@ -829,14 +890,15 @@ static hipError_t adam_geometry(const void *kernel, uint64_t n, const AdamLaunch
 hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad_fp16,
                                   void *p16, uint64_t n, const StepScalars &s, int mode,
                                   const uint32_t *flag, const float *inv_override,
-                                  const AdamLaunch &cfg, int cus, hipStream_t stream)
+                                  const AdamLaunch &cfg, const DeviceInfo &dev,
+                                  hipStream_t stream)
 {
     if (n == 0) return hipSuccess;
-    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    if (!adam_variant_valid(cfg.variant) || dev.cus <= 0) return hipErrorInvalidValue;
     adam_kernel_t kernel = pick_kernel<InPlaceFamily>(cfg.variant, mode);
     if (kernel == nullptr) return hipErrorInvalidValue;
     AdamGeometry geo;
-    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, cus, geo);
+    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, dev, geo);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(geo.grid), dim3(geo.wg), geo.lds, stream, p, m, v,
                        reinterpret_cast<const uint16_t *>(grad_fp16),
@@ -847,18 +909,18 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
 hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, const float *v_in,
                                       const void *grad_fp16, float *p_out, float *m_out,
                                       float *v_out, void *p16, uint64_t n, const StepScalars &s,
-                                      int mode, uint32_t *flag, const AdamLaunch &cfg, int cus,
-                                      hipStream_t stream)
+                                      int mode, uint32_t *flag, const AdamLaunch &cfg,
+                                      const DeviceInfo &dev, hipStream_t stream)
 {
     // The flag starts at 0 on the stream; the update kernel can only raise it.
     hipLaunchKernelGGL(k_grad_empty, dim3(1), dim3(64), 0, stream, (double *)nullptr, flag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n == 0) return e;
-    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    if (!adam_variant_valid(cfg.variant) || dev.cus <= 0) return hipErrorInvalidValue;
     adam_oop_kernel_t kernel = pick_kernel<OutOfPlaceFamily>(cfg.variant, mode);
     if (kernel == nullptr) return hipErrorInvalidValue;
     AdamGeometry geo;
-    e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, cus, geo);
+    e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, dev, geo);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(geo.grid), dim3(geo.wg), geo.lds, stream, p_in, m_in, v_in,
                        reinterpret_cast<const uint16_t *>(grad_fp16), p_out, m_out, v_out,
@@ -868,11 +930,11 @@ hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, cons
 
 hipError_t launch_adam_multi_block_step(const MultiArgs &args, uint32_t num_blocks,
                                         const StepScalars &s, int mode, const uint32_t *flags,
-                                        const float *inv_override, const AdamLaunch &cfg, int cus,
-                                        hipStream_t stream)
+                                        const float *inv_override, const AdamLaunch &cfg,
+                                        const DeviceInfo &dev, hipStream_t stream)
 {
     if (num_blocks == 0 || num_blocks > kMultiMaxBlocks) return hipErrorInvalidValue;
-    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    if (!adam_variant_valid(cfg.variant) || dev.cus <= 0) return hipErrorInvalidValue;
     uint64_t longest = 0;
     for (uint32_t b = 0; b < num_blocks; ++b)
         if (args.d[b].n > longest) longest = args.d[b].n;
@@ -880,7 +942,7 @@ hipError_t launch_adam_multi_block_step(const MultiArgs &args, uint32_t num_bloc
     adam_multi_kernel_t kernel = pick_kernel<MultiBlockFamily>(cfg.variant, mode);
     if (kernel == nullptr) return hipErrorInvalidValue;
     AdamGeometry geo;
-    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), longest, cfg, cus, geo);
+    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), longest, cfg, dev, geo);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(geo.grid, num_blocks), dim3(geo.wg), geo.lds, stream, args, s,
                        flags, inv_override);
@@ -889,14 +951,15 @@ hipError_t launch_adam_multi_block_step(const MultiArgs &args, uint32_t num_bloc
 
 hipError_t launch_adam_ring_step(const RingView &ring, uint32_t block, const void *grad_fp16,
                                  uint64_t n, const StepScalars &s, int mode,
-                                 const AdamLaunch &cfg, int cus, hipStream_t stream)
+                                 const AdamLaunch &cfg, const DeviceInfo &dev,
+                                  hipStream_t stream)
 {
     if (n == 0) return hipSuccess;
-    if (!adam_variant_valid(cfg.variant) || cus <= 0) return hipErrorInvalidValue;
+    if (!adam_variant_valid(cfg.variant) || dev.cus <= 0) return hipErrorInvalidValue;
     adam_ring_kernel_t kernel = pick_kernel<RingFamily>(cfg.variant, mode);
     if (kernel == nullptr) return hipErrorInvalidValue;
     AdamGeometry geo;
-    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, cus, geo);
+    hipError_t e = adam_geometry(reinterpret_cast<const void *>(kernel), n, cfg, dev, geo);
     if (e != hipSuccess) return e;
     unsigned long long *attempts = reinterpret_cast<unsigned long long *>(ring.attempts);
     unsigned long long *overflow_attempt =

@@ -116,6 +116,10 @@ lohan_status_t lohan_offload_create(lohan_offload_t **handle, void *device_slab,
               hipStreamCreateWithFlags(&h->s_out, hipStreamNonBlocking) == hipSuccess &&
               create_events(h->ev_grad, num_slots) && create_events(h->ev_h2d, num_slots) &&
               create_events(h->ev_step, num_slots) && create_events(h->ev_d2h, num_slots);
+    // Every slot's workspace starts with its ticket counters at zero.
+    for (int i = 0; ok && i < num_slots; ++i)
+        ok = lohan_workspace_init(h->slab + h->slot_bytes * (size_t)i + 3 * h->array_bytes,
+                                  lohan::kWorkspaceBytes, h->s_compute) == LOHAN_OK;
     if (!ok) {
         release(h);
         return LOHAN_ERR_HIP;

@@ -38,7 +38,11 @@ class DeviceBlock:
         self.n = self.p.numel()
         self.flag = torch.full((1,), 7, dtype=torch.int32, device=device)     # stale on purpose
         self.sqnorm = torch.full((1,), -1.0, dtype=torch.float64, device=device)
-        self.ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=device)
+        # Garbage everywhere, then the documented one-time preparation.
+        self.ws = torch.full((lohan.lohan_workspace_bytes(),), 0xA5, dtype=torch.uint8,
+                             device=device)
+        lohan.lohan_workspace_init(self.ws)
+        torch.cuda.current_stream().synchronize()      # usable from side streams from here on
 
     def step(self, hy: dict, flags: int = 0, stream=None):
         lohan.lohan_adam_block_step(self.p, self.m, self.v, self.g, self.p16, self.n,

@@ -14,8 +14,10 @@ import paper_2403_06504_amd as lohan
 from paper_2403_06504_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADERS = [os.path.join(ROOT, "include", "lohan_adam.h"),
-           os.path.join(ROOT, "include", "lohan_swap_planner.h")]
+PRODUCT_HEADERS = [os.path.join(ROOT, "include", "lohan_adam.h"),
+                   os.path.join(ROOT, "include", "lohan_swap_planner.h")]
+TUNING_HEADER = os.path.join(ROOT, "include", "lohan_adam_tuning.h")      # bench-only
+HEADERS = PRODUCT_HEADERS + [TUNING_HEADER]
 
 
 @pytest.fixture(scope="module")
@@ -26,8 +28,8 @@ def lib():
     return lohan.load_library()
 
 
-def declared_functions():
-    text = "".join(open(h).read() for h in HEADERS)
+def declared_functions(headers=None):
+    text = "".join(open(h).read() for h in (HEADERS if headers is None else headers))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(lohan_[a-z_0-9]+)\s*\(", text)))
 
@@ -379,23 +381,75 @@ def test_clip_loss_scale_matches_oracle(lib, oracle):
 
 
 def test_launch_config_knob(lib):
-    before = lohan.lohan_get_launch_config()
+    before = lohan.lohan_tuning_get_launch_config()
     try:
-        lohan.lohan_set_launch_config(2 | (1 << 2) | (1 << 4), 16, 12, 4)
-        assert lohan.lohan_get_launch_config() == (2 | (1 << 2) | (1 << 4), 16, 12, 4)
-        lohan.lohan_set_launch_config()                       # all defaults
-        v, a, w, r = lohan.lohan_get_launch_config()
-        assert v == -1 and a >= 0 and w >= 0 and r > 0        # -1: variant chosen per call
-        lohan.lohan_set_launch_config(0, 0, 0, 0)
-        assert lohan.lohan_get_launch_config()[:3] == (0, 0, 0)
+        lohan.lohan_tuning_set_launch_config(2 | (1 << 2) | (1 << 4), 16, 12, 4, 1)
+        assert lohan.lohan_tuning_get_launch_config() == (2 | (1 << 2) | (1 << 4), 16, 12, 4, 1)
+        lohan.lohan_tuning_set_launch_config()                       # all defaults
+        v, a, w, r, pol = lohan.lohan_tuning_get_launch_config()
+        assert v == -1 and a >= 0 and w >= 0 and r > 0 and pol == -1   # -1: chosen per call
+        lohan.lohan_tuning_set_launch_config(0, 0, 0, 0, 0)
+        assert lohan.lohan_tuning_get_launch_config()[:3] == (0, 0, 0)
+        assert lohan.lohan_tuning_get_launch_config()[4] == 0
         for bad in (3, 2 << 2, 3 << 4, 1 << 6, 1000):
             with pytest.raises(lohan.LohanError):
-                lohan.lohan_set_launch_config(bad, 0, 0, 0)
-        for bad in ((0, 100000, 0, 0), (0, 0, 33, 0), (0, 0, 0, 17)):
+                lohan.lohan_tuning_set_launch_config(bad, 0, 0, 0)
+        for bad in ((0, 100000, 0, 0), (0, 0, 33, 0), (0, 0, 0, 17), (0, 0, 0, 0, 2)):
             with pytest.raises(lohan.LohanError):
-                lohan.lohan_set_launch_config(*bad)
+                lohan.lohan_tuning_set_launch_config(*bad)
     finally:
-        lohan.lohan_set_launch_config(*before)
+        lohan.lohan_tuning_set_launch_config(*before)
+
+
+def test_launch_override_is_per_thread_and_not_in_the_product_header(lib):
+    """The product headers expose no process-wide mutable setting: the launch-shape override
+    lives in the bench-only header and only affects the thread that set it."""
+    import threading
+    product = declared_functions(PRODUCT_HEADERS)
+    assert not [n for n in product if "launch_config" in n or n.startswith("lohan_tuning_")]
+    assert not [n for n in product if re.search(r"(^|_)set_", n)]
+    tuning = declared_functions([TUNING_HEADER])
+    assert "lohan_tuning_set_launch_config" in tuning
+    assert all(n.startswith("lohan_tuning_") for n in tuning)
+    before = lohan.lohan_tuning_get_launch_config()
+    seen = {}
+
+    def other_thread():
+        seen["initial"] = lohan.lohan_tuning_get_launch_config()
+        lohan.lohan_tuning_set_launch_config(1, 8, 16, 2, 0)
+        seen["after_own_set"] = lohan.lohan_tuning_get_launch_config()
+
+    try:
+        lohan.lohan_tuning_set_launch_config(2, 4, 8, 3, 1)
+        t = threading.Thread(target=other_thread)
+        t.start()
+        t.join()
+        assert seen["initial"][0] == -1 and seen["initial"][4] == -1      # built-in defaults
+        assert seen["after_own_set"] == (1, 8, 16, 2, 0)
+        assert lohan.lohan_tuning_get_launch_config() == (2, 4, 8, 3, 1)   # untouched by it
+    finally:
+        lohan.lohan_tuning_set_launch_config(*before)
+
+
+def test_workspace_init_validation(lib):
+    ws_bytes = lib.lohan_workspace_bytes()
+    assert lib.lohan_workspace_init(None, ws_bytes, None) == 1
+    assert lib.lohan_workspace_init(A + 8, ws_bytes, None) == 2
+    assert lib.lohan_workspace_init(A, ws_bytes - 1, None) == 4
+
+
+def test_probe_validation_returns_before_any_launch(lib):
+    def probe(pattern, a=A, b=A * 2, c=A * 3, g=A * 4, h=A * 5, n=1024, waves=0):
+        return lib.lohan_tuning_probe(pattern, a, b, c, g, h, n, waves, None)
+    assert probe(-1) == 3 and probe(5) == 3 and probe(0, waves=33) == 3 and probe(0, waves=-1) == 3
+    assert probe(lohan.LOHAN_PROBE_READ, a=None) == 1
+    assert probe(lohan.LOHAN_PROBE_WRITE, b=None) == 1
+    assert probe(lohan.LOHAN_PROBE_COPY, b=None) == 1
+    for name in ("a", "b", "c", "g", "h"):
+        assert probe(lohan.LOHAN_PROBE_FIVE_STREAM, **{name: None}) == 1
+        assert probe(lohan.LOHAN_PROBE_FIVE_STREAM, **{name: A + 8}) == 2
+    assert probe(lohan.LOHAN_PROBE_FIVE_STREAM, n=(1 << 31) * 256) == 3
+    assert probe(lohan.LOHAN_PROBE_FIVE_STREAM, n=255) == 0          # no whole tile: nothing to do
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

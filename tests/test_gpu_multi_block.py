@@ -43,7 +43,7 @@ class BlockSet:
         nb = len(self.sizes)
         self.flags = torch.full((max(nb, 1),), 7, dtype=torch.int32, device=DEV)
         self.sqnorms = torch.full((max(nb, 1),), -1.0, dtype=torch.float64, device=DEV)
-        self.ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=DEV)
+        self.ws = lohan.new_workspace(DEV)
         self.array = lohan.make_block_array(
             [(b.p, b.m, b.v, b.g, b.p16, b.n) if b.n else (None, None, None, None, None, 0)
              for b in self.blocks])
@@ -184,14 +184,14 @@ def test_every_kernel_variant_multi_block(oracle):
         for variant in variants:
             for wgs, waves in ((0, 0), (1, 8), (0, 2)):
                 say(f"[multi variant] variant={variant} wgs_per_cu={wgs} waves_per_cu={waves}")
-                lohan.lohan_set_launch_config(variant, wgs, waves, 0)
+                lohan.lohan_tuning_set_launch_config(variant, wgs, waves, 0)
                 bs = BlockSet(sizes, seed0=3)
                 assert bs.step(want_norms=False) == [0] * len(sizes)
                 for i, blk in enumerate(bs.blocks):
                     assert assert_state_parity(blk.host(), hosts[i],
                                                what=f"variant {variant} block {i}") == ZERO
     finally:
-        lohan.lohan_set_launch_config()
+        lohan.lohan_tuning_set_launch_config()
 
 
 def test_config1_blocks_as_a_twelve_layer_model(oracle):
@@ -206,7 +206,7 @@ def test_config1_blocks_as_a_twelve_layer_model(oracle):
 
 
 def test_no_blocks_is_a_no_op():
-    ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    ws = lohan.new_workspace(DEV)
     flags = torch.full((1,), 3, dtype=torch.int32, device=DEV)
     lohan.lohan_adam_multi_block_step([], 1e-4, 0.9, 0.999, 1e-8, 0.01, 1, 1024.0, 0.0, flags,
                                       None, 0, ws)

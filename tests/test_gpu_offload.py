@@ -160,7 +160,7 @@ def test_step_runs_directly_on_pinned_host_state(oracle):
     for i, n in enumerate((1_000_003, 65_536, 17)):
         for overflow in (False, True):
             b = HostBlock(n, seed=40 + i, overflow=overflow)
-            ws = torch.empty(lohan.lohan_workspace_bytes(), dtype=torch.uint8, device=DEV)
+            ws = lohan.new_workspace(DEV)
             hy = b.hy
             before = {k: b.oracle_state[k].copy() for k in ("p", "m", "v", "p16")}
             for k in range(2):

@@ -127,7 +127,7 @@ def test_every_kernel_variant_out_of_place(oracle):
         for variant in variants:
             for wgs, waves in ((0, 0), (1, 8), (0, 2)):
                 say(f"[oop variant] variant={variant} wgs_per_cu={wgs} waves_per_cu={waves}")
-                lohan.lohan_set_launch_config(variant, wgs, waves, 0)
+                lohan.lohan_tuning_set_launch_config(variant, wgs, waves, 0)
                 blk = TwoSets({k: t.clone() for k, t in ref.items()})
                 assert blk.step(hy) == 0
                 worst = assert_state_parity(blk.host(), host, what=f"oop variant={variant}")
@@ -137,7 +137,7 @@ def test_every_kernel_variant_out_of_place(oracle):
                 blk2.g.view(torch.int16)[n - 1] = 0x7C00
                 assert blk2.step(hy) == 1
     finally:
-        lohan.lohan_set_launch_config()
+        lohan.lohan_tuning_set_launch_config()
 
 
 def test_empty_block_out_of_place():

@@ -26,7 +26,7 @@ def say(msg):
 def _library_is_native():
     assert torch.cuda.is_available(), "these tests need a GPU"
     lohan.load_library()            # raises if the HIP library was not built
-    lohan.lohan_set_launch_config()         # built-in defaults, the shape bench.py times
+    lohan.lohan_tuning_set_launch_config()         # built-in defaults, the shape bench.py times
     yield
 
 
@@ -74,12 +74,12 @@ def test_every_kernel_variant_matches(oracle):
         for variant in all_variants():
             for wgs, waves in ((0, 0), (1, 8), (8, 4), (0, 2)):
                 say(f"[variant] variant={variant} wgs_per_cu={wgs} waves_per_cu={waves}")
-                lohan.lohan_set_launch_config(variant, wgs, waves, 0)
+                lohan.lohan_tuning_set_launch_config(variant, wgs, waves, 0)
                 blk = DeviceBlock({k: t.clone() for k, t in ref_blk.items()})
                 assert gpu_steps(blk, hy, 2) == [0, 0]
                 assert_state_parity(blk.host(), host, what=f"variant={variant}")
     finally:
-        lohan.lohan_set_launch_config()
+        lohan.lohan_tuning_set_launch_config()
 
 
 def test_bf16_copy_rounding_all_upper_halves(oracle):
