@@ -9,8 +9,15 @@ Adam-updated elements per second; the roofline object prices the dominant kernel
 (k_adam_block_step, 28 algorithmic bytes per element) against the 8 TB/s HBM peak using HIP events
 recorded on the launch stream inside the timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt13b|gpt175b|gpt_h768|
-                     stream13b|offload13b|shapes|models|gpt13b_oop|gpt175b_oop|ring13b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload default|gpt13b|gpt175b|
+                     gpt_h768|stream13b|offload13b|shapes|models|gpt13b_oop|gpt175b_oop|ring13b|
+                     ceiling]
+
+With no flags the line is the 175B-shaped block (the largest single-block configuration, 100
+timed steps) and carries the same object for the 13B-shaped block under "gpt13b"; each has the
+spread (min / median / max) of the per-launch event durations, the same kernel's figure on the
+allocator's placement, and the ceiling the five-stream access pattern reaches on the same arrays
+with trivial arithmetic (lohan_tuning_probe).  `--workload ceiling` runs all bandwidth probes.
 
 The *_oop workloads time lohan_adam_block_step_out_of_place instead: the overflow test fused into
 a single 28 B/element pass between two sets of state (not the default: it doubles the state).
@@ -31,31 +38,29 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 ADAM_BYTES_PER_ELEM = 28        # read g16 2 + p 4 + m 4 + v 4, write p 4 + m 4 + v 4 + bf16 2
 REDUCE_BYTES_PER_ELEM = 2       # one read of g16
-
-# HBM bytes per k_adam_block_step launch measured with two rocprofv3 --pmc runs of this script
-# (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy:
-# factor 2.000 and 1.000 on gfx950).  Summary: profiles/k_adam_block_step_gpt13b_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"gpt13b": 8601691 * 1024,      # profiles/..._gpt13b_hbm_traffic.md
-                          "gpt175b": 49545515 * 1024,    # profiles/..._gpt175b_trace_and_traffic.md
-                          "gpt13b_oop": 8601956 * 1024}  # profiles/k_adam_block_step_oop_gpt13b_...
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2403_06504_amd", "csrc", "lohan_kernels.hip")
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="gpt13b",
-                    choices=["gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b", "shapes",
-                             "gpt13b_oop", "gpt175b_oop", "models", "ring13b"])
+    ap.add_argument("--workload", default="default",
+                    choices=["default", "gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b",
+                             "shapes", "gpt13b_oop", "gpt175b_oop", "models", "ring13b",
+                             "ceiling"],
+                    help="default = the 175B-shaped block (headline) with the 13B-shaped block "
+                         "nested under 'gpt13b'")
     ap.add_argument("--variant", type=int, default=None, help="kernel launch-shape override")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--waves-per-cu", type=int, default=-1,
                     help="occupancy throttle override (0 = none, -1 = built-in default)")
+    ap.add_argument("--reduce-policy", type=int, default=-1,
+                    help="loads of the gradient reduction: 0 default, 1 nontemporal, -1 automatic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--compare-allocator", action="store_true",
-                    help="also time the update kernel on the five separate torch allocations "
-                         "before the block is moved into the library's placement")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the five-stream bandwidth probe after the timed region")
     ap.add_argument("--placement", choices=["library", "allocator"], default="library",
                     help="gpt13b/gpt175b/gpt_h768/shapes/models: where the blocks' arrays sit -- at "
                          "the offsets lohan_model_placement gives inside one slab (default), or "
@@ -69,21 +74,46 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(block, wl, sample_elems=1 << 27):
-    """Time the CPU oracle, as it stands, on the first `sample_elems` elements of the same block
-    (copied to the host before the timed GPU region)."""
-    import numpy as np
+def measured_traffic(workload_name):
+    """HBM bytes per k_adam_block_step launch as the rocprofv3 --pmc summary under profiles/
+    recorded them (machine-readable lines 'traffic_bytes_per_launch: N' and
+    'kernel_source_sha256: H'), with a staleness marker: the figure belongs to the kernel source
+    whose hash the summary names.  (None, note) when there is no summary for this workload."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", f"k_adam_block_step_{workload_name}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None, None
+    text = open(path).read()
+    m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", text, flags=re.M)
+    if not m:
+        return None, None
+    h = re.search(r"^kernel_source_sha256:\s*([0-9a-f]{64})", text, flags=re.M)
+    now = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
+    state = "current" if h and h.group(1) == now else "stale: kernel source changed since"
+    return int(m.group(1)), f"profiles/{os.path.basename(path)} ({state})"
+
+
+def cpu_model_name():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(block, wl, synth, sample_elems=1 << 27):
+    """Time the CPU oracle, as it stands, on the first `sample_elems` elements of the bench block
+    (copied to the host before the timed GPU region) and on the whole h=768 block, on one thread
+    and on every core the process may use."""
     from oracle import reference as oracle
-    from paper_2403_06504_amd import synthetic_inputs as synth
 
-    k = min(sample_elems, wl.n)
-    host = {name: synth.to_numpy_bits(block[name][:k]) for name in ("p", "m", "v", "g", "p16")}
-    hy = wl.hyper()
-    threads = min(oracle.max_threads(), 16 if os.environ.get("OMP_NUM_THREADS") is None
-                  else int(os.environ["OMP_NUM_THREADS"]))
-    threads = max(1, threads)
+    env = os.environ.get("OMP_NUM_THREADS")
+    threads = max(1, min(oracle.max_threads(), int(env)) if env else oracle.max_threads())
 
-    def time_step(nthreads, reps):
+    def time_step(host, hy, nthreads, reps):
         best = float("inf")
         for r in range(reps):
             t0 = time.perf_counter()
@@ -93,30 +123,43 @@ def cpu_baseline(block, wl, sample_elems=1 << 27):
             assert f == 0
         return best
 
-    t_multi = time_step(threads, 5)
-    t_single = time_step(1, 3)
+    k = min(sample_elems, wl.n)
+    host = {name: synth.to_numpy_bits(block[name][:k]) for name in ("p", "m", "v", "g", "p16")}
+    t_multi = time_step(host, wl.hyper(), threads, 5)
+    t_single = time_step(host, wl.hyper(), 1, 3)
     t0 = time.perf_counter()
     oracle.grad_sqnorm(host["g"], wl.loss_scale)
     t_norm = time.perf_counter() - t0
+
+    small = synth.WORKLOADS["gpt_h768"]
+    sblock = synth.make_block(small, seed=0, device="cpu")
+    shost = {name: synth.to_numpy_bits(sblock[name]) for name in ("p", "m", "v", "g", "p16")}
+    s_multi = time_step(shost, small.hyper(), threads, 5)
+    s_single = time_step(shost, small.hyper(), 1, 3)
     return {
         "value": k / t_multi, "unit": "elements/s", "cores": threads, "kind": "oracle",
         "sample": f"first {k} elements of the {wl.name} block; oracle Adam block step (overflow "
                   f"check + update + bf16 copy), best of 5 on {threads} OpenMP threads",
         "single_thread_value": k / t_single,
         "single_thread_with_sqnorm_value": k / (t_single + t_norm),
-        "host_cpus": os.cpu_count(),
+        "gpt_h768_whole_block": {"elements": small.n, "value": small.n / s_multi,
+                                 "single_thread_value": small.n / s_single},
+        "effective_gbps_at_28B": 28 * k / t_multi / 1e9,
+        "cpu_model": cpu_model_name(), "host_cpus": os.cpu_count(),
     }
 
 
-def placed_views(n, torch, lohan, dev):
+def placed_views(n, torch, lohan, dev, slab=None):
     """One slab with room for a full group of n-element blocks at the offsets
     lohan_model_placement gives (the layout a framework holding the whole model would use), and
     views of block 0's five arrays in it.  Allocate it before anything else, as a framework
-    would: a slab carved out of fresh memory keeps the lanes' relative position physically.
+    would: a slab carved out of fresh memory keeps the lanes' relative position physically
+    (`slab`: reuse this earlier allocation if it is large enough).
     Returns (views, slab, description)."""
     gib = 1 << 30
     offsets, slab_bytes, align, group = lohan.lohan_model_placement(n)     # one full group
-    slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=dev)
+    if slab is None or slab.numel() < slab_bytes + align:
+        slab = torch.empty(slab_bytes + align, dtype=torch.uint8, device=dev)
     start = (-slab.data_ptr()) % align
     spec = {"p": ("param_fp32", torch.float32), "m": ("exp_avg", torch.float32),
             "v": ("exp_avg_sq", torch.float32), "g": ("grad_fp16", torch.float16),
@@ -131,8 +174,15 @@ def placed_views(n, torch, lohan, dev):
     return views, slab, what
 
 
+def spread(values_ms):
+    """min / median / max / mean of a list of per-launch durations."""
+    v = sorted(values_ms)
+    return {"min_ms": v[0], "median_ms": v[len(v) // 2], "max_ms": v[-1],
+            "avg_ms": sum(v) / len(v), "launches": len(v)}
+
+
 def adam_kernel_only_ms(block, wl, torch, lohan, reps):
-    """Average duration of the update kernel alone on `block` (prechecked, flag 0)."""
+    """Per-launch durations of the update kernel alone on `block` (prechecked, flag 0)."""
     flag = torch.zeros(1, dtype=torch.int32, device=block["p"].device)
     hy = wl.hyper()
 
@@ -144,27 +194,53 @@ def adam_kernel_only_ms(block, wl, torch, lohan, reps):
 
     for w in range(3):
         call(hy["step"] + w)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    evs[0].record()
     for k in range(reps):
         call(hy["step"] + 3 + k)
+        evs[k + 1].record()
+    torch.cuda.synchronize()
+    return [evs[k].elapsed_time(evs[k + 1]) for k in range(reps)]
+
+
+def probe_ms(pattern, block, n, waves, torch, lohan, reps=10):
+    """Average duration of one bandwidth-probe launch on the block's own arrays."""
+    def call():
+        lohan.lohan_tuning_probe(pattern, block["p"], block["m"], block["v"], block["g"],
+                                 block["p16"], n, waves)
+    call()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / reps
 
 
-def bench_block(args, torch, lohan, synth):
-    wl = synth.WORKLOADS[args.workload]
+def five_stream_ceiling(block, n, torch, lohan):
+    """What the machine sustains for the update kernel's own access pattern with trivial
+    arithmetic, on the same arrays (best of a few occupancy limits).  Overwrites the block."""
+    best = None
+    for waves in (8, 11, 16):
+        ms = probe_ms(lohan.LOHAN_PROBE_FIVE_STREAM, block, n, waves, torch, lohan)
+        gbps = ADAM_BYTES_PER_ELEM * (n // 256 * 256) / ms / 1e6
+        if best is None or gbps > best[0]:
+            best = (gbps, waves)
+    return best
+
+
+def measure_block(wl, args, torch, lohan, synth, with_cpu_baseline, slab=None):
+    """One block through the whole hot path, `args.steps` timed steps; returns the JSON object."""
     dev = "cuda:0"
     n = wl.n
     placement = "five separate allocations of torch's caching allocator"
-    allocator_ms = None
+    allocator = None
     if args.placement == "library":
-        views, slab, placement = placed_views(n, torch, lohan, dev)
+        views, slab, placement = placed_views(n, torch, lohan, dev, slab)
     block = synth.make_block(wl, seed=0, device=dev)
     if args.placement == "library":
-        if args.compare_allocator:
-            allocator_ms = adam_kernel_only_ms(block, wl, torch, lohan, min(args.steps, 20))
+        allocator = spread(adam_kernel_only_ms(block, wl, torch, lohan, min(args.steps, 30)))
         for k in views:
             views[k].copy_(block[k])
         block = views
@@ -174,7 +250,7 @@ def bench_block(args, torch, lohan, synth):
     ws = lohan.new_workspace(dev)
     hy = wl.hyper()
 
-    base = None if args.no_cpu_baseline else cpu_baseline(block, wl)
+    base = cpu_baseline(block, wl, synth) if with_cpu_baseline else None
 
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)        # 1 GiB
@@ -208,43 +284,131 @@ def bench_block(args, torch, lohan, synth):
     elapsed = time.perf_counter() - t0
 
     assert int(flag.cpu().item()) == 0, "synthetic gradients must not overflow"
-    adam_all = sorted(e[0].elapsed_time(e[1]) for e in events)
-    adam_ms = sum(adam_all) / args.steps
-    reduce_ms = sum(e[2].elapsed_time(e[0]) for e in events) / args.steps
-    ms_per_step = elapsed * 1e3 / args.steps
-    achieved = ADAM_BYTES_PER_ELEM * n / (adam_ms * 1e-3) / 1e9
+    adam = spread([e[0].elapsed_time(e[1]) for e in events])
+    reduce_ = spread([e[2].elapsed_time(e[0]) for e in events])
+    step_s = elapsed / args.steps
+
+    def gbps(nbytes, ms):
+        return nbytes / (ms * 1e-3) / 1e9
+
+    achieved = gbps(ADAM_BYTES_PER_ELEM * n, adam["median_ms"])
+    traffic, traffic_source = measured_traffic(wl.name)
+    roofline = {"kernel": "k_adam_block_step", "bound": "hbm", "achieved": achieved,
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                "frac_basis": "median of the per-launch HIP-event durations in the timed region",
+                "traffic": traffic, "traffic_source": traffic_source,
+                "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n,
+                "launch_ms": adam,
+                "frac_at_min": gbps(ADAM_BYTES_PER_ELEM * n, adam["min_ms"]) / HBM_PEAK_GBPS,
+                "frac_at_max": gbps(ADAM_BYTES_PER_ELEM * n, adam["max_ms"]) / HBM_PEAK_GBPS,
+                "frac_at_avg": gbps(ADAM_BYTES_PER_ELEM * n, adam["avg_ms"]) / HBM_PEAK_GBPS}
     out = {
         "metric": "adam_updated_elements_per_sec",
-        "value": n / (elapsed / args.steps),
+        "value": n / step_s,
         "unit": "elements/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": step_s * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: one GPT block, n={n} elements "
                                f"(fp32 p/m/v, fp16 grads x loss scale {wl.loss_scale:g}, "
                                f"bf16 copy), AdamW step {wl.step}",
                    "elements": n, "bytes_per_element_step": 30, "placement": placement,
-                   "launch_config": list(lohan.lohan_tuning_get_launch_config())},
-        "step_hbm_gbps": (ADAM_BYTES_PER_ELEM + REDUCE_BYTES_PER_ELEM) * n /
-                         (elapsed / args.steps) / 1e9,
-        "roofline": {"kernel": "k_adam_block_step", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "avg_launch_ms": adam_ms,
-                     "median_launch_ms": adam_all[len(adam_all) // 2],
-                     "min_launch_ms": adam_all[0],
-                     "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
-        "reduce_kernel": {"kernel": "k_grad_reduce+k_grad_finalize", "avg_ms": reduce_ms,
-                          "achieved_gbps": REDUCE_BYTES_PER_ELEM * n / (reduce_ms * 1e-3) / 1e9},
+                   "launch_config": list(lohan.lohan_tuning_get_launch_config()),
+                   "device_info": list(lohan.lohan_tuning_device_info())},
+        "whole_step": {"note": "flag/norm reduction + update, launch gaps included (what `value` "
+                               "times)",
+                       "hbm_gbps_at_30B": 30 * n / step_s / 1e9,
+                       "frac_of_peak_at_30B": 30 * n / step_s / 1e9 / HBM_PEAK_GBPS,
+                       "frac_of_peak_at_28B": 28 * n / step_s / 1e9 / HBM_PEAK_GBPS},
+        "roofline": roofline,
+        "reduce_kernel": {"kernel": "k_grad_reduce (one launch: partials, ticket, combination)",
+                          "launch_ms": reduce_,
+                          "achieved_gbps": gbps(REDUCE_BYTES_PER_ELEM * n, reduce_["median_ms"])},
         "cpu_baseline": base,
     }
-    if allocator_ms is not None:
-        gbps = ADAM_BYTES_PER_ELEM * n / (allocator_ms * 1e-3) / 1e9
+    if allocator is not None:
+        a = gbps(ADAM_BYTES_PER_ELEM * n, allocator["median_ms"])
         out["allocator_placement"] = {
             "note": "the same kernel on five separate torch allocations, measured in this run "
                     "before the block was moved into the library's placement",
-            "avg_launch_ms": allocator_ms, "achieved": gbps, "frac": gbps / HBM_PEAK_GBPS}
+            "launch_ms": allocator, "achieved": a, "frac": a / HBM_PEAK_GBPS}
+    if not args.no_ceiling:
+        ceiling, waves = five_stream_ceiling(block, n, torch, lohan)
+        roofline["measured_ceiling_gbps"] = ceiling
+        roofline["frac_of_ceiling"] = achieved / ceiling
+        roofline["ceiling_note"] = (
+            "lohan_tuning_probe FIVE_STREAM on the same arrays after the timed region: the "
+            f"kernel's access pattern with trivial arithmetic, best at {waves} waves per CU")
     return out
+
+
+def bench_block(args, torch, lohan, synth):
+    return measure_block(synth.WORKLOADS[args.workload], args, torch, lohan, synth,
+                         not args.no_cpu_baseline)
+
+
+def bench_default(args, torch, lohan, synth):
+    """The two target shapes: the 175B-shaped block is the headline line (the largest
+    single-block configuration), the 13B-shaped block rides along under 'gpt13b'."""
+    slab = None
+    if args.placement == "library":
+        # One slab, allocated first and used by both blocks in turn, as a framework's arena is.
+        need = max(sum(lohan.lohan_model_placement(synth.WORKLOADS[w].n)[1:3])
+                   for w in ("gpt175b", "gpt13b"))
+        slab = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    out = measure_block(synth.WORKLOADS["gpt175b"], args, torch, lohan, synth,
+                        not args.no_cpu_baseline, slab)
+    torch.cuda.empty_cache()
+    out["gpt13b"] = measure_block(synth.WORKLOADS["gpt13b"], args, torch, lohan, synth, False,
+                                  slab)
+    return out
+
+
+def bench_ceiling(args, torch, lohan, synth):
+    """What the machine sustains on 13B-sized arrays (in the library's placement) for pure reads,
+    pure writes, a copy, the step's five-stream pattern with trivial arithmetic, and
+    hipMemcpyAsync device-to-device -- each at several occupancy limits."""
+    wl = synth.WORKLOADS["gpt13b"]
+    dev = "cuda:0"
+    n = wl.n
+    views, slab, placement = placed_views(n, torch, lohan, dev)
+    for k in ("p", "m", "v"):
+        views[k].normal_(0.0, 0.02)
+    views["g"].normal_(0.0, 65.0)
+    views["p16"].zero_()
+    patterns = [("read", lohan.LOHAN_PROBE_READ, 4), ("write", lohan.LOHAN_PROBE_WRITE, 4),
+                ("copy", lohan.LOHAN_PROBE_COPY, 8),
+                ("five_stream", lohan.LOHAN_PROBE_FIVE_STREAM, 28),
+                ("hipMemcpyDtoD", lohan.LOHAN_PROBE_MEMCPY, 8)]
+    rows = {}
+    reps = max(5, min(args.steps, 20))
+    for name, pattern, width in patterns:
+        sweep = (0,) if pattern == lohan.LOHAN_PROBE_MEMCPY else (0, 8, 11, 16, 24)
+        per = {}
+        for waves in sweep:
+            ms = probe_ms(pattern, views, n, waves, torch, lohan, reps)
+            per[str(waves)] = width * n / ms / 1e6
+        best = max(per, key=per.get)
+        rows[name] = {"bytes_per_element": width, "gbps_by_waves_per_cu": per,
+                      "best_gbps": per[best], "best_waves_per_cu": int(best),
+                      "frac_of_peak": per[best] / HBM_PEAK_GBPS}
+    five = rows["five_stream"]
+    ms = 28 * n / five["best_gbps"] / 1e6
+    return {
+        "metric": "adam_updated_elements_per_sec", "value": n / (ms * 1e-3),
+        "unit": "elements/s", "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"ceiling: bandwidth probes on 13B-sized arrays (n={n}), "
+                               "trivial arithmetic; `value` is the five-stream pattern's rate",
+                   "elements": n, "placement": placement,
+                   "device_info": list(lohan.lohan_tuning_device_info())},
+        "roofline": {"kernel": "k_probe_five_stream", "bound": "hbm",
+                     "achieved": five["best_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": five["frac_of_peak"], "traffic": None},
+        "probes": rows, "cpu_baseline": None,
+    }
 
 
 def bench_block_oop(args, torch, lohan, synth):
@@ -296,7 +460,8 @@ def bench_block_oop(args, torch, lohan, synth):
         "roofline": {"kernel": "k_adam_block_step_oop (events also span the one-lane flag clear)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "traffic": measured_traffic(args.workload)[0],
+                     "traffic_source": measured_traffic(args.workload)[1],
                      "avg_launch_ms": call_ms, "median_launch_ms": all_ms[len(all_ms) // 2],
                      "min_launch_ms": all_ms[0],
                      "algorithmic_bytes_per_launch": ADAM_BYTES_PER_ELEM * n},
@@ -423,24 +588,36 @@ def bench_stream(args, torch, lohan, synth):
         for s in side:
             main.wait_stream(s)
 
+    # A one-tile probe launch between the phases: a kernel of a distinctive name in a rocprofv3
+    # kernel trace, so that the trace can be cut into the phases below.
+    mark_buf = torch.zeros(256, dtype=torch.float32, device=dev)
+
+    def phase_marker():
+        torch.cuda.synchronize()
+        lohan.lohan_tuning_probe(lohan.LOHAN_PROBE_READ, mark_buf, None, None, None, None, 256)
+        torch.cuda.synchronize()
+
     for w in range(args.warmup):
         one_pass(hy["step"] + w)
-    torch.cuda.synchronize()
+    phase_marker()                                           # phase 1: GEMMs alone
     t0 = time.perf_counter()
     for k in range(args.steps):
         gemm_only()
     torch.cuda.synchronize()
     gemm_s = (time.perf_counter() - t0) / args.steps
+    phase_marker()                                           # phase 2: block steps alone
     t0 = time.perf_counter()
     for k in range(args.steps):
         one_pass(hy["step"] + args.warmup + k, gemm=False)
     torch.cuda.synchronize()
     steps_only_s = (time.perf_counter() - t0) / args.steps
+    phase_marker()                                           # phase 3: the stream itself
     t0 = time.perf_counter()
     for k in range(args.steps):
         one_pass(hy["step"] + args.warmup + args.steps + k)
     torch.cuda.synchronize()
     elapsed = (time.perf_counter() - t0) / args.steps
+    phase_marker()                                           # phase 4: the ring form
     assert all(int(f.cpu().item()) == 0 for f in flags)
     total = n * nblocks
 
@@ -775,10 +952,16 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     lohan.load_library()
-    if args.variant is not None or args.wgs_per_cu or args.waves_per_cu >= 0:
+    if (args.variant is not None or args.wgs_per_cu or args.waves_per_cu >= 0 or
+            args.reduce_policy >= 0):
         lohan.lohan_tuning_set_launch_config(-1 if args.variant is None else args.variant,
-                                      args.wgs_per_cu, args.waves_per_cu, 0)
-    if args.workload == "stream13b":
+                                             args.wgs_per_cu, args.waves_per_cu, 0,
+                                             args.reduce_policy)
+    if args.workload == "default":
+        out = bench_default(args, torch, lohan, synth)
+    elif args.workload == "ceiling":
+        out = bench_ceiling(args, torch, lohan, synth)
+    elif args.workload == "stream13b":
         out = bench_stream(args, torch, lohan, synth)
     elif args.workload == "offload13b":
         out = bench_offload(args, torch, lohan, synth)

@@ -93,9 +93,12 @@ constexpr int kReduceThreads = 64;
 constexpr int kReduceUnroll = 8;
 constexpr int kReduceWaves = kReduceThreads / 64;
 
-// Device-scope accesses to the partials and the ticket counter: they are written by one
-// workgroup and read by another within the same launch, so they must not be served from a
-// cache that is private to a CU or to an XCD.
+// Accesses to the partials and the ticket counter: they are written by one workgroup and read
+// by another within the same launch, possibly on another XCD with its own L2.  All of them are
+// device-scope atomics, which are performed at the device's point of coherence, so no cache
+// that is private to a CU or an XCD is involved and no cache-wide write-back or invalidation is
+// needed (a release/acquire fence per workgroup costs exactly that on this chip, and a thousand
+// of them at once tripled the duration of the whole reduction).
 template <typename T>
 __device__ __forceinline__ T ld_device_scope(const T *ptr)
 {
@@ -105,6 +108,21 @@ template <typename T>
 __device__ __forceinline__ void st_device_scope(T *ptr, T val)
 {
     __hip_atomic_store(ptr, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Publish a value and learn that it has been performed: an exchange returns the old value only
+// after the new one is in place.
+template <typename T>
+__device__ __forceinline__ T publish_device_scope(T *ptr, T val)
+{
+    return __hip_atomic_exchange(ptr, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Zero, but computed from a and b as far as the compiler can tell: whatever consumes the result
+// is issued after the operations that produced a and b have returned.
+__device__ __forceinline__ uint32_t zero_after(uint32_t a, uint32_t b)
+{
+    uint32_t z = 0;
+    asm volatile("" : "+v"(z) : "v"(a), "v"(b));
+    return z;
 }
 
 // Sum / OR over the workgroup: wavefront butterfly over the 64 lanes (fixed pairing), then LDS
@@ -187,14 +205,20 @@ __device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g,
 
     workgroup_combine<WITH_NORM>(tid, acc, ovf);
 
-    // Publish this workgroup's partial, then take a ticket.  The release half of the ticket's
-    // ordering makes the partial visible device-wide before the ticket is.
+    // Publish this workgroup's partial, then take a ticket.  The ticket's increment consumes what
+    // the publishing exchanges returned, so it is issued only once the partial is in place: whoever
+    // draws a later ticket finds it.
     __shared__ uint32_t s_is_last;
     if (tid == 0) {
-        if constexpr (WITH_NORM) st_device_scope(partial_sum + slot_base + wg, acc);
-        st_device_scope(partial_flag + slot_base + wg, ovf);
+        uint32_t seen = 0;
+        if constexpr (WITH_NORM) {
+            const double old = publish_device_scope(partial_sum + slot_base + wg, acc);
+            seen = (uint32_t)__builtin_bit_cast(uint64_t, old);
+        }
+        const uint32_t old_flag = publish_device_scope(partial_flag + slot_base + wg, ovf);
         const uint32_t ticket =
-            __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(counter, 1u + zero_after(seen, old_flag), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
         s_is_last = ticket == nwg - 1 ? 1u : 0u;
     }
     __syncthreads();
@@ -202,12 +226,29 @@ __device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g,
 
     // Last arrival: every partial has been published.  Combine them in a fixed order (lane l takes
     // partials l, l + kThreads, ... in turn; then the same butterfly as above).
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // The loads of a round are all issued before the first is used: they miss every cache by
+    // design, so one round costs one trip to memory instead of kFinalBatch of them.
+    constexpr uint32_t kFinalBatch = 16;
     double total = 0.0;
     uint32_t any = 0;
-    for (uint32_t i = tid; i < nwg; i += kThreads) {
-        if constexpr (WITH_NORM) total += ld_device_scope(partial_sum + slot_base + i);
-        any |= ld_device_scope(partial_flag + slot_base + i);
+    for (uint32_t first = 0; first < nwg; first += kFinalBatch * kThreads) {
+        double part[kFinalBatch];
+        uint32_t bits[kFinalBatch];
+#pragma unroll
+        for (uint32_t j = 0; j < kFinalBatch; ++j) {
+            const uint32_t i = first + j * kThreads + tid;
+            part[j] = 0.0;
+            bits[j] = 0u;
+            if (i < nwg) {
+                if constexpr (WITH_NORM) part[j] = ld_device_scope(partial_sum + slot_base + i);
+                bits[j] = ld_device_scope(partial_flag + slot_base + i);
+            }
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < kFinalBatch; ++j) {
+            if constexpr (WITH_NORM) total += part[j];     // + 0.0 past the end: no change
+            any |= bits[j];
+        }
     }
     workgroup_combine<WITH_NORM>(tid, total, any);
     if (tid == 0) {
