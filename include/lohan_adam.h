@@ -49,7 +49,8 @@ typedef enum {
     LOHAN_ERR_ALIGN = 2,      /* a data pointer or the workspace is not 16-byte aligned */
     LOHAN_ERR_ARG = 3,        /* a scalar argument is out of its domain (see each call) */
     LOHAN_ERR_WORKSPACE = 4,  /* workspace_bytes < lohan_workspace_bytes() */
-    LOHAN_ERR_HIP = 5         /* the HIP runtime reported an error at launch */
+    LOHAN_ERR_HIP = 5,        /* the HIP runtime reported an error at launch */
+    LOHAN_ERR_TOO_LARGE = 6   /* n exceeds LOHAN_GRAD_SQNORM_STATIC_MAX_N (lohan_grad_sqnorm_static) */
 } lohan_status_t;
 
 enum {
@@ -104,6 +105,24 @@ lohan_status_t lohan_grad_overflow_check(const void *grad_fp16, uint64_t n,
 lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_scale,
                                  double *sqnorm, uint32_t *overflow_flag,
                                  void *workspace, size_t workspace_bytes, hipStream_t stream);
+
+/*
+ * lohan_grad_sqnorm for callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and kernels as lohan_grad_sqnorm, minus the workspace: the partial results
+ * and the ticket counter live in a static device array of the library (lohan_workspace_bytes()
+ * = about 49 KiB, present on every GPU the library runs on until the process ends).  The call
+ * allocates nothing, frees nothing and never synchronises.  Its first call on a device resolves
+ * that device's copy of the array and enqueues a small fill kernel ahead of the reduction.
+ *   n   at most LOHAN_GRAD_SQNORM_STATIC_MAX_N elements, else LOHAN_ERR_TOO_LARGE
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (two
+ * streams, two threads) race and give unspecified results -- order them, or use
+ * lohan_grad_sqnorm with separate workspaces.  Other errors as lohan_grad_sqnorm.
+ */
+#define LOHAN_GRAD_SQNORM_STATIC_MAX_N (1ull << 40)
+lohan_status_t lohan_grad_sqnorm_static(const void *grad_fp16, uint64_t n, float loss_scale,
+                                        double *sqnorm, uint32_t *overflow_flag,
+                                        hipStream_t stream);
 
 /*
  * One block step (Sec. IV-C "CPU Compute": update the model states of block i and emit its 16-bit

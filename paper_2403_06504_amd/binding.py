@@ -21,7 +21,7 @@ LOHAN_FLAG_P16_FP16 = 4
 
 EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
-    "lohan_grad_sqnorm", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
+    "lohan_grad_sqnorm", "lohan_grad_sqnorm_static", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
     "lohan_adam_block_step_out_of_place", "lohan_adam_multi_block_step", "lohan_model_placement",
     "lohan_ring_bytes", "lohan_ring_init", "lohan_ring_adam_block_step", "lohan_ring_read",
     "lohan_clip_loss_scale", "lohan_workspace_init",
@@ -105,6 +105,8 @@ def load_library():
     lib.lohan_grad_overflow_check.restype = ctypes.c_int
     lib.lohan_grad_sqnorm.argtypes = [vp, u64, f32, vp, vp, vp, sz, vp]
     lib.lohan_grad_sqnorm.restype = ctypes.c_int
+    lib.lohan_grad_sqnorm_static.argtypes = [vp, u64, f32, vp, vp, vp]
+    lib.lohan_grad_sqnorm_static.restype = ctypes.c_int
     lib.lohan_adam_block_step.argtypes = [vp, vp, vp, vp, vp, u64, f32, f32, f32, f32, f32,
                                           ctypes.c_int64, f32, vp, ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_block_step.restype = ctypes.c_int
@@ -269,6 +271,13 @@ def lohan_grad_sqnorm(grad_fp16, n, loss_scale, sqnorm, overflow_flag, workspace
         _addr(grad_fp16, n, _F16, "grad_fp16"), int(n), float(loss_scale),
         _addr(sqnorm, 1, _F64, "sqnorm"), _addr(overflow_flag, 1, _U32, "overflow_flag"),
         ws, ws_bytes, _stream(stream)))
+
+
+def lohan_grad_sqnorm_static(grad_fp16, n, loss_scale, sqnorm, overflow_flag, stream=None):
+    _check(load_library().lohan_grad_sqnorm_static(
+        _addr(grad_fp16, n, _F16, "grad_fp16"), int(n), float(loss_scale),
+        _addr(sqnorm, 1, _F64, "sqnorm"), _addr(overflow_flag, 1, _U32, "overflow_flag"),
+        _stream(stream)))
 
 
 def lohan_adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n,

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <mutex>
 #include <cmath>
 #include <cstdint>
 #include <limits>
@@ -122,6 +123,8 @@ const char *lohan_status_string(lohan_status_t status)
     case LOHAN_ERR_ARG: return "a scalar argument is out of its domain";
     case LOHAN_ERR_WORKSPACE: return "workspace is smaller than lohan_workspace_bytes()";
     case LOHAN_ERR_HIP: return "the HIP runtime reported an error at launch";
+    case LOHAN_ERR_TOO_LARGE:
+        return "n exceeds the maximum of the entry point that allocates nothing";
     default: return "unknown status";
     }
 }
@@ -566,6 +569,64 @@ float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm)
     double coef = (double)max_norm / (norm + 1e-6);
     if (coef > 1.0) coef = 1.0;
     return (float)((double)loss_scale / coef);
+}
+
+// ------------------------------------------------------------------------------------------------
+// lohan_grad_sqnorm for callers that cannot allocate: the workspace is a static device array.
+// ------------------------------------------------------------------------------------------------
+
+}  // extern "C"
+
+// One copy of this array exists on every GPU the library runs on, at that GPU's own address, and
+// stays there until the process ends.  Its name is only a host-side handle for
+// hipGetSymbolAddress: kernels and copies are given the resolved per-device address, never the
+// name.  The loader zero-fills it, which is the state the ticket counters need.
+static __device__ __align__(256) unsigned char scratch[lohan::kWorkspaceBytes];
+
+namespace {
+
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device; resolved once per device, with that device
+// current.  The first call on a device also enqueues the counter fill on `stream`, ahead of the
+// caller's reduction.  NULL on error.
+void *scratch_on_current_device(hipStream_t stream)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] != nullptr) return g_scratch_ptr[dev];
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr)
+        return nullptr;
+    if (lohan::launch_workspace_init(ptr, stream) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+    return ptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+lohan_status_t lohan_grad_sqnorm_static(const void *grad_fp16, uint64_t n, float loss_scale,
+                                        double *sqnorm, uint32_t *overflow_flag,
+                                        hipStream_t stream)
+{
+    if (sqnorm == nullptr || (grad_fp16 == nullptr && n != 0)) return LOHAN_ERR_NULL;
+    if (misaligned(grad_fp16, 16) || misaligned(sqnorm, 8) || misaligned(overflow_flag, 4))
+        return LOHAN_ERR_ALIGN;
+    if (!finite_pos(loss_scale)) return LOHAN_ERR_ARG;
+    if (n > LOHAN_GRAD_SQNORM_STATIC_MAX_N) return LOHAN_ERR_TOO_LARGE;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
+    void *workspace = scratch_on_current_device(stream);
+    if (workspace == nullptr) return LOHAN_ERR_HIP;
+    const double inv = 1.0 / (double)loss_scale;
+    hipError_t e = lohan::launch_grad_reduce(grad_fp16, n, true, inv * inv, sqnorm, overflow_flag,
+                                             workspace, reduce_workgroups(dev), reduce_streams(n),
+                                             stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
 lohan_status_t lohan_workspace_init(void *workspace, size_t workspace_bytes, hipStream_t stream)

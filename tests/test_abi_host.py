@@ -52,7 +52,7 @@ def test_workspace_bytes_and_status_strings(lib):
     ws = lohan.lohan_workspace_bytes()
     assert 0 < ws <= (1 << 20) and ws % 16 == 0
     seen = set()
-    for code in range(0, 6):
+    for code in range(0, 7):
         s = lohan.lohan_status_string(code)
         assert s and s not in seen
         seen.add(s)
@@ -111,6 +111,18 @@ def test_reduction_validation_returns_before_any_launch(lib):
     for bad in (0.0, -2.0, math.inf, math.nan):
         assert lib.lohan_grad_sqnorm(A, 8, f(bad), A * 4, A * 3, A * 2, ws_bytes, None) == 3
     assert lib.lohan_grad_sqnorm(A, 8, f(1.0), A * 4, None, A * 2, 8, None) == 4
+
+
+def test_static_sqnorm_validation_returns_before_any_launch(lib):
+    f = ctypes.c_float
+    assert lib.lohan_grad_sqnorm_static(A, 8, f(1.0), None, A * 3, None) == 1
+    assert lib.lohan_grad_sqnorm_static(None, 8, f(1.0), A * 4, A * 3, None) == 1
+    assert lib.lohan_grad_sqnorm_static(A + 2, 8, f(1.0), A * 4, A * 3, None) == 2
+    assert lib.lohan_grad_sqnorm_static(A, 8, f(1.0), A * 4 + 4, A * 3, None) == 2
+    for bad in (0.0, -2.0, math.inf, math.nan):
+        assert lib.lohan_grad_sqnorm_static(A, 8, f(bad), A * 4, A * 3, None) == 3
+    assert lib.lohan_grad_sqnorm_static(A, (1 << 40) + 1, f(1.0), A * 4, A * 3, None) == 6
+    assert "maximum" in lohan.lohan_status_string(6)
 
 
 def test_clipped_step_validation_returns_before_any_launch(lib):
