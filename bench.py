@@ -497,13 +497,13 @@ def bench_ring(args, torch, lohan, synth):
             g.copy_(src["g"])
             grads.append(g)
             del src
-    ring = torch.empty(lohan.lohan_ring_bytes(nblocks), dtype=torch.uint8, device=dev)
-    lohan.lohan_ring_init(ring, slots, n)
+    ring = torch.empty(lohan.lohan_ring_bytes(nblocks, 1), dtype=torch.uint8, device=dev)
+    lohan.lohan_ring_init(ring, [slot + (n,) for slot in slots], nblocks)
     hy = wl.hyper()
 
     def one_step(k):
         b = nblocks - 1 - (k % nblocks)
-        lohan.lohan_ring_adam_block_step(ring, nblocks, b, grads[b], n, hy["lr"], hy["beta1"],
+        lohan.lohan_ring_adam_block_step(ring, nblocks, 1, b, grads[b], n, hy["lr"], hy["beta1"],
                                          hy["beta2"], hy["eps"], hy["weight_decay"],
                                          hy["step"] + k // nblocks, hy["loss_scale"], 0)
 
@@ -519,9 +519,9 @@ def bench_ring(args, torch, lohan, synth):
         events[k][1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    slot_of, spare, skipped = lohan.lohan_ring_read(ring, nblocks)
+    slot_of, spares, skipped = lohan.lohan_ring_read(ring, nblocks, 1)
     assert skipped == [0] * nblocks, "synthetic gradients must not overflow"
-    assert sorted(slot_of + [spare]) == list(range(nblocks + 1))
+    assert sorted(slot_of + spares) == list(range(nblocks + 1))
     all_ms = sorted(e[0].elapsed_time(e[1]) for e in events)
     call_ms = sum(all_ms) / args.steps
     achieved = ADAM_BYTES_PER_ELEM * n / (call_ms * 1e-3) / 1e9
@@ -625,10 +625,10 @@ def bench_stream(args, torch, lohan, synth):
     # is the spare; every step is the single-pass out-of-place update, committed on the device.
     # A ring's steps must be ordered, so they all go to one side stream.
     spare = {k: torch.empty_like(blocks[0][k]) for k in ("p", "m", "v", "p16")}
-    slot_list = [(blk["p"], blk["m"], blk["v"], blk["p16"]) for blk in blocks]
-    slot_list.append((spare["p"], spare["m"], spare["v"], spare["p16"]))
-    ring = torch.empty(lohan.lohan_ring_bytes(nblocks), dtype=torch.uint8, device=dev)
-    lohan.lohan_ring_init(ring, slot_list, n)
+    slot_list = [(blk["p"], blk["m"], blk["v"], blk["p16"], n) for blk in blocks]
+    slot_list.append((spare["p"], spare["m"], spare["v"], spare["p16"], n))
+    ring = torch.empty(lohan.lohan_ring_bytes(nblocks, 1), dtype=torch.uint8, device=dev)
+    lohan.lohan_ring_init(ring, slot_list, nblocks)
 
     def ring_pass(t):
         s = side[0]
@@ -637,7 +637,7 @@ def bench_stream(args, torch, lohan, synth):
             ev = torch.cuda.Event()
             ev.record(main)
             s.wait_event(ev)
-            lohan.lohan_ring_adam_block_step(ring, nblocks, i, blocks[i]["g"], n, hy["lr"],
+            lohan.lohan_ring_adam_block_step(ring, nblocks, 1, i, blocks[i]["g"], n, hy["lr"],
                                              hy["beta1"], hy["beta2"], hy["eps"],
                                              hy["weight_decay"], t, hy["loss_scale"], 0, stream=s)
         main.wait_stream(s)
@@ -650,7 +650,7 @@ def bench_stream(args, torch, lohan, synth):
         ring_pass(t_ring0 + 1 + k)
     torch.cuda.synchronize()
     ring_elapsed = (time.perf_counter() - t0) / args.steps
-    assert lohan.lohan_ring_read(ring, nblocks)[2] == [0] * nblocks
+    assert lohan.lohan_ring_read(ring, nblocks, 1)[2] == [0] * nblocks
     return {
         "metric": "adam_updated_elements_per_sec", "value": total / elapsed,
         "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

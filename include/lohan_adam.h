@@ -201,7 +201,7 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
  *                           (so param_bf16_out must not be the only live copy of the old P16)
  * The price is a second set of the 12 B/element fp32 state (and of the 16-bit copy).  Clipping by
  * the block's own norm cannot be fused this way (the scale depends on the whole block): use
- * lohan_grad_sqnorm + lohan_adam_block_step_clipped for that.
+ * lohan_grad_sqnorm + lohan_adam_block_step_out_of_place_clipped for that.
  *   *_in            device, in : n floats each; must not overlap any output
  *   *_out           device, out: n floats each; each must differ from its input array, else
  *                   LOHAN_ERR_ARG (other overlaps are undefined)
@@ -218,49 +218,92 @@ lohan_status_t lohan_adam_block_step_out_of_place(
     hipStream_t stream);
 
 /*
+ * The out-of-place step with per-block gradient-norm clipping resolved on the device: as
+ * lohan_adam_block_step_out_of_place, but the unscale factor is 1 / fp32(loss_scale / coef) with
+ * coef = min(1, max_norm / (sqrt(*sqnorm) + 1e-6)), computed by a one-lane kernel ahead of the
+ * update exactly as in lohan_adam_block_step_clipped.  *sqnorm must already hold this block's
+ * result of lohan_grad_sqnorm on `stream`; the clip scale needs the whole block's norm before the
+ * first element is updated, so a clipping run keeps that 2-byte pass whatever form the update
+ * takes.  The overflow test stays fused into the update (*overflow_flag is written here).
+ *   sqnorm      device, in: one double, 8-byte aligned
+ *   max_norm    finite and > 0, else LOHAN_ERR_ARG
+ *   workspace   required (holds the device-side scalar); may be the one lohan_grad_sqnorm used
+ */
+lohan_status_t lohan_adam_block_step_out_of_place_clipped(
+    const float *param_fp32_in, const float *exp_avg_in, const float *exp_avg_sq_in,
+    const void *grad_fp16, float *param_fp32_out, float *exp_avg_out, float *exp_avg_sq_out,
+    void *param_bf16_out, uint64_t n, float lr, float beta1, float beta2, float eps,
+    float weight_decay, int64_t step, float loss_scale, const double *sqnorm, float max_norm,
+    uint32_t *overflow_flag, uint32_t flags, void *workspace, size_t workspace_bytes,
+    hipStream_t stream);
+
+/*
  * Ring form of the out-of-place step: single-pass (28 bytes per element) updates for a whole
- * model at the price of ONE spare block of state instead of a second copy of everything.
- * A model of B equal blocks lives in B + 1 slots; a slot holds the P32, the two OS32 moments and
- * the P16 copy of one block (Table II).  The step of block b (the "CPU Compute" step of
- * Sec. IV-C, with lohan_adam_block_step's arithmetic) reads the slot that currently holds b,
- * writes the spare slot, and a one-lane kernel then makes the spare b's slot and b's old slot the
- * new spare -- unless b's gradients held inf/NaN, in which case nothing changes hands and the old
- * slot stays b's state, bit-identical.  Which slot holds which block is a table in DEVICE memory
- * (the ring), read by the kernels themselves, so no host decision and no host synchronisation
- * sits between the blocks of a backward pass.
- *   ring        device memory of lohan_ring_bytes(B) bytes, 16-byte aligned, owned by the caller,
- *               initialised once by lohan_ring_init and from then on changed only by the steps.
- *               All steps of one ring must be enqueued on one stream (or otherwise ordered).
- *   lohan_ring_init   copies the B + 1 slot descriptors (HOST array; block b starts in slot b,
- *               slot B is the spare) into the ring with a synchronous copy.  Slot arrays: n
- *               elements each, 16-byte aligned, not overlapping; LOHAN_ERR_NULL / _ALIGN per
- *               slot, LOHAN_ERR_WORKSPACE if ring_bytes is too small, LOHAN_ERR_ARG if B is 0.
+ * model at the price of ONE spare slot per distinct block length instead of a second copy of
+ * everything.  A "block" here is whatever unit the gradient handler of Sec. IV-C fires on: a
+ * whole transformer block, or one gradient tensor of it (the attention and MLP weight matrices
+ * and the small bias / LayerNorm vectors have different lengths; the same few lengths repeat in
+ * every layer).  The B blocks live in B slots, and S further slots are spares, one for each
+ * distinct length; a slot holds the P32, the two OS32 moments and the P16 copy of one block
+ * (Table II).  The step of block b (the "CPU Compute" step of Sec. IV-C, with
+ * lohan_adam_block_step's arithmetic) reads the slot that currently holds b, writes the spare of
+ * b's length, and a one-lane kernel then makes that spare b's slot and b's old slot the spare --
+ * unless b's gradients held inf/NaN, in which case nothing changes hands and the old slot stays
+ * b's state, bit-identical.  Which slot holds which block is a table in DEVICE memory (the ring),
+ * read by the kernels themselves, so no host decision and no host synchronisation sits between
+ * the blocks of a backward pass.
+ *   ring        device memory of lohan_ring_bytes(B, S) bytes, 16-byte aligned, owned by the
+ *               caller, initialised once by lohan_ring_init and from then on changed only by the
+ *               steps.  All steps of one ring must be enqueued on one stream (or otherwise
+ *               ordered).
+ *   lohan_ring_init   copies the B + S slot descriptors (HOST array; block b starts in slot b,
+ *               slots B .. B+S-1 are the spares) into the ring with a synchronous copy.  Every
+ *               block must find a spare of exactly its length and no two spares may have the
+ *               same length, else LOHAN_ERR_ARG; also LOHAN_ERR_ARG unless 1 <= S <= B.  Slot
+ *               arrays: n elements each, 16-byte aligned, not overlapping (a slot with n == 0
+ *               may have NULL arrays); LOHAN_ERR_NULL / _ALIGN per slot, LOHAN_ERR_WORKSPACE if
+ *               ring_bytes is too small.
  *   lohan_ring_adam_block_step   enqueues the step of `block` and its commit on `stream`;
  *               allocates nothing, never synchronises.  Arguments as lohan_adam_block_step
  *               (flags: LOHAN_FLAG_L2_MODE, LOHAN_FLAG_P16_FP16); block >= B -> LOHAN_ERR_ARG.
+ *               n must be the length the block was registered with: the kernel compares it with
+ *               the table and, if it differs, touches nothing and reports the step as skipped.
  *               n == 0 does nothing.
+ *   lohan_ring_adam_block_step_clipped   the same with per-block clipping resolved on the device
+ *               from *sqnorm (device, this block's result of lohan_grad_sqnorm on `stream`) and
+ *               max_norm, as lohan_adam_block_step_clipped; the scalar lives in the ring.
  *   lohan_ring_read   synchronises `stream`, then copies to the host (each output may be NULL):
- *               slot_of[b] = the slot that holds block b, *spare = the spare slot, and
- *               skipped[b] = 1 if the most recent step of block b found inf/NaN gradients and
- *               was skipped, else 0 -- the overflow flag of lohan_adam_block_step: the caller
- *               does not advance that block's step count.  The forward pass finds block b's P16
- *               in slot slot_of[b].
+ *               slot_of[b] = the slot that holds block b, spares[j] = the spare slot of the
+ *               length that slot B + j had at init, and skipped[b] = 1 if the most recent step
+ *               of block b found inf/NaN gradients (or a wrong n) and was skipped, else 0 -- the
+ *               overflow flag of lohan_adam_block_step: the caller does not advance that
+ *               block's step count.  The forward pass finds block b's P16 in slot slot_of[b].
  */
 typedef struct {
     float *param_fp32, *exp_avg, *exp_avg_sq;   /* device: n floats each */
     void *param_16;                             /* device: n 16-bit values */
+    uint64_t n;                                 /* elements this slot holds */
 } lohan_ring_slot_t;
 
-size_t lohan_ring_bytes(uint32_t num_blocks);
+size_t lohan_ring_bytes(uint32_t num_blocks, uint32_t num_spares);
 lohan_status_t lohan_ring_init(void *ring, size_t ring_bytes, const lohan_ring_slot_t *slots,
-                               uint32_t num_blocks);
-lohan_status_t lohan_ring_adam_block_step(void *ring, uint32_t num_blocks, uint32_t block,
-                                          const void *grad_fp16, uint64_t n, float lr,
-                                          float beta1, float beta2, float eps,
+                               uint32_t num_blocks, uint32_t num_spares);
+lohan_status_t lohan_ring_adam_block_step(void *ring, uint32_t num_blocks, uint32_t num_spares,
+                                          uint32_t block, const void *grad_fp16, uint64_t n,
+                                          float lr, float beta1, float beta2, float eps,
                                           float weight_decay, int64_t step, float loss_scale,
                                           uint32_t flags, hipStream_t stream);
-lohan_status_t lohan_ring_read(const void *ring, uint32_t num_blocks, uint32_t *slot_of,
-                               uint32_t *spare, uint32_t *skipped, hipStream_t stream);
+lohan_status_t lohan_ring_adam_block_step_clipped(void *ring, uint32_t num_blocks,
+                                                  uint32_t num_spares, uint32_t block,
+                                                  const void *grad_fp16, uint64_t n, float lr,
+                                                  float beta1, float beta2, float eps,
+                                                  float weight_decay, int64_t step,
+                                                  float loss_scale, const double *sqnorm,
+                                                  float max_norm, uint32_t flags,
+                                                  hipStream_t stream);
+lohan_status_t lohan_ring_read(const void *ring, uint32_t num_blocks, uint32_t num_spares,
+                               uint32_t *slot_of, uint32_t *spares, uint32_t *skipped,
+                               hipStream_t stream);
 
 /*
  * One block of a multi-block call: the tensors of Table II for that block, as the arguments of
@@ -280,8 +323,12 @@ typedef struct {
  * number of launches instead of two or three per block (small blocks -- the DiT shapes of
  * Table VI, the h=768 test block -- are otherwise bound by launch gaps and by the ramp of each
  * short kernel).  Every block keeps its own overflow flag, its own norm and its own skip
- * decision, exactly as if lohan_grad_sqnorm / lohan_adam_block_step[_clipped] had been called on
- * it alone; the results are bit-identical to those calls.
+ * decision, as if lohan_grad_sqnorm / lohan_adam_block_step[_clipped] had been called on it
+ * alone: flags and the state after an unclipped step are bit-identical to those calls.  The
+ * squared norm is reduced over a different number of workgroups than in a single-block call, so
+ * its float64 value may differ from that call's in the last bits (both are within 1e-5 relative
+ * of the exact sum); a clipped step is bit-identical to lohan_adam_block_step_clipped given the
+ * same squared norm.
  *   blocks          HOST array of num_blocks descriptors (read during the call only; they travel
  *                   to the device inside the kernel arguments, nothing is uploaded or allocated)
  *   num_blocks      any count; runs of up to 64 consecutive blocks of similar length share one
@@ -340,6 +387,26 @@ typedef struct {
 lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
                                      lohan_block_offsets_t *offsets, size_t *slab_bytes,
                                      size_t *slab_alignment, uint32_t *blocks_per_group);
+
+/*
+ * The same placement for units of UNEQUAL length -- the gradient tensors of Sec. IV-C's handler
+ * (per layer: the attention and MLP matrices of 3h^2, h^2, 4h^2, 4h^2 elements and the h-sized
+ * bias / LayerNorm vectors), or the slots of a ring with its spares.  lengths[i] is the element
+ * count of unit i; units keep their order.  The rule is lohan_model_placement's: the period P is
+ * chosen for the LONGEST fp32 array (4 GiB, else 12 GiB); maximal runs of consecutive units whose
+ * fp32 arrays fit one lane together form a group; within a group all p arrays sit back to back
+ * in lane 0, the m arrays at the same offsets in lane 1 (+P + 1 MiB), the v arrays in lane 2
+ * (+2P + 2 MiB); the 16-bit arrays fill the room left in lanes 0 and 1, first fit, and otherwise
+ * follow lane 2.  Arrays of 2 MiB and more start on 1 MiB boundaries, smaller ones on 4 KiB
+ * boundaries (so a model's many short vectors cost little).  If the longest fp32 array is below
+ * 256 MiB or fits neither period, the units are packed one after the other (p, m, v, g, p16).
+ * For equal lengths of 2^26 elements and more the offsets equal lohan_model_placement's.
+ *   lengths, offsets   host: count entries each (both may be NULL only if count == 0)
+ * LOHAN_ERR_NULL for NULL outputs, LOHAN_ERR_ARG if a length exceeds 2^40.
+ */
+lohan_status_t lohan_tensor_placement(const uint64_t *lengths, uint32_t count,
+                                      lohan_block_offsets_t *offsets, size_t *slab_bytes,
+                                      size_t *slab_alignment);
 
 /*
  * Host-only helper for per-block gradient-norm clipping: returns the loss scale to hand to
@@ -403,7 +470,11 @@ lohan_status_t lohan_offload_create(lohan_offload_t **handle, void *device_slab,
  * LOHAN_FLAG_P16_FP16.
  * The block's host arrays must not be touched until lohan_offload_drain (or a later
  * synchronisation of the caller's own with the copy-out) and *blk itself is read only during
- * the call.  Validation errors enqueue nothing.
+ * the call.  Validation errors enqueue nothing.  If the HIP runtime fails after part of the
+ * block's work has been enqueued, LOHAN_ERR_HIP is returned and the handle is POISONED: its slot
+ * bookkeeping no longer describes what is in flight, so every later lohan_offload_submit and
+ * lohan_offload_wait_last_step returns LOHAN_ERR_HIP without enqueueing anything; lohan_offload_drain
+ * and lohan_offload_destroy still work.  The failed block's host arrays are unspecified.
  */
 lohan_status_t lohan_offload_submit(lohan_offload_t *handle, const lohan_offload_block_t *blk,
                                     float lr, float beta1, float beta2, float eps,

@@ -71,6 +71,14 @@ enum {
 lohan_status_t lohan_tuning_probe(int pattern, float *a, float *b, float *c, const void *g16,
                                   void *h16, uint64_t n, int waves_per_cu, hipStream_t stream);
 
+/*
+ * Fault injection for tests of the offload pipeline's error path: the (after_calls + 1)-th HIP
+ * runtime call that later lohan_offload_submit calls on this handle would make is not issued and
+ * reports failure instead.  Nothing faults on the device: the submit returns LOHAN_ERR_HIP and
+ * the handle is poisoned exactly as after a real runtime failure.  LOHAN_ERR_NULL / _ARG.
+ */
+lohan_status_t lohan_tuning_offload_inject_failure(lohan_offload_t *handle, int after_calls);
+
 #ifdef __cplusplus
 }
 #endif

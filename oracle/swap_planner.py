@@ -11,10 +11,11 @@ Readings where the paper is silent:
     operations, THP_G operations/s.
   * layer_list is sorted by offloading benefit OB = FLOP_layer / A_layer (Eq. 6), highest first,
     ties keeping the original order; a layer with A = 0 has infinite benefit.
-  * Algorithm 1 as printed: A_G2M and FLOP_r are advanced before the iteration time is evaluated;
-    a layer whose T_iter does not improve on T_min is still appended while A_G2M < A_interBlock
-    (the floor that avoids running out of GPU memory) and T_min is then left alone; the first
-    non-improving layer at or above the floor ends the search and is not appended.
+  * Algorithm 1 is read as a rule over the prefixes of the benefit order: a prefix ENDS the search
+    when it holds at least A_interBlock bytes (the floor that avoids running out of GPU memory)
+    and its T_iter is no better than the best T_iter of any shorter non-empty prefix; the plan is
+    the prefix just before the first one that ends the search (all layers if none does).  A prefix
+    below the floor never ends the search, however bad its T_iter.
 """
 import math
 
@@ -56,24 +57,24 @@ def recompute_flops(layers, flop_f: float, a_g2m: float):
 
 
 def plan(layers, hw: dict):
-    """Algorithm 1.  layers: list of (flop, act_bytes).  Returns (swap_list as indices into
-    `layers` in swapping order, A_G2M of the swap list, FLOP_r, T_iter of the swap list)."""
+    """Algorithm 1 by its definition over prefixes.  layers: list of (flop, act_bytes).  Returns
+    (swap_list as indices into `layers` in swapping order, A_G2M of the swap list, FLOP_r,
+    T_iter of the swap list)."""
     order = sorted(range(len(layers)), key=lambda i: -offloading_benefit(*layers[i]))
-    swap_list = []
-    t_min = math.inf
-    a_g2m = 0.0
-    flop_r = hw["flop_f"]                                           # full recomputation
-    for i in order:
-        flop, act = layers[i]
-        a_g2m += act
-        flop_r -= flop
-        t_iter = iter_time(hw, a_g2m, flop_r)
-        if t_iter >= t_min:
-            if a_g2m >= hw["a_interblock"]:
-                break
-        else:
-            t_min = t_iter
-        swap_list.append(i)
-    a_sw = sum(layers[i][1] for i in swap_list)
-    f_r = hw["flop_f"] - sum(layers[i][0] for i in swap_list)
-    return swap_list, a_sw, f_r, iter_time(hw, a_sw, f_r)
+
+    def swapped_bytes(k):                    # A_G2M when the first k layers are swapped
+        return sum((layers[i][1] for i in order[:k]), 0.0)
+
+    def recompute_left(k):                   # FLOP_r of Eq. 7 at the k-th breakpoint
+        return hw["flop_f"] - sum((layers[i][0] for i in order[:k]), 0.0)
+
+    def t_iter(k):
+        return iter_time(hw, swapped_bytes(k), recompute_left(k))
+
+    def ends_search(k):
+        best_shorter = min((t_iter(j) for j in range(1, k)), default=math.inf)
+        return swapped_bytes(k) >= hw["a_interblock"] and t_iter(k) >= best_shorter
+
+    first_end = next((k for k in range(1, len(order) + 1) if ends_search(k)), None)
+    count = len(order) if first_end is None else first_end - 1
+    return order[:count], swapped_bytes(count), recompute_left(count), t_iter(count)

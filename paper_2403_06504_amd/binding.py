@@ -22,11 +22,13 @@ LOHAN_FLAG_P16_FP16 = 4
 EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
     "lohan_grad_sqnorm", "lohan_grad_sqnorm_static", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
-    "lohan_adam_block_step_out_of_place", "lohan_adam_multi_block_step", "lohan_model_placement",
-    "lohan_ring_bytes", "lohan_ring_init", "lohan_ring_adam_block_step", "lohan_ring_read",
+    "lohan_adam_block_step_out_of_place", "lohan_adam_block_step_out_of_place_clipped",
+    "lohan_adam_multi_block_step", "lohan_model_placement", "lohan_tensor_placement",
+    "lohan_ring_bytes", "lohan_ring_init", "lohan_ring_adam_block_step",
+    "lohan_ring_adam_block_step_clipped", "lohan_ring_read",
     "lohan_clip_loss_scale", "lohan_workspace_init",
     "lohan_tuning_set_launch_config", "lohan_tuning_get_launch_config",
-    "lohan_tuning_device_info", "lohan_tuning_probe",
+    "lohan_tuning_device_info", "lohan_tuning_probe", "lohan_tuning_offload_inject_failure",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
     "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
     "lohan_swap_iter_time", "lohan_swap_recompute_flops", "lohan_plan_activation_swapping",
@@ -65,7 +67,8 @@ class LohanBlock(ctypes.Structure):
 class LohanRingSlot(ctypes.Structure):
     """Mirror of lohan_ring_slot_t."""
     _fields_ = [("param_fp32", ctypes.c_void_p), ("exp_avg", ctypes.c_void_p),
-                ("exp_avg_sq", ctypes.c_void_p), ("param_16", ctypes.c_void_p)]
+                ("exp_avg_sq", ctypes.c_void_p), ("param_16", ctypes.c_void_p),
+                ("n", ctypes.c_uint64)]
 
 
 class LohanBlockOffsets(ctypes.Structure):
@@ -122,18 +125,29 @@ def load_library():
                                                 f32, f32, f32, f32, ctypes.c_int64, f32, f32, vp,
                                                 vp, ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_multi_block_step.restype = ctypes.c_int
-    lib.lohan_ring_bytes.argtypes = [ctypes.c_uint32]
+    lib.lohan_adam_block_step_out_of_place_clipped.argtypes = [
+        vp, vp, vp, vp, vp, vp, vp, vp, u64, f32, f32, f32, f32, f32, ctypes.c_int64, f32, vp, f32,
+        vp, ctypes.c_uint32, vp, sz, vp]
+    lib.lohan_adam_block_step_out_of_place_clipped.restype = ctypes.c_int
+    u32 = ctypes.c_uint32
+    lib.lohan_ring_bytes.argtypes = [u32, u32]
     lib.lohan_ring_bytes.restype = sz
-    lib.lohan_ring_init.argtypes = [vp, sz, ctypes.POINTER(LohanRingSlot), ctypes.c_uint32]
+    lib.lohan_ring_init.argtypes = [vp, sz, ctypes.POINTER(LohanRingSlot), u32, u32]
     lib.lohan_ring_init.restype = ctypes.c_int
-    lib.lohan_ring_adam_block_step.argtypes = [vp, ctypes.c_uint32, ctypes.c_uint32, vp, u64, f32,
-                                               f32, f32, f32, f32, ctypes.c_int64, f32,
-                                               ctypes.c_uint32, vp]
+    lib.lohan_ring_adam_block_step.argtypes = [vp, u32, u32, u32, vp, u64, f32, f32, f32, f32, f32,
+                                               ctypes.c_int64, f32, u32, vp]
     lib.lohan_ring_adam_block_step.restype = ctypes.c_int
-    lib.lohan_ring_read.argtypes = [vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32),
-                                    ctypes.POINTER(ctypes.c_uint32),
-                                    ctypes.POINTER(ctypes.c_uint32), vp]
+    lib.lohan_ring_adam_block_step_clipped.argtypes = [vp, u32, u32, u32, vp, u64, f32, f32, f32,
+                                                       f32, f32, ctypes.c_int64, f32, vp, f32,
+                                                       u32, vp]
+    lib.lohan_ring_adam_block_step_clipped.restype = ctypes.c_int
+    lib.lohan_ring_read.argtypes = [vp, u32, u32, ctypes.POINTER(u32), ctypes.POINTER(u32),
+                                    ctypes.POINTER(u32), vp]
     lib.lohan_ring_read.restype = ctypes.c_int
+    lib.lohan_tensor_placement.argtypes = [ctypes.POINTER(u64), u32,
+                                           ctypes.POINTER(LohanBlockOffsets), ctypes.POINTER(sz),
+                                           ctypes.POINTER(sz)]
+    lib.lohan_tensor_placement.restype = ctypes.c_int
     lib.lohan_model_placement.argtypes = [u64, ctypes.c_uint32, ctypes.POINTER(LohanBlockOffsets),
                                           ctypes.POINTER(sz), ctypes.POINTER(sz),
                                           ctypes.POINTER(ctypes.c_uint32)]
@@ -150,6 +164,8 @@ def load_library():
     lib.lohan_tuning_device_info.restype = ctypes.c_int
     lib.lohan_tuning_probe.argtypes = [ctypes.c_int, vp, vp, vp, vp, vp, u64, ctypes.c_int, vp]
     lib.lohan_tuning_probe.restype = ctypes.c_int
+    lib.lohan_tuning_offload_inject_failure.argtypes = [vp, ctypes.c_int]
+    lib.lohan_tuning_offload_inject_failure.restype = ctypes.c_int
     lib.lohan_offload_slab_bytes.argtypes = [u64, ctypes.c_int]
     lib.lohan_offload_slab_bytes.restype = sz
     lib.lohan_offload_create.argtypes = [ctypes.POINTER(vp), vp, sz, u64, ctypes.c_int,
@@ -354,41 +370,87 @@ def lohan_adam_multi_block_step(blocks, lr, beta1, beta2, eps, weight_decay, ste
         _addr(sqnorms, num_blocks, _F64, "sqnorms"), int(flags), ws, ws_bytes, _stream(stream)))
 
 
-def lohan_ring_bytes(num_blocks) -> int:
-    return int(load_library().lohan_ring_bytes(int(num_blocks)))
+def lohan_adam_block_step_out_of_place_clipped(param_fp32_in, exp_avg_in, exp_avg_sq_in,
+                                               grad_fp16, param_fp32_out, exp_avg_out,
+                                               exp_avg_sq_out, param_bf16_out, n, lr, beta1,
+                                               beta2, eps, weight_decay, step, loss_scale, sqnorm,
+                                               max_norm, overflow_flag, flags, workspace,
+                                               workspace_bytes=None, stream=None):
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_adam_block_step_out_of_place_clipped(
+        _addr(param_fp32_in, n, _F32, "param_fp32_in"), _addr(exp_avg_in, n, _F32, "exp_avg_in"),
+        _addr(exp_avg_sq_in, n, _F32, "exp_avg_sq_in"), _addr(grad_fp16, n, _F16, "grad_fp16"),
+        _addr(param_fp32_out, n, _F32, "param_fp32_out"),
+        _addr(exp_avg_out, n, _F32, "exp_avg_out"),
+        _addr(exp_avg_sq_out, n, _F32, "exp_avg_sq_out"),
+        _addr(param_bf16_out, n, _BF16, "param_bf16_out"), int(n),
+        float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
+        float(loss_scale), _addr(sqnorm, 1, _F64, "sqnorm"), float(max_norm),
+        _addr(overflow_flag, 1, _U32, "overflow_flag"), int(flags), ws, ws_bytes,
+        _stream(stream)))
 
 
-def lohan_ring_init(ring, slots, n, ring_bytes=None):
-    """slots: sequence of num_blocks + 1 tuples (param_fp32, exp_avg, exp_avg_sq, param_16) of
-    tensors / addresses holding n elements each; `ring`: uint8 device tensor or address."""
-    num_blocks = len(slots) - 1
+def lohan_ring_bytes(num_blocks, num_spares=1) -> int:
+    return int(load_library().lohan_ring_bytes(int(num_blocks), int(num_spares)))
+
+
+def lohan_ring_init(ring, slots, num_blocks, ring_bytes=None):
+    """slots: sequence of tuples (param_fp32, exp_avg, exp_avg_sq, param_16, n) of tensors /
+    addresses: first the num_blocks block slots, then one spare per distinct length; `ring`:
+    uint8 device tensor or address."""
+    num_spares = len(slots) - num_blocks
     arr = (LohanRingSlot * len(slots))()
-    for i, (p, m, v, h) in enumerate(slots):
+    for i, (p, m, v, h, n) in enumerate(slots):
         arr[i] = LohanRingSlot(_addr(p, n, _F32, "param_fp32"), _addr(m, n, _F32, "exp_avg"),
-                               _addr(v, n, _F32, "exp_avg_sq"), _addr(h, n, _BF16, "param_16"))
+                               _addr(v, n, _F32, "exp_avg_sq"), _addr(h, n, _BF16, "param_16"),
+                               int(n))
     if ring_bytes is None:
         ring_bytes = ring.numel() * ring.element_size() if hasattr(ring, "numel") else 0
     _check(load_library().lohan_ring_init(_addr(ring, what="ring"), int(ring_bytes), arr,
-                                          int(num_blocks)))
+                                          int(num_blocks), int(num_spares)))
 
 
-def lohan_ring_adam_block_step(ring, num_blocks, block, grad_fp16, n, lr, beta1, beta2, eps,
-                               weight_decay, step, loss_scale, flags=0, stream=None):
+def lohan_ring_adam_block_step(ring, num_blocks, num_spares, block, grad_fp16, n, lr, beta1,
+                               beta2, eps, weight_decay, step, loss_scale, flags=0, stream=None):
     _check(load_library().lohan_ring_adam_block_step(
-        _addr(ring, what="ring"), int(num_blocks), int(block),
+        _addr(ring, what="ring"), int(num_blocks), int(num_spares), int(block),
         _addr(grad_fp16, n, _F16, "grad_fp16"), int(n), float(lr), float(beta1), float(beta2),
         float(eps), float(weight_decay), int(step), float(loss_scale), int(flags),
         _stream(stream)))
 
 
-def lohan_ring_read(ring, num_blocks, stream=None):
-    """Synchronises the stream.  Returns (slot_of list, spare, skipped list of 0/1)."""
+def lohan_ring_adam_block_step_clipped(ring, num_blocks, num_spares, block, grad_fp16, n, lr,
+                                       beta1, beta2, eps, weight_decay, step, loss_scale, sqnorm,
+                                       max_norm, flags=0, stream=None):
+    _check(load_library().lohan_ring_adam_block_step_clipped(
+        _addr(ring, what="ring"), int(num_blocks), int(num_spares), int(block),
+        _addr(grad_fp16, n, _F16, "grad_fp16"), int(n), float(lr), float(beta1), float(beta2),
+        float(eps), float(weight_decay), int(step), float(loss_scale),
+        _addr(sqnorm, 1, _F64, "sqnorm"), float(max_norm), int(flags), _stream(stream)))
+
+
+def lohan_ring_read(ring, num_blocks, num_spares=1, stream=None):
+    """Synchronises the stream.  Returns (slot_of list, spares list, skipped list of 0/1)."""
     slot_of = (ctypes.c_uint32 * num_blocks)()
     last = (ctypes.c_uint32 * num_blocks)()
-    spare = ctypes.c_uint32()
-    _check(load_library().lohan_ring_read(_addr(ring, what="ring"), int(num_blocks), slot_of,
-                                          ctypes.byref(spare), last, _stream(stream)))
-    return list(slot_of), spare.value, list(last)
+    spares = (ctypes.c_uint32 * num_spares)()
+    _check(load_library().lohan_ring_read(_addr(ring, what="ring"), int(num_blocks),
+                                          int(num_spares), slot_of, spares, last,
+                                          _stream(stream)))
+    return list(slot_of), list(spares), list(last)
+
+
+def lohan_tensor_placement(lengths):
+    """Returns (offsets, slab_bytes, slab_alignment); offsets as lohan_model_placement's."""
+    count = len(lengths)
+    arr = (ctypes.c_uint64 * max(1, count))(*[int(x) for x in lengths])
+    out = (LohanBlockOffsets * max(1, count))()
+    total, align = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load_library().lohan_tensor_placement(arr, count, out, ctypes.byref(total),
+                                                 ctypes.byref(align)))
+    fields = [f for f, _ in LohanBlockOffsets._fields_]
+    return ([{f: getattr(out[b], f) for f in fields} for b in range(count)], total.value,
+            align.value)
 
 
 def lohan_model_placement(n, num_blocks=None):
@@ -489,6 +551,10 @@ def lohan_offload_drain(handle):
 
 def lohan_offload_destroy(handle):
     _check(load_library().lohan_offload_destroy(handle))
+
+
+def lohan_tuning_offload_inject_failure(handle, after_calls):
+    _check(load_library().lohan_tuning_offload_inject_failure(handle, int(after_calls)))
 
 
 def _swap_hw(hw: dict) -> LohanSwapHw:

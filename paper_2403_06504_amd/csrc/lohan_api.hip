@@ -291,12 +291,17 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
-lohan_status_t lohan_adam_block_step_out_of_place(
-    const float *param_fp32_in, const float *exp_avg_in, const float *exp_avg_sq_in,
-    const void *grad_fp16, float *param_fp32_out, float *exp_avg_out, float *exp_avg_sq_out,
-    void *param_bf16_out, uint64_t n, float lr, float beta1, float beta2, float eps,
-    float weight_decay, int64_t step, float loss_scale, uint32_t *overflow_flag, uint32_t flags,
-    hipStream_t stream)
+namespace {
+
+// Shared by the two out-of-place entry points; sqnorm == NULL means no clipping.
+lohan_status_t step_out_of_place(const float *param_fp32_in, const float *exp_avg_in,
+                                 const float *exp_avg_sq_in, const void *grad_fp16,
+                                 float *param_fp32_out, float *exp_avg_out, float *exp_avg_sq_out,
+                                 void *param_bf16_out, uint64_t n, float lr, float beta1,
+                                 float beta2, float eps, float weight_decay, int64_t step,
+                                 float loss_scale, const double *sqnorm, float max_norm,
+                                 uint32_t *overflow_flag, uint32_t flags, void *workspace,
+                                 size_t workspace_bytes, hipStream_t stream)
 {
     if ((flags & LOHAN_FLAG_PRECHECKED) != 0) return LOHAN_ERR_ARG;
     lohan_status_t st = validate_step_args(param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16,
@@ -312,15 +317,57 @@ lohan_status_t lohan_adam_block_step_out_of_place(
     if (n != 0 && (param_fp32_out == param_fp32_in || exp_avg_out == exp_avg_in ||
                    exp_avg_sq_out == exp_avg_sq_in))
         return LOHAN_ERR_ARG;
+    float *inv_dev = nullptr;
+    if (sqnorm != nullptr) {
+        if (misaligned(sqnorm, 8)) return LOHAN_ERR_ALIGN;
+        if (!finite_pos(max_norm)) return LOHAN_ERR_ARG;
+        st = check_workspace(workspace, workspace_bytes);
+        if (st != LOHAN_OK) return st;
+        inv_dev = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
+                                            lohan::kScalarsOffset);
+    }
     const lohan::DeviceInfo dev = current_device();
     if (dev.cus <= 0) return LOHAN_ERR_HIP;
     const lohan::StepScalars s =
         make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
+    if (inv_dev != nullptr && n != 0 &&
+        lohan::launch_clip_scale(sqnorm, loss_scale, max_norm, inv_dev, 1, stream) != hipSuccess)
+        return LOHAN_ERR_HIP;
     hipError_t e = lohan::launch_adam_block_step_oop(
         param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16, param_fp32_out, exp_avg_out,
-        exp_avg_sq_out, param_bf16_out, n, s, kernel_mode(flags), overflow_flag,
+        exp_avg_sq_out, param_bf16_out, n, s, kernel_mode(flags), overflow_flag, inv_dev,
         adam_launch_for(n), dev, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
+}  // namespace
+
+lohan_status_t lohan_adam_block_step_out_of_place(
+    const float *param_fp32_in, const float *exp_avg_in, const float *exp_avg_sq_in,
+    const void *grad_fp16, float *param_fp32_out, float *exp_avg_out, float *exp_avg_sq_out,
+    void *param_bf16_out, uint64_t n, float lr, float beta1, float beta2, float eps,
+    float weight_decay, int64_t step, float loss_scale, uint32_t *overflow_flag, uint32_t flags,
+    hipStream_t stream)
+{
+    return step_out_of_place(param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16, param_fp32_out,
+                             exp_avg_out, exp_avg_sq_out, param_bf16_out, n, lr, beta1, beta2, eps,
+                             weight_decay, step, loss_scale, nullptr, 0.0f, overflow_flag, flags,
+                             nullptr, 0, stream);
+}
+
+lohan_status_t lohan_adam_block_step_out_of_place_clipped(
+    const float *param_fp32_in, const float *exp_avg_in, const float *exp_avg_sq_in,
+    const void *grad_fp16, float *param_fp32_out, float *exp_avg_out, float *exp_avg_sq_out,
+    void *param_bf16_out, uint64_t n, float lr, float beta1, float beta2, float eps,
+    float weight_decay, int64_t step, float loss_scale, const double *sqnorm, float max_norm,
+    uint32_t *overflow_flag, uint32_t flags, void *workspace, size_t workspace_bytes,
+    hipStream_t stream)
+{
+    if (sqnorm == nullptr) return LOHAN_ERR_NULL;
+    return step_out_of_place(param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16, param_fp32_out,
+                             exp_avg_out, exp_avg_sq_out, param_bf16_out, n, lr, beta1, beta2, eps,
+                             weight_decay, step, loss_scale, sqnorm, max_norm, overflow_flag,
+                             flags, workspace, workspace_bytes, stream);
 }
 
 lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t num_blocks,
@@ -408,17 +455,65 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
     return LOHAN_OK;
 }
 
-size_t lohan_ring_bytes(uint32_t num_blocks) { return lohan::ring_bytes(num_blocks); }
+namespace {
+
+constexpr uint32_t kRingMaxBlocks = 1u << 20;
+
+bool ring_counts_ok(uint32_t num_blocks, uint32_t num_spares)
+{
+    return num_blocks != 0 && num_blocks <= kRingMaxBlocks && num_spares != 0 &&
+           num_spares <= num_blocks;
+}
+
+lohan_status_t ring_step(void *ring, uint32_t num_blocks, uint32_t num_spares, uint32_t block,
+                         const void *grad_fp16, uint64_t n, float lr, float beta1, float beta2,
+                         float eps, float weight_decay, int64_t step, float loss_scale,
+                         const double *sqnorm, float max_norm, uint32_t flags, hipStream_t stream)
+{
+    if (ring == nullptr || (grad_fp16 == nullptr && n != 0)) return LOHAN_ERR_NULL;
+    if (misaligned(ring, 16) || misaligned(grad_fp16, 16) || misaligned(sqnorm, 8))
+        return LOHAN_ERR_ALIGN;
+    if (!ring_counts_ok(num_blocks, num_spares) || block >= num_blocks) return LOHAN_ERR_ARG;
+    if ((flags & ~(uint32_t)(LOHAN_FLAG_L2_MODE | LOHAN_FLAG_P16_FP16)) != 0) return LOHAN_ERR_ARG;
+    if (step < 1 || !finite_pos(loss_scale) || !finite_nonneg(lr) || !finite_nonneg(eps) ||
+        !finite_nonneg(weight_decay) || !unit_interval(beta1) || !unit_interval(beta2))
+        return LOHAN_ERR_ARG;
+    if (sqnorm != nullptr && !finite_pos(max_norm)) return LOHAN_ERR_ARG;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
+    const lohan::StepScalars s =
+        make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
+    const lohan::RingView view = lohan::ring_view(ring, num_blocks, num_spares);
+    float *inv_dev = nullptr;
+    if (sqnorm != nullptr && n != 0) {
+        inv_dev = view.clip_inv + block;
+        if (lohan::launch_clip_scale(sqnorm, loss_scale, max_norm, inv_dev, 1, stream) !=
+            hipSuccess)
+            return LOHAN_ERR_HIP;
+    }
+    hipError_t e = lohan::launch_adam_ring_step(view, block, grad_fp16, n, s, kernel_mode(flags),
+                                                inv_dev, adam_launch_for(n), dev, stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
+}  // namespace
+
+size_t lohan_ring_bytes(uint32_t num_blocks, uint32_t num_spares)
+{
+    return lohan::ring_bytes(num_blocks, num_spares);
+}
 
 lohan_status_t lohan_ring_init(void *ring, size_t ring_bytes, const lohan_ring_slot_t *slots,
-                               uint32_t num_blocks)
+                               uint32_t num_blocks, uint32_t num_spares)
 {
     if (ring == nullptr || slots == nullptr) return LOHAN_ERR_NULL;
     if (misaligned(ring, 16)) return LOHAN_ERR_ALIGN;
-    if (num_blocks == 0 || num_blocks > (1u << 20)) return LOHAN_ERR_ARG;
-    if (ring_bytes < lohan::ring_bytes(num_blocks)) return LOHAN_ERR_WORKSPACE;
-    for (uint32_t i = 0; i <= num_blocks; ++i) {
+    if (!ring_counts_ok(num_blocks, num_spares)) return LOHAN_ERR_ARG;
+    if (ring_bytes < lohan::ring_bytes(num_blocks, num_spares)) return LOHAN_ERR_WORKSPACE;
+    const uint32_t total = num_blocks + num_spares;
+    for (uint32_t i = 0; i < total; ++i) {
         const lohan_ring_slot_t &slot = slots[i];
+        if (slot.n == 0) continue;                      // an empty slot needs no memory
         if (slot.param_fp32 == nullptr || slot.exp_avg == nullptr || slot.exp_avg_sq == nullptr ||
             slot.param_16 == nullptr)
             return LOHAN_ERR_NULL;
@@ -426,35 +521,51 @@ lohan_status_t lohan_ring_init(void *ring, size_t ring_bytes, const lohan_ring_s
             misaligned(slot.exp_avg_sq, 16) || misaligned(slot.param_16, 16))
             return LOHAN_ERR_ALIGN;
     }
-    // Host image of the table: block b starts in slot b, the last slot is the spare.
-    const size_t bytes = lohan::ring_bytes(num_blocks);
+    // Host image of the table: block b starts in slot b; spare j (slot num_blocks + j) founds
+    // class j, and a block belongs to the class whose spare has exactly its length.
+    const size_t bytes = lohan::ring_bytes(num_blocks, num_spares);
     std::vector<char> image(bytes, 0);
-    lohan::RingView view = lohan::ring_view(image.data(), num_blocks);
-    for (uint32_t i = 0; i <= num_blocks; ++i)
+    lohan::RingView view = lohan::ring_view(image.data(), num_blocks, num_spares);
+    for (uint32_t i = 0; i < total; ++i)
         view.slots[i] = lohan::RingSlot{slots[i].param_fp32, slots[i].exp_avg,
                                         slots[i].exp_avg_sq,
-                                        reinterpret_cast<uint16_t *>(slots[i].param_16)};
-    for (uint32_t b = 0; b < num_blocks; ++b) view.slot_of[b] = b;
-    *view.spare = num_blocks;
+                                        reinterpret_cast<uint16_t *>(slots[i].param_16),
+                                        slots[i].n};
+    for (uint32_t j = 0; j < num_spares; ++j) {
+        for (uint32_t k = 0; k < j; ++k)
+            if (slots[num_blocks + k].n == slots[num_blocks + j].n) return LOHAN_ERR_ARG;
+        view.spare_of_class[j] = num_blocks + j;
+    }
+    for (uint32_t b = 0; b < num_blocks; ++b) {
+        uint32_t cls = num_spares;
+        for (uint32_t j = 0; j < num_spares; ++j)
+            if (slots[num_blocks + j].n == slots[b].n) cls = j;
+        if (cls == num_spares) return LOHAN_ERR_ARG;    // no spare of this block's length
+        view.slot_of[b] = b;
+        view.class_of[b] = cls;
+    }
     return hipMemcpy(ring, image.data(), bytes, hipMemcpyHostToDevice) == hipSuccess
                ? LOHAN_OK
                : LOHAN_ERR_HIP;
 }
 
-lohan_status_t lohan_ring_read(const void *ring, uint32_t num_blocks, uint32_t *slot_of,
-                               uint32_t *spare, uint32_t *skipped, hipStream_t stream)
+lohan_status_t lohan_ring_read(const void *ring, uint32_t num_blocks, uint32_t num_spares,
+                               uint32_t *slot_of, uint32_t *spares, uint32_t *skipped,
+                               hipStream_t stream)
 {
     if (ring == nullptr) return LOHAN_ERR_NULL;
     if (misaligned(ring, 16)) return LOHAN_ERR_ALIGN;
-    if (num_blocks == 0 || num_blocks > (1u << 20)) return LOHAN_ERR_ARG;
+    if (!ring_counts_ok(num_blocks, num_spares)) return LOHAN_ERR_ARG;
     if (hipStreamSynchronize(stream) != hipSuccess) return LOHAN_ERR_HIP;
-    const lohan::RingView view = lohan::ring_view(const_cast<void *>(ring), num_blocks);
+    const lohan::RingView view =
+        lohan::ring_view(const_cast<void *>(ring), num_blocks, num_spares);
     if (slot_of != nullptr &&
         hipMemcpy(slot_of, view.slot_of, sizeof(uint32_t) * num_blocks, hipMemcpyDeviceToHost) !=
             hipSuccess)
         return LOHAN_ERR_HIP;
-    if (spare != nullptr &&
-        hipMemcpy(spare, view.spare, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess)
+    if (spares != nullptr &&
+        hipMemcpy(spares, view.spare_of_class, sizeof(uint32_t) * num_spares,
+                  hipMemcpyDeviceToHost) != hipSuccess)
         return LOHAN_ERR_HIP;
     if (skipped != nullptr) {
         // The two counter arrays are adjacent in the ring: one copy brings both.
@@ -470,27 +581,28 @@ lohan_status_t lohan_ring_read(const void *ring, uint32_t num_blocks, uint32_t *
     return LOHAN_OK;
 }
 
-lohan_status_t lohan_ring_adam_block_step(void *ring, uint32_t num_blocks, uint32_t block,
-                                          const void *grad_fp16, uint64_t n, float lr,
-                                          float beta1, float beta2, float eps,
+lohan_status_t lohan_ring_adam_block_step(void *ring, uint32_t num_blocks, uint32_t num_spares,
+                                          uint32_t block, const void *grad_fp16, uint64_t n,
+                                          float lr, float beta1, float beta2, float eps,
                                           float weight_decay, int64_t step, float loss_scale,
                                           uint32_t flags, hipStream_t stream)
 {
-    if (ring == nullptr || (grad_fp16 == nullptr && n != 0)) return LOHAN_ERR_NULL;
-    if (misaligned(ring, 16) || misaligned(grad_fp16, 16)) return LOHAN_ERR_ALIGN;
-    if (num_blocks == 0 || num_blocks > (1u << 20) || block >= num_blocks) return LOHAN_ERR_ARG;
-    if ((flags & ~(uint32_t)(LOHAN_FLAG_L2_MODE | LOHAN_FLAG_P16_FP16)) != 0) return LOHAN_ERR_ARG;
-    if (step < 1 || !finite_pos(loss_scale) || !finite_nonneg(lr) || !finite_nonneg(eps) ||
-        !finite_nonneg(weight_decay) || !unit_interval(beta1) || !unit_interval(beta2))
-        return LOHAN_ERR_ARG;
-    const lohan::DeviceInfo dev = current_device();
-    if (dev.cus <= 0) return LOHAN_ERR_HIP;
-    const lohan::StepScalars s =
-        make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
-    hipError_t e = lohan::launch_adam_ring_step(lohan::ring_view(ring, num_blocks), block,
-                                                grad_fp16, n, s, kernel_mode(flags),
-                                                adam_launch_for(n), dev, stream);
-    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+    return ring_step(ring, num_blocks, num_spares, block, grad_fp16, n, lr, beta1, beta2, eps,
+                     weight_decay, step, loss_scale, nullptr, 0.0f, flags, stream);
+}
+
+lohan_status_t lohan_ring_adam_block_step_clipped(void *ring, uint32_t num_blocks,
+                                                  uint32_t num_spares, uint32_t block,
+                                                  const void *grad_fp16, uint64_t n, float lr,
+                                                  float beta1, float beta2, float eps,
+                                                  float weight_decay, int64_t step,
+                                                  float loss_scale, const double *sqnorm,
+                                                  float max_norm, uint32_t flags,
+                                                  hipStream_t stream)
+{
+    if (sqnorm == nullptr) return LOHAN_ERR_NULL;
+    return ring_step(ring, num_blocks, num_spares, block, grad_fp16, n, lr, beta1, beta2, eps,
+                     weight_decay, step, loss_scale, sqnorm, max_norm, flags, stream);
 }
 
 lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
@@ -555,6 +667,111 @@ lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
             o.param_bf16 = group_base + take_narrow();
         }
         group_base += room_at[2];                 // lane 2 and what follows it end the group
+    }
+    *slab_bytes = group_base;
+    return LOHAN_OK;
+}
+
+lohan_status_t lohan_tensor_placement(const uint64_t *lengths, uint32_t count,
+                                      lohan_block_offsets_t *offsets, size_t *slab_bytes,
+                                      size_t *slab_alignment)
+{
+    constexpr size_t kBig = 2ull << 20;           // arrays of this size and more: 2 MiB granule
+    constexpr size_t kSmall = 4096;               // smaller ones: 4 KiB granule
+    constexpr size_t kSkew = 1ull << 20;          // lanes are one period plus this apart
+    constexpr size_t kSmallest = 256ull << 20;    // below this the placement gains under 1 %
+    constexpr size_t kPeriods[2] = {4ull << 30, 12ull << 30};
+    if (slab_bytes == nullptr || slab_alignment == nullptr ||
+        (count != 0 && (lengths == nullptr || offsets == nullptr)))
+        return LOHAN_ERR_NULL;
+    for (uint32_t i = 0; i < count; ++i)
+        if (lengths[i] > (1ull << 40)) return LOHAN_ERR_ARG;
+    auto rounded = [&](size_t bytes) {
+        const size_t g = bytes >= kBig ? kBig : kSmall;
+        return (bytes + g - 1) / g * g;
+    };
+    *slab_alignment = kBig;
+    size_t largest = 0;
+    for (uint32_t i = 0; i < count; ++i)
+        if (rounded((size_t)lengths[i] * 4) > largest) largest = rounded((size_t)lengths[i] * 4);
+    size_t period = 0;
+    if (largest >= kSmallest)
+        for (size_t candidate : kPeriods)
+            if (period == 0 && largest <= candidate - kBig) period = candidate;
+
+    // Where an array of `bytes` may start at or after `at` (relative to a 2 MiB-aligned origin):
+    // long arrays on 1 MiB boundaries (the lanes themselves are skewed by 1 MiB), short ones on
+    // 4 KiB boundaries.
+    auto aligned = [&](size_t at, size_t bytes) {
+        const size_t a = bytes >= kBig ? kSkew : kSmall;
+        return (at + a - 1) / a * a;
+    };
+    if (period == 0) {                            // plain tensor-major packing
+        size_t at = 0;
+        auto take = [&](size_t bytes) {
+            const size_t start = aligned(at, bytes);
+            at = start + bytes;
+            return start;
+        };
+        for (uint32_t i = 0; i < count; ++i) {
+            const size_t wide = rounded((size_t)lengths[i] * 4);
+            const size_t narrow = rounded((size_t)lengths[i] * 2);
+            lohan_block_offsets_t &o = offsets[i];
+            o.param_fp32 = take(wide);
+            o.exp_avg = take(wide);
+            o.exp_avg_sq = take(wide);
+            o.grad_fp16 = take(narrow);
+            o.param_bf16 = take(narrow);
+        }
+        *slab_bytes = at;
+        return LOHAN_OK;
+    }
+
+    const size_t lane[3] = {0, period + kSkew, 2 * (period + kSkew)};
+    size_t group_base = 0;
+    uint32_t first = 0;
+    while (first < count) {
+        // A group: consecutive tensors whose fp32 arrays fit one lane together.
+        uint32_t end = first;
+        size_t lane_used = 0;
+        while (end < count) {
+            const size_t wide = rounded((size_t)lengths[end] * 4);
+            const size_t at = aligned(lane_used, wide);
+            if (at + wide > period - kBig) break;
+            lane_used = at + wide;
+            ++end;
+        }
+        // Free room behind the fp32 arrays of lanes 0 and 1 (up to the next lane's start) takes
+        // 16-bit arrays, first fit; whatever does not fit follows lane 2.
+        size_t room_at[3] = {lane[0] + lane_used, lane[1] + lane_used, lane[2] + lane_used};
+        const size_t room_end[2] = {lane[1], lane[2]};
+        auto take_narrow = [&](size_t bytes) {
+            for (int w = 0; w < 2; ++w) {
+                const size_t at = aligned(room_at[w], bytes);
+                if (at + bytes <= room_end[w]) {
+                    room_at[w] = at + bytes;
+                    return at;
+                }
+            }
+            const size_t at = aligned(room_at[2], bytes);
+            room_at[2] = at + bytes;
+            return at;
+        };
+        size_t within = 0;
+        for (uint32_t i = first; i < end; ++i) {
+            const size_t wide = rounded((size_t)lengths[i] * 4);
+            const size_t narrow = rounded((size_t)lengths[i] * 2);
+            within = aligned(within, wide);
+            lohan_block_offsets_t &o = offsets[i];
+            o.param_fp32 = group_base + lane[0] + within;
+            o.exp_avg = group_base + lane[1] + within;
+            o.exp_avg_sq = group_base + lane[2] + within;
+            o.grad_fp16 = group_base + take_narrow(narrow);
+            o.param_bf16 = group_base + take_narrow(narrow);
+            within += wide;
+        }
+        group_base += (room_at[2] + kBig - 1) / kBig * kBig;
+        first = end;
     }
     *slab_bytes = group_base;
     return LOHAN_OK;

@@ -35,41 +35,51 @@ struct MultiArgs {
     MultiDesc d[kMultiMaxBlocks];
 };
 
-// Ring of slots (see k_adam_ring_step).  Device memory layout of a ring for B blocks, all parts
-// 16-byte aligned: B + 1 RingSlot entries, then B uint64 attempt counters, then B uint64
-// "attempt that last overflowed" values, then B uint32 slot indices (slot_of), then one uint32
-// (the spare slot).
+// Ring of slots (see k_adam_ring_step).  Device memory layout of a ring for B blocks and S spare
+// slots (one per distinct block length), all parts 16-byte aligned: B + S RingSlot entries, then B
+// uint64 attempt counters, then B uint64 "attempt that last overflowed" values, then B uint32 slot
+// indices (slot_of), then B uint32 class indices (class_of), then S uint32 slot indices (the
+// spare of each class), then B floats (the unscale factor of a clipped step, one per block).
 struct RingSlot {
     float *p, *m, *v;
     uint16_t *p16;
+    uint64_t n;
 };
 struct RingView {
     RingSlot *slots;
     uint64_t *attempts;
     uint64_t *overflow_attempt;
     uint32_t *slot_of;
-    uint32_t *spare;
+    uint32_t *class_of;
+    uint32_t *spare_of_class;
+    float *clip_inv;
 };
 inline size_t ring_pad16(size_t x) { return (x + 15) / 16 * 16; }
-inline size_t ring_bytes(uint32_t num_blocks)
+inline size_t ring_bytes(uint32_t num_blocks, uint32_t num_spares)
 {
-    return ring_pad16(sizeof(RingSlot) * ((size_t)num_blocks + 1)) +
-           2 * ring_pad16(sizeof(uint64_t) * (size_t)num_blocks) +
-           ring_pad16(sizeof(uint32_t) * (size_t)num_blocks) + 16;
+    const size_t b = num_blocks, s = num_spares;
+    return ring_pad16(sizeof(RingSlot) * (b + s)) + 2 * ring_pad16(sizeof(uint64_t) * b) +
+           2 * ring_pad16(sizeof(uint32_t) * b) + ring_pad16(sizeof(uint32_t) * s) +
+           ring_pad16(sizeof(float) * b);
 }
-inline RingView ring_view(void *ring, uint32_t num_blocks)
+inline RingView ring_view(void *ring, uint32_t num_blocks, uint32_t num_spares)
 {
+    const size_t b = num_blocks, s = num_spares;
     char *base = reinterpret_cast<char *>(ring);
     RingView view;
     view.slots = reinterpret_cast<RingSlot *>(base);
-    base += ring_pad16(sizeof(RingSlot) * ((size_t)num_blocks + 1));
+    base += ring_pad16(sizeof(RingSlot) * (b + s));
     view.attempts = reinterpret_cast<uint64_t *>(base);
-    base += ring_pad16(sizeof(uint64_t) * (size_t)num_blocks);
+    base += ring_pad16(sizeof(uint64_t) * b);
     view.overflow_attempt = reinterpret_cast<uint64_t *>(base);
-    base += ring_pad16(sizeof(uint64_t) * (size_t)num_blocks);
+    base += ring_pad16(sizeof(uint64_t) * b);
     view.slot_of = reinterpret_cast<uint32_t *>(base);
-    base += ring_pad16(sizeof(uint32_t) * (size_t)num_blocks);
-    view.spare = reinterpret_cast<uint32_t *>(base);
+    base += ring_pad16(sizeof(uint32_t) * b);
+    view.class_of = reinterpret_cast<uint32_t *>(base);
+    base += ring_pad16(sizeof(uint32_t) * b);
+    view.spare_of_class = reinterpret_cast<uint32_t *>(base);
+    base += ring_pad16(sizeof(uint32_t) * s);
+    view.clip_inv = reinterpret_cast<float *>(base);
     return view;
 }
 
@@ -121,13 +131,15 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
 hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, const float *v_in,
                                       const void *grad_fp16, float *p_out, float *m_out,
                                       float *v_out, void *p16, uint64_t n, const StepScalars &s,
-                                      int mode, uint32_t *flag, const AdamLaunch &cfg,
-                                      const DeviceInfo &dev, hipStream_t stream);
+                                      int mode, uint32_t *flag, const float *inv_override,
+                                      const AdamLaunch &cfg, const DeviceInfo &dev,
+                                      hipStream_t stream);
 
 // Ring form: the step of `block` from its current slot into the spare, then the commit.
 hipError_t launch_adam_ring_step(const RingView &ring, uint32_t block, const void *grad_fp16,
                                  uint64_t n, const StepScalars &s, int mode,
-                                 const AdamLaunch &cfg, const DeviceInfo &dev, hipStream_t stream);
+                                 const float *inv_override, const AdamLaunch &cfg,
+                                 const DeviceInfo &dev, hipStream_t stream);
 
 // sqnorm[0..count) -> inv_out[0..count)
 hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,

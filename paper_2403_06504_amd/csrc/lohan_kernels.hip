@@ -614,32 +614,43 @@ __global__ __launch_bounds__(WG) void k_adam_block_step_oop(
     const float *__restrict__ pi, const float *__restrict__ mi, const float *__restrict__ vi,
     const uint16_t *__restrict__ g, float *__restrict__ po, float *__restrict__ mo,
     float *__restrict__ vo, uint16_t *__restrict__ p16, uint64_t n, StepScalars s,
-    uint32_t *__restrict__ flag)
+    uint32_t *__restrict__ flag, const float *__restrict__ inv_override)
 {
+    // Device-side clipping: the unscale factor then comes from k_clip_scale's output.
+    if (inv_override != nullptr) s.inv = *inv_override;
     uint32_t ovf = 0;
     adam_oop_body<WG, UNROLL, POLICY, MODE>(pi, mi, vi, g, po, mo, vo, p16, n, s, ovf);
     if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0 && (threadIdx.x & 63u) == 0)
         atomicOr(flag, 1u);
 }
 
-// Ring form of the out-of-place step: a model of B equal blocks lives in B + 1 slots (each slot
-// holds p, m, v and the 16-bit copy of one block), one of them spare.  The step of block b reads
-// the slot that holds b and writes the spare; k_ring_commit then makes the spare b's slot and b's
-// old slot the spare -- unless the gradients overflowed, in which case nothing changes.  Which
-// slot holds which block is a table in device memory, so no host decision (and no host
-// synchronisation) sits between the blocks of a backward pass.  Every block counts its attempts
-// (steps enqueued so far); an overflowing step records its attempt number with an atomic max,
-// which needs no clearing and tells "the latest attempt overflowed" from any older one.
+// Ring form of the out-of-place step: the blocks (or single tensors) of a model live in slots
+// (each slot holds p, m, v and the 16-bit copy of one block), plus one spare slot per distinct
+// length ("class").  The step of block b reads the slot that holds b and writes the spare of b's
+// class; k_ring_commit then makes that spare b's slot and b's old slot the class's spare --
+// unless the gradients overflowed, in which case nothing changes.  Which slot holds which block
+// is a table in device memory, so no host decision (and no host synchronisation) sits between
+// the blocks of a backward pass.  Every block counts its attempts (steps enqueued so far); an
+// overflowing step records its attempt number with an atomic max, which needs no clearing and
+// tells "the latest attempt overflowed" from any older one.  A step whose n is not the length
+// the block was registered with touches nothing and is recorded like an overflow.
 template <int WG, int UNROLL, int POLICY, int MODE>
 __global__ __launch_bounds__(WG) void k_adam_ring_step(
     const RingSlot *__restrict__ slots, const uint32_t *__restrict__ slot_of,
-    const uint32_t *__restrict__ spare, const unsigned long long *__restrict__ attempts,
+    const uint32_t *__restrict__ class_of, const uint32_t *__restrict__ spare_of_class,
+    const unsigned long long *__restrict__ attempts,
     unsigned long long *__restrict__ overflow_attempt, uint32_t block,
-    const uint16_t *__restrict__ g, uint64_t n, StepScalars s)
+    const uint16_t *__restrict__ g, uint64_t n, StepScalars s,
+    const float *__restrict__ inv_override)
 {
     const RingSlot in = slots[slot_of[block]];
-    const RingSlot out = slots[*spare];
+    const RingSlot out = slots[spare_of_class[class_of[block]]];
     const unsigned long long attempt = attempts[block] + 1;
+    if (in.n != n || out.n != n) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicMax(overflow_attempt + block, attempt);
+        return;
+    }
+    if (inv_override != nullptr) s.inv = *inv_override;
     uint32_t ovf = 0;
     adam_oop_body<WG, UNROLL, POLICY, MODE>(in.p, in.m, in.v, g, out.p, out.m, out.v, out.p16, n,
                                             s, ovf);
@@ -647,7 +658,9 @@ __global__ __launch_bounds__(WG) void k_adam_ring_step(
         atomicMax(overflow_attempt + block, attempt);
 }
 
-__global__ void k_ring_commit(uint32_t *__restrict__ slot_of, uint32_t *__restrict__ spare,
+__global__ void k_ring_commit(uint32_t *__restrict__ slot_of,
+                              const uint32_t *__restrict__ class_of,
+                              uint32_t *__restrict__ spare_of_class,
                               unsigned long long *__restrict__ attempts,
                               const unsigned long long *__restrict__ overflow_attempt,
                               uint32_t block)
@@ -656,9 +669,10 @@ __global__ void k_ring_commit(uint32_t *__restrict__ slot_of, uint32_t *__restri
     const unsigned long long attempt = attempts[block] + 1;
     attempts[block] = attempt;
     if (overflow_attempt[block] == attempt) return;    // skipped: the inputs stay the state
+    const uint32_t cls = class_of[block];
     const uint32_t old_slot = slot_of[block];
-    slot_of[block] = *spare;
-    *spare = old_slot;
+    slot_of[block] = spare_of_class[cls];
+    spare_of_class[cls] = old_slot;
 }
 
 // Per-block norm clipping without a host round trip: from the squared norm that
@@ -801,12 +815,13 @@ typedef void (*adam_kernel_t)(float *, float *, float *, const uint16_t *, uint1
                               StepScalars, const uint32_t *, const float *);
 typedef void (*adam_oop_kernel_t)(const float *, const float *, const float *, const uint16_t *,
                                   float *, float *, float *, uint16_t *, uint64_t, StepScalars,
-                                  uint32_t *);
+                                  uint32_t *, const float *);
 
 typedef void (*adam_multi_kernel_t)(MultiArgs, StepScalars, const uint32_t *, const float *);
 typedef void (*adam_ring_kernel_t)(const RingSlot *, const uint32_t *, const uint32_t *,
-                                   const unsigned long long *, unsigned long long *, uint32_t,
-                                   const uint16_t *, uint64_t, StepScalars);
+                                   const uint32_t *, const unsigned long long *,
+                                   unsigned long long *, uint32_t, const uint16_t *, uint64_t,
+                                   StepScalars, const float *);
 
 // The kernel families share the variant space; a family names the function-pointer type and
 // the instantiation for one point of it.
@@ -950,8 +965,9 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
 hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, const float *v_in,
                                       const void *grad_fp16, float *p_out, float *m_out,
                                       float *v_out, void *p16, uint64_t n, const StepScalars &s,
-                                      int mode, uint32_t *flag, const AdamLaunch &cfg,
-                                      const DeviceInfo &dev, hipStream_t stream)
+                                      int mode, uint32_t *flag, const float *inv_override,
+                                      const AdamLaunch &cfg, const DeviceInfo &dev,
+                                      hipStream_t stream)
 {
     // The flag starts at 0 on the stream; the update kernel can only raise it.
     hipLaunchKernelGGL(k_grad_empty, dim3(1), dim3(64), 0, stream, (double *)nullptr, flag);
@@ -965,7 +981,7 @@ hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, cons
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(geo.grid), dim3(geo.wg), geo.lds, stream, p_in, m_in, v_in,
                        reinterpret_cast<const uint16_t *>(grad_fp16), p_out, m_out, v_out,
-                       reinterpret_cast<uint16_t *>(p16), n, s, flag);
+                       reinterpret_cast<uint16_t *>(p16), n, s, flag, inv_override);
     return hipGetLastError();
 }
 
@@ -992,8 +1008,8 @@ hipError_t launch_adam_multi_block_step(const MultiArgs &args, uint32_t num_bloc
 
 hipError_t launch_adam_ring_step(const RingView &ring, uint32_t block, const void *grad_fp16,
                                  uint64_t n, const StepScalars &s, int mode,
-                                 const AdamLaunch &cfg, const DeviceInfo &dev,
-                                  hipStream_t stream)
+                                 const float *inv_override, const AdamLaunch &cfg,
+                                 const DeviceInfo &dev, hipStream_t stream)
 {
     if (n == 0) return hipSuccess;
     if (!adam_variant_valid(cfg.variant) || dev.cus <= 0) return hipErrorInvalidValue;
@@ -1006,12 +1022,13 @@ hipError_t launch_adam_ring_step(const RingView &ring, uint32_t block, const voi
     unsigned long long *overflow_attempt =
         reinterpret_cast<unsigned long long *>(ring.overflow_attempt);
     hipLaunchKernelGGL(kernel, dim3(geo.grid), dim3(geo.wg), geo.lds, stream, ring.slots,
-                       ring.slot_of, ring.spare, attempts, overflow_attempt, block,
-                       reinterpret_cast<const uint16_t *>(grad_fp16), n, s);
+                       ring.slot_of, ring.class_of, ring.spare_of_class, attempts,
+                       overflow_attempt, block, reinterpret_cast<const uint16_t *>(grad_fp16), n,
+                       s, inv_override);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_ring_commit, dim3(1), dim3(64), 0, stream, ring.slot_of, ring.spare,
-                       attempts, overflow_attempt, block);
+    hipLaunchKernelGGL(k_ring_commit, dim3(1), dim3(64), 0, stream, ring.slot_of, ring.class_of,
+                       ring.spare_of_class, attempts, overflow_attempt, block);
     return hipGetLastError();
 }
 

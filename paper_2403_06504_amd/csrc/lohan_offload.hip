@@ -21,6 +21,7 @@
 #include <vector>
 
 #include "lohan_adam.h"
+#include "lohan_adam_tuning.h"
 #include "lohan_kernels.h"
 
 struct lohan_offload {
@@ -35,6 +36,13 @@ struct lohan_offload {
     std::vector<bool> used;
     uint64_t submitted = 0;
     int last_slot = -1;
+    // Set when a submit failed after part of its work had been enqueued: the slot bookkeeping no
+    // longer describes what is in flight, so the handle only drains and dies from then on.
+    bool poisoned = false;
+    // Fault injection for tests (lohan_tuning_offload_inject_failure): when positive, counts the
+    // HIP runtime calls of submits down; the call that brings it to zero is not issued and
+    // reports failure instead.
+    int fail_countdown = 0;
 };
 
 namespace {
@@ -77,6 +85,20 @@ void release(lohan_offload *h)
 #define LOHAN_HIP_TRY(expr)                      \
     do {                                         \
         if ((expr) != hipSuccess) return LOHAN_ERR_HIP; \
+    } while (0)
+
+// Inside lohan_offload_submit, once enqueueing has begun: a failing runtime call (or an injected
+// one) poisons the handle before the error is returned.
+inline bool injected_failure(lohan_offload *h)
+{
+    return h->fail_countdown > 0 && --h->fail_countdown == 0;
+}
+#define LOHAN_SUBMIT_TRY(h, expr)                                \
+    do {                                                         \
+        if (injected_failure(h) || (expr) != hipSuccess) {       \
+            (h)->poisoned = true;                                \
+            return LOHAN_ERR_HIP;                                \
+        }                                                        \
     } while (0)
 
 }  // namespace
@@ -134,6 +156,7 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
                                     float max_norm, uint32_t flags, hipStream_t producer_stream)
 {
     if (h == nullptr || blk == nullptr) return LOHAN_ERR_NULL;
+    if (h->poisoned) return LOHAN_ERR_HIP;
     if (blk->host_param_fp32 == nullptr || blk->host_exp_avg == nullptr ||
         blk->host_exp_avg_sq == nullptr || blk->grad_fp16 == nullptr ||
         blk->param_bf16_out == nullptr || blk->overflow_flag == nullptr)
@@ -165,25 +188,28 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
     // Stage in.  The slot is free once the copy-out of its previous occupant has finished; the
     // serialised mode additionally waits for the copy-out of the previous block, so that no two
     // of the three steps ever overlap.
-    if (h->used[s]) LOHAN_HIP_TRY(hipStreamWaitEvent(h->s_in, h->ev_d2h[s], 0));
+    if (h->used[s]) LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_in, h->ev_d2h[s], 0));
     if (h->mode == LOHAN_OFFLOAD_SERIALIZED && h->last_slot >= 0)
-        LOHAN_HIP_TRY(hipStreamWaitEvent(h->s_in, h->ev_d2h[(size_t)h->last_slot], 0));
-    LOHAN_HIP_TRY(hipMemcpyAsync(dp, blk->host_param_fp32, bytes, hipMemcpyHostToDevice, h->s_in));
-    LOHAN_HIP_TRY(hipMemcpyAsync(dm, blk->host_exp_avg, bytes, hipMemcpyHostToDevice, h->s_in));
-    LOHAN_HIP_TRY(hipMemcpyAsync(dv, blk->host_exp_avg_sq, bytes, hipMemcpyHostToDevice, h->s_in));
-    LOHAN_HIP_TRY(hipEventRecord(h->ev_h2d[s], h->s_in));
+        LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_in, h->ev_d2h[(size_t)h->last_slot], 0));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dp, blk->host_param_fp32, bytes, hipMemcpyHostToDevice, h->s_in));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dm, blk->host_exp_avg, bytes, hipMemcpyHostToDevice, h->s_in));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dv, blk->host_exp_avg_sq, bytes, hipMemcpyHostToDevice, h->s_in));
+    LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_h2d[s], h->s_in));
 
     // Step: needs the staged states and the gradients the producer stream has enqueued so far.
-    LOHAN_HIP_TRY(hipEventRecord(h->ev_grad[s], producer_stream));
-    LOHAN_HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_grad[s], 0));
-    LOHAN_HIP_TRY(hipStreamWaitEvent(h->s_compute, h->ev_h2d[s], 0));
+    LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_grad[s], producer_stream));
+    LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_compute, h->ev_grad[s], 0));
+    LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_compute, h->ev_h2d[s], 0));
     if (blk->sqnorm != nullptr)
         st = lohan_grad_sqnorm(blk->grad_fp16, blk->n, loss_scale, blk->sqnorm,
                                blk->overflow_flag, ws, lohan::kWorkspaceBytes, h->s_compute);
     else
         st = lohan_grad_overflow_check(blk->grad_fp16, blk->n, blk->overflow_flag, ws,
                                        lohan::kWorkspaceBytes, h->s_compute);
-    if (st != LOHAN_OK) return st;
+    if (st != LOHAN_OK) {
+        h->poisoned = true;
+        return st;
+    }
     if (clip)
         st = lohan_adam_block_step_clipped(dp, dm, dv, blk->grad_fp16, blk->param_bf16_out,
                                            blk->n, lr, beta1, beta2, eps, weight_decay, step,
@@ -194,15 +220,18 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
                                    beta1, beta2, eps, weight_decay, step, loss_scale,
                                    blk->overflow_flag, flags | LOHAN_FLAG_PRECHECKED, nullptr, 0,
                                    h->s_compute);
-    if (st != LOHAN_OK) return st;
-    LOHAN_HIP_TRY(hipEventRecord(h->ev_step[s], h->s_compute));
+    if (st != LOHAN_OK) {
+        h->poisoned = true;
+        return st;
+    }
+    LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_step[s], h->s_compute));
 
     // Stage out.  A skipped step left the slot untouched, so the copy writes back the same bits.
-    LOHAN_HIP_TRY(hipStreamWaitEvent(h->s_out, h->ev_step[s], 0));
-    LOHAN_HIP_TRY(hipMemcpyAsync(blk->host_param_fp32, dp, bytes, hipMemcpyDeviceToHost, h->s_out));
-    LOHAN_HIP_TRY(hipMemcpyAsync(blk->host_exp_avg, dm, bytes, hipMemcpyDeviceToHost, h->s_out));
-    LOHAN_HIP_TRY(hipMemcpyAsync(blk->host_exp_avg_sq, dv, bytes, hipMemcpyDeviceToHost, h->s_out));
-    LOHAN_HIP_TRY(hipEventRecord(h->ev_d2h[s], h->s_out));
+    LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_out, h->ev_step[s], 0));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_param_fp32, dp, bytes, hipMemcpyDeviceToHost, h->s_out));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_exp_avg, dm, bytes, hipMemcpyDeviceToHost, h->s_out));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_exp_avg_sq, dv, bytes, hipMemcpyDeviceToHost, h->s_out));
+    LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_d2h[s], h->s_out));
 
     h->used[s] = true;
     h->last_slot = slot;
@@ -213,6 +242,7 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
 lohan_status_t lohan_offload_wait_last_step(lohan_offload_t *h, hipStream_t stream)
 {
     if (h == nullptr) return LOHAN_ERR_NULL;
+    if (h->poisoned) return LOHAN_ERR_HIP;
     if (h->last_slot < 0) return LOHAN_OK;
     LOHAN_HIP_TRY(hipStreamWaitEvent(stream, h->ev_step[(size_t)h->last_slot], 0));
     return LOHAN_OK;
@@ -224,6 +254,14 @@ lohan_status_t lohan_offload_drain(lohan_offload_t *h)
     LOHAN_HIP_TRY(hipStreamSynchronize(h->s_in));
     LOHAN_HIP_TRY(hipStreamSynchronize(h->s_compute));
     LOHAN_HIP_TRY(hipStreamSynchronize(h->s_out));
+    return LOHAN_OK;
+}
+
+lohan_status_t lohan_tuning_offload_inject_failure(lohan_offload_t *h, int after_calls)
+{
+    if (h == nullptr) return LOHAN_ERR_NULL;
+    if (after_calls < 0) return LOHAN_ERR_ARG;
+    h->fail_countdown = after_calls + 1;
     return LOHAN_OK;
 }
 

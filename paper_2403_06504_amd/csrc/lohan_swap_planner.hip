@@ -100,34 +100,34 @@ lohan_status_t lohan_plan_activation_swapping(const lohan_layer_t *layers, size_
         if (!nonneg_finite(layers[i].flop) || !nonneg_finite(layers[i].act_bytes))
             return LOHAN_ERR_ARG;
 
-    // layer_list.sortByOffloadingBenefit()
+    // Every candidate answer is a prefix of the benefit order.  Evaluate them all: swapped bytes,
+    // recomputation left (Eq. 7 at a breakpoint) and modelled iteration time (Eq. 1-5) of the
+    // first k layers, k = 0..n.
     const std::vector<uint32_t> order = benefit_order(layers, n);
+    std::vector<double> swapped(n + 1, 0.0), saved(n + 1, 0.0), time(n + 1, 0.0);
+    for (size_t k = 1; k <= n; ++k) {
+        swapped[k] = swapped[k - 1] + layers[order[k - 1]].act_bytes;
+        saved[k] = saved[k - 1] + layers[order[k - 1]].flop;
+    }
+    for (size_t k = 0; k <= n; ++k) time[k] = iter_time(*hw, swapped[k], hw->flop_f - saved[k]);
 
-    size_t count = 0;
-    double t_min = std::numeric_limits<double>::infinity();
-    double a_run = 0.0;
-    double f_run = hw->flop_f;                                  // full recomputation
-    for (uint32_t idx : order) {
-        a_run += layers[idx].act_bytes;
-        f_run -= layers[idx].flop;
-        const double t = iter_time(*hw, a_run, f_run);
-        if (t >= t_min) {
-            if (a_run >= hw->a_interblock) break;               // past the out-of-memory floor
-        } else {
-            t_min = t;
+    // Algorithm 1 (Sec. IV-D) keeps extending the prefix until one fails to beat every shorter
+    // non-empty prefix while already holding at least A_interBlock bytes; the prefix before that
+    // one is the plan (T_iter is convex along the order, so this is where it turns).
+    size_t count = n;
+    double best = std::numeric_limits<double>::infinity();
+    for (size_t k = 1; k <= n; ++k) {
+        if (swapped[k] >= hw->a_interblock && time[k] >= best) {
+            count = k - 1;
+            break;
         }
-        swap_list[count++] = idx;
+        best = std::min(best, time[k]);
     }
-    // Describe the list that is returned (the layer that ended the search is not part of it).
-    double a_sw = 0.0, f_sw = 0.0;
-    for (size_t k = 0; k < count; ++k) {
-        a_sw += layers[swap_list[k]].act_bytes;
-        f_sw += layers[swap_list[k]].flop;
-    }
+    for (size_t k = 0; k < count; ++k) swap_list[k] = order[k];
     *n_swapped = count;
-    *a_g2m = a_sw;
-    *flop_r = hw->flop_f - f_sw;
-    *t_iter = iter_time(*hw, a_sw, hw->flop_f - f_sw);
+    *a_g2m = swapped[count];
+    *flop_r = hw->flop_f - saved[count];
+    *t_iter = time[count];
     return LOHAN_OK;
 }
 

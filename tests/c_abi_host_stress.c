@@ -83,11 +83,33 @@ int main(void)
                                     (uint32_t *)0xB000, NULL, 0, (void *)0xC000,
                                     lohan_workspace_bytes(), NULL) != LOHAN_ERR_NULL)
         return 10;
-    lohan_ring_slot_t slots[3] = {{(float *)0x1000, (float *)0x2000, (float *)0x3000, (void *)0x4000},
-                                  {(float *)0x5000, (float *)0x6000, (float *)0x7000, (void *)0x8000},
-                                  {(float *)0x9000, (float *)0xA000, (float *)0xB004, (void *)0xC000}};
-    if (lohan_ring_init((void *)0x10000, lohan_ring_bytes(2), slots, 2) != LOHAN_ERR_ALIGN)
+    lohan_ring_slot_t slots[3] = {
+        {(float *)0x1000, (float *)0x2000, (float *)0x3000, (void *)0x4000, 16},
+        {(float *)0x5000, (float *)0x6000, (float *)0x7000, (void *)0x8000, 16},
+        {(float *)0x9000, (float *)0xA000, (float *)0xB004, (void *)0xC000, 16}};
+    if (lohan_ring_init((void *)0x10000, lohan_ring_bytes(2, 1), slots, 2, 1) != LOHAN_ERR_ALIGN)
         return 11;
+    slots[2].exp_avg_sq = (float *)0xB000;
+    slots[2].n = 17;                                    /* no spare of the blocks' length */
+    if (lohan_ring_init((void *)0x10000, lohan_ring_bytes(2, 1), slots, 2, 1) != LOHAN_ERR_ARG)
+        return 12;
+    /* per-tensor placement: many shapes, every array inside the slab and disjoint */
+    for (int trial = 0; trial < 200; ++trial) {
+        uint64_t lengths[24];
+        lohan_block_offsets_t off[24];
+        const uint32_t count = 1 + (uint32_t)(trial % 24);
+        for (uint32_t i = 0; i < count; ++i)
+            lengths[i] = (uint64_t)((trial * 2654435761u + i * 40503u) % 97) *
+                             (trial % 3 == 0 ? 3000001ull : 20011ull) +
+                         (trial % 5 == 0 && i == 0 ? (1ull << 27) : 0);
+        size_t bytes = 0, align = 0;
+        if (lohan_tensor_placement(lengths, count, off, &bytes, &align) != LOHAN_OK) return 13;
+        for (uint32_t i = 0; i < count; ++i) {
+            if (off[i].param_fp32 + lengths[i] * 4 > bytes || off[i].param_bf16 + lengths[i] * 2 > bytes)
+                return 14;
+            checksum += (double)off[i].exp_avg_sq * 1e-12;
+        }
+    }
     printf("ok %.6e\n", checksum);
     return 0;
 }

@@ -102,25 +102,13 @@ def assert_state_parity(got: dict, want: dict, what=""):
     return worst
 
 
-def assert_parity_given_scales(got: dict, want: dict, old: dict, g_bits, s_eff_gpu, s_eff_orc, lr,
-                               what=""):
-    """Compare a clipped step.  `want` is the oracle's result with ITS effective loss scale,
-    `old` the state before the step.  Equal effective scales (as fp32) demand bit equality; scales
-    one ulp apart make every unscaled gradient differ by one ulp between the two sides, so the
-    outputs may differ by a few ulp of the operands that were summed (sums can cancel): the bound
-    is then taken at the operands' magnitude."""
-    a32, b32 = np.float32(s_eff_gpu), np.float32(s_eff_orc)
-    if a32 == b32:
-        worst = assert_state_parity(got, want, what=what)
-        assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}, (what, worst)
-        return
-    assert abs(int(a32.view(np.uint32)) - int(b32.view(np.uint32))) == 1, (what, a32, b32)
-    gval = np.abs(g_bits.view(np.float16).astype(np.float32)) / b32
-    mag = {"p": np.maximum(np.maximum(np.abs(old["p"]), np.abs(want["p"])), np.float32(lr)),
-           "m": np.maximum(np.maximum(np.abs(old["m"]), np.abs(want["m"])), gval),
-           "v": np.maximum(np.maximum(old["v"], want["v"]), gval * gval)}
-    for k in ("p", "m", "v"):
-        err = np.abs(got[k].astype(np.float64) - want[k].astype(np.float64))
-        bound = 4 * np.spacing(mag[k]).astype(np.float64)
-        i = int(np.argmax(err - bound))
-        assert np.all(err <= bound), (what, k, i, float(err[i]), float(bound[i]))
+def assert_scale_within_one_ulp(s_eff_gpu, s_eff_orc, what=""):
+    """Clipped route, first half of the bar: the effective loss scale fp32(S / coef) that the HIP
+    path derives from ITS squared norm and the one the oracle derives from its own may differ by
+    at most one fp32 unit in the last place (the two norms agree to 1e-5 relative or far better,
+    and the scale is rounded once to fp32).  The second half -- the oracle stepped with the HIP
+    path's own effective scale equals the HIP result bit for bit -- is assert_state_parity with
+    an all-zero worst case, at the call site."""
+    a = int(np.float32(s_eff_gpu).view(np.uint32))
+    b = int(np.float32(s_eff_orc).view(np.uint32))
+    assert abs(a - b) <= 1, (what, float(np.float32(s_eff_gpu)), float(np.float32(s_eff_orc)))

@@ -261,38 +261,121 @@ def test_model_placement_properties(lib):
 
 
 def test_ring_validation_returns_before_any_device_call(lib):
-    need = lib.lohan_ring_bytes(4)
-    assert need >= 5 * 32 + 2 * 4 * 8 + 4 * 4 + 4 and need % 16 == 0
-    assert lib.lohan_ring_bytes(40) > need
-    good = (binding.LohanRingSlot * 5)(*[binding.LohanRingSlot(A * (4 * i + 1), A * (4 * i + 2),
-                                                               A * (4 * i + 3), A * (4 * i + 4))
-                                         for i in range(5)])
-    assert lib.lohan_ring_init(None, need, good, 4) == 1
-    assert lib.lohan_ring_init(A, need, None, 4) == 1
-    assert lib.lohan_ring_init(A + 8, need, good, 4) == 2
-    assert lib.lohan_ring_init(A, need, good, 0) == 3
-    assert lib.lohan_ring_init(A, need - 1, good, 4) == 4
-    for field in ("param_fp32", "exp_avg", "exp_avg_sq", "param_16"):
-        bad = (binding.LohanRingSlot * 5)(*good)
-        setattr(bad[4], field, None)                             # the spare slot counts too
-        assert lib.lohan_ring_init(A, need, bad, 4) == 1, field
-        setattr(bad[4], field, A * 50 + 4)
-        assert lib.lohan_ring_init(A, need, bad, 4) == 2, field
+    need = lib.lohan_ring_bytes(4, 1)
+    assert need >= 5 * 40 + 2 * 4 * 8 + 2 * 4 * 4 + 4 + 4 * 4 and need % 16 == 0
+    assert lib.lohan_ring_bytes(40, 1) > need and lib.lohan_ring_bytes(4, 3) > need
 
-    def step(ring=A, nb=4, block=1, g=A * 2, n=16, step=1, loss_scale=1024.0, flags=0, **over):
+    def slots(lengths):
+        return (binding.LohanRingSlot * len(lengths))(*[
+            binding.LohanRingSlot(A * (4 * i + 1), A * (4 * i + 2), A * (4 * i + 3),
+                                  A * (4 * i + 4), n) for i, n in enumerate(lengths)])
+
+    good = slots([16] * 5)
+    assert lib.lohan_ring_init(None, need, good, 4, 1) == 1
+    assert lib.lohan_ring_init(A, need, None, 4, 1) == 1
+    assert lib.lohan_ring_init(A + 8, need, good, 4, 1) == 2
+    assert lib.lohan_ring_init(A, need, good, 0, 1) == 3
+    assert lib.lohan_ring_init(A, need, good, 4, 0) == 3            # at least one spare
+    assert lib.lohan_ring_init(A, need, good, 2, 3) == 3            # more spares than blocks
+    assert lib.lohan_ring_init(A, need - 1, good, 4, 1) == 4
+    for field in ("param_fp32", "exp_avg", "exp_avg_sq", "param_16"):
+        bad = slots([16] * 5)
+        setattr(bad[4], field, None)                             # the spare slot counts too
+        assert lib.lohan_ring_init(A, need, bad, 4, 1) == 1, field
+        setattr(bad[4], field, A * 50 + 4)
+        assert lib.lohan_ring_init(A, need, bad, 4, 1) == 2, field
+    # unequal lengths: every block needs a spare of exactly its length, spares must be distinct
+    need2 = lib.lohan_ring_bytes(4, 2)
+    assert lib.lohan_ring_init(A, need2, slots([16, 8, 16, 8, 16, 9]), 4, 2) == 3
+    assert lib.lohan_ring_init(A, need2, slots([16, 8, 16, 8, 16, 16]), 4, 2) == 3
+    assert lib.lohan_ring_init(A, need2, slots([16, 8, 16, 7, 16, 8]), 4, 2) == 3
+
+    def step(ring=A, nb=4, ns=1, block=1, g=A * 2, n=16, step=1, loss_scale=1024.0, flags=0,
+             **over):
         h = dict(GOOD, **over)
-        return lib.lohan_ring_adam_block_step(ring, nb, block, g, n, h["lr"], h["beta1"],
+        return lib.lohan_ring_adam_block_step(ring, nb, ns, block, g, n, h["lr"], h["beta1"],
                                               h["beta2"], h["eps"], h["weight_decay"], step,
                                               loss_scale, flags, None)
 
     assert step(ring=None) == 1 and step(g=None) == 1
     assert step(ring=A + 4) == 2 and step(g=A * 2 + 2) == 2
-    assert step(block=4) == 3 and step(nb=0) == 3
+    assert step(block=4) == 3 and step(nb=0) == 3 and step(ns=0) == 3 and step(ns=5) == 3
     assert step(flags=2) == 3 and step(flags=8) == 3            # no prechecked form
     assert step(step=0) == 3 and step(loss_scale=math.nan) == 3 and step(beta2=1.0) == 3
-    assert lib.lohan_ring_read(None, 4, None, None, None, None) == 1
-    assert lib.lohan_ring_read(A + 4, 4, None, None, None, None) == 2
-    assert lib.lohan_ring_read(A, 0, None, None, None, None) == 3
+
+    def clipped(sqnorm=A * 9, max_norm=1.0, **kw):
+        return lib.lohan_ring_adam_block_step_clipped(
+            kw.get("ring", A), 4, 1, kw.get("block", 1), A * 2, 16, GOOD["lr"], GOOD["beta1"],
+            GOOD["beta2"], GOOD["eps"], GOOD["weight_decay"], 1, GOOD["loss_scale"], sqnorm,
+            max_norm, 0, None)
+
+    assert clipped(sqnorm=None) == 1 and clipped(sqnorm=A * 9 + 4) == 2
+    for bad in (0.0, -1.0, math.inf, math.nan):
+        assert clipped(max_norm=bad) == 3
+    assert lib.lohan_ring_read(None, 4, 1, None, None, None, None) == 1
+    assert lib.lohan_ring_read(A + 4, 4, 1, None, None, None, None) == 2
+    assert lib.lohan_ring_read(A, 0, 1, None, None, None, None) == 3
+
+
+def test_out_of_place_clipped_validation(lib):
+    ws_bytes = lib.lohan_workspace_bytes()
+
+    def status(sqnorm=A * 20, max_norm=1.0, ws=A * 21, wsb=ws_bytes, flags=0, po=A * 11):
+        return lib.lohan_adam_block_step_out_of_place_clipped(
+            A, A * 2, A * 3, A * 4, po, A * 12, A * 13, A * 5, 16, GOOD["lr"], GOOD["beta1"],
+            GOOD["beta2"], GOOD["eps"], GOOD["weight_decay"], 1, GOOD["loss_scale"], sqnorm,
+            max_norm, A * 6, flags, ws, wsb, None)
+
+    assert status(sqnorm=None) == 1 and status(ws=None) == 1
+    assert status(sqnorm=A * 20 + 4) == 2 and status(ws=A * 21 + 8) == 2
+    assert status(max_norm=0.0) == 3 and status(max_norm=math.nan) == 3
+    assert status(flags=lohan.LOHAN_FLAG_PRECHECKED) == 3
+    assert status(po=A) == 3                                   # output must differ from input
+    assert status(wsb=16) == 4
+
+
+def test_tensor_placement_properties(lib):
+    """Per-tensor placement: inside the slab, aligned, disjoint, p/m/v of one tensor at the same
+    offset within lanes one period + 1 MiB apart, and equal to the equal-block placement when the
+    lengths are equal."""
+    mib, gib = 1 << 20, 1 << 30
+    h = 5120
+    one_layer = [3 * h * h, 3 * h, h * h, h, 4 * h * h, 4 * h, 4 * h * h, h, h, h, h, h]
+    cases = [one_layer * 40, [12 * 1024 * 1024] * 3, [7, 0, 300, 5_000_000],
+             [12 * 12288 * 12288, 12 * 5120 * 5120, 1000], [1 << 26] * 9, [3 * (1 << 30) + 5] * 2]
+    for lengths in cases:
+        offsets, total, align = lohan.lohan_tensor_placement(lengths)
+        assert align == 2 * mib and len(offsets) == len(lengths)
+        spans = []
+        for n, o in zip(lengths, offsets):
+            for field, width in (("param_fp32", 4), ("exp_avg", 4), ("exp_avg_sq", 4),
+                                 ("grad_fp16", 2), ("param_bf16", 2)):
+                assert o[field] % 4096 == 0 and o[field] + n * width <= total
+                if n * width >= 2 * mib:
+                    assert o[field] % mib == 0
+                spans.append((o[field], o[field] + n * width))
+        spans = sorted(s for s in spans if s[1] > s[0])
+        assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:])), "arrays overlap"
+        widest = max(lengths) * 4
+        if 256 * mib <= widest <= 12 * gib - 2 * mib:
+            period = 4 * gib if widest <= 4 * gib - 2 * mib else 12 * gib
+            for o in offsets:
+                assert o["exp_avg"] - o["param_fp32"] == period + mib
+                assert o["exp_avg_sq"] - o["exp_avg"] == period + mib
+        payload = 16 * sum(lengths)
+        assert total >= payload
+    # equal lengths of 2^26 elements and more: the same offsets as lohan_model_placement
+    for n, count in ((12 * 5120 * 5120, 7), (12 * 12288 * 12288, 3), (1 << 26, 20)):
+        a, total_a, _, _ = lohan.lohan_model_placement(n, count)
+        b, total_b, _ = lohan.lohan_tensor_placement([n] * count)
+        assert a == b and total_a == total_b
+    # a 13B model tensor by tensor: the short vectors cost little
+    offsets, total, _ = lohan.lohan_tensor_placement(one_layer * 40)
+    equal, total_equal, _, _ = lohan.lohan_model_placement(12 * h * h, 40)
+    assert total <= 1.02 * total_equal
+    with pytest.raises(lohan.LohanError) as e:
+        lohan.lohan_tensor_placement([1, (1 << 40) + 1])
+    assert e.value.status == 3
 
 
 def test_offload_create_validation_touches_no_device(lib):

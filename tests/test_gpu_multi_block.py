@@ -10,7 +10,7 @@ import torch
 import paper_2403_06504_amd as lohan
 from paper_2403_06504_amd import synthetic_inputs as synth
 
-from gpu_util import (RTOL_SQNORM, DeviceBlock, assert_parity_given_scales, assert_state_parity,
+from gpu_util import (RTOL_SQNORM, DeviceBlock, assert_scale_within_one_ulp, assert_state_parity,
                       oracle_steps)
 
 pytestmark = pytest.mark.gpu
@@ -143,13 +143,26 @@ def test_prechecked_flags_are_read_only(oracle):
 
 @pytest.mark.parametrize("S,max_norm", [(65536.0, 0.5), (3000.0, 0.05), (1024.0, 100.0)])
 def test_per_block_clipping(oracle, S, max_norm):
-    """Each block is clipped by its own norm; bit-identical to the single-block clipped route, and
-    against the oracle as that route is."""
+    """Each block is clipped by its own norm.  Bar against the oracle, per block: the effective
+    loss scale from the call's own squared norm is within one fp32 ulp of the oracle's, and the
+    oracle stepped with that scale reproduces the block bit for bit.  Against the single-block
+    clipped route: the reduction splits a block over a different number of workgroups there, so
+    its float64 sum may differ in the last bits; the states are bit-identical whenever the two
+    routes' norms are."""
     sizes = [300_007, 70_001, 1_000_003, 257]
+    want_norms = S != 3000.0
     bs = BlockSet(sizes, seed0=30, S=S, overflow=(1,))
     single = BlockSet(sizes, seed0=30, S=S, overflow=(1,))
     hosts = bs.host()
-    assert bs.step(max_norm=max_norm, want_norms=(S != 3000.0)) == [0, 1, 0, 0]
+    assert bs.step(max_norm=max_norm, want_norms=want_norms) == [0, 1, 0, 0]
+    if want_norms:
+        norms = bs.sqnorms.cpu().numpy()
+    else:
+        # The norms of that call stayed in its workspace; the same call on the same data with the
+        # norms requested reproduces them (fixed-order reduction, same launch shape).
+        probe = BlockSet(sizes, seed0=30, S=S, overflow=(1,))
+        probe.step(max_norm=max_norm, want_norms=True)
+        norms = probe.sqnorms.cpu().numpy()
     hy = bs.hy
     for i, blk in enumerate(single.blocks):
         blk.norm(S)
@@ -159,18 +172,23 @@ def test_per_block_clipping(oracle, S, max_norm):
                                             max_norm, blk.flag, 0, blk.ws)
         torch.cuda.synchronize()
         a, b = bs.blocks[i].host(), blk.host()
-        for k in ("p", "m", "v", "p16"):
-            assert np.array_equal(a[k].view(np.uint8), b[k].view(np.uint8)), (i, k)
-        if i == 1:
+        if i == 1:                                   # overflowed: both routes left it untouched
+            for k in ("p", "m", "v", "p16"):
+                assert np.array_equal(a[k].view(np.uint8), hosts[i][k].view(np.uint8)), (i, k)
+                assert np.array_equal(b[k].view(np.uint8), hosts[i][k].view(np.uint8)), (i, k)
             continue
-        sq_gpu = float(blk.sqnorm.cpu().item())
-        s_eff_gpu = lohan.lohan_clip_loss_scale(sq_gpu, S, max_norm)
+        sq_multi, sq_single = float(norms[i]), float(blk.sqnorm.cpu().item())
+        assert abs(sq_multi - sq_single) <= RTOL_SQNORM * sq_single
+        if sq_multi == sq_single:
+            for k in ("p", "m", "v", "p16"):
+                assert np.array_equal(a[k].view(np.uint8), b[k].view(np.uint8)), (i, k)
+        s_eff_gpu = lohan.lohan_clip_loss_scale(sq_multi, S, max_norm)
         sq_orc = oracle.grad_sqnorm(hosts[i]["g"], S)
+        assert abs(sq_multi - sq_orc) <= RTOL_SQNORM * sq_orc
         s_eff_orc = float(oracle.clip_loss_scale(sq_orc, S, max_norm))
-        old = {k: hosts[i][k].copy() for k in ("p", "m", "v")}
-        oracle_steps(oracle, hosts[i], dict(hy, loss_scale=s_eff_orc), 1, nthreads=4)
-        assert_parity_given_scales(a, hosts[i], old, hosts[i]["g"], s_eff_gpu, s_eff_orc,
-                                   hy["lr"], what=f"multi-block clipping block {i}")
+        assert_scale_within_one_ulp(s_eff_gpu, s_eff_orc, what=f"multi-block clipping block {i}")
+        oracle_steps(oracle, hosts[i], dict(hy, loss_scale=s_eff_gpu), 1, nthreads=4)
+        assert assert_state_parity(a, hosts[i], what=f"multi-block clipping block {i}") == ZERO
 
 
 def test_every_kernel_variant_multi_block(oracle):
@@ -251,14 +269,10 @@ def test_multi_block_call_in_a_hip_graph(oracle):
             assert abs(norms[i] - sq_orc) <= RTOL_SQNORM * sq_orc
             s_eff_gpu = lohan.lohan_clip_loss_scale(float(norms[i]), S, max_norm)
             s_eff_orc = float(oracle.clip_loss_scale(sq_orc, S, max_norm))
-            old = {k: h[k].copy() for k in ("p", "m", "v")}
-            oracle_steps(oracle, h, dict(hy, loss_scale=s_eff_orc), 1, nthreads=4)
+            assert_scale_within_one_ulp(s_eff_gpu, s_eff_orc, what=f"replay {r} block {i}")
+            oracle_steps(oracle, h, dict(hy, loss_scale=s_eff_gpu), 1, nthreads=4)
             got = blk.host()
-            assert_parity_given_scales(got, h, old, h["g"], s_eff_gpu, s_eff_orc, hy["lr"],
-                                       what=f"graph replay {r} block {i}")
-            if np.float32(s_eff_gpu) != np.float32(s_eff_orc):
-                for k in ("p", "m", "v", "p16"):        # keep the two sides on the same state
-                    h[k][...] = got[k]
+            assert assert_state_parity(got, h, what=f"graph replay {r} block {i}") == ZERO
         scratch.add_(1.0)
         warm.step(max_norm=max_norm)
     assert float(scratch[0].cpu()) == 3.0

@@ -213,3 +213,68 @@ def test_175b_block_out_of_place_sampled(oracle):
     assert bool(torch.all(err <= scale))
     blk.g.view(torch.int16)[wl.n - 1] = 0x7E00
     assert blk.step(dict(hy, step=hy["step"] + 1)) == 1 and blk.cur == 1
+
+
+@pytest.mark.parametrize("n,S,max_norm", [(1_000_003, 65536.0, 0.5), (70_001, 3000.0, 0.05),
+                                          (5_000, 1024.0, 100.0), (7, 65536.0, 1e-3)])
+def test_clipped_single_pass_form(oracle, n, S, max_norm):
+    """lohan_grad_sqnorm + lohan_adam_block_step_out_of_place_clipped: per-block clipping resolved
+    on the device, the update out of place with the overflow test fused in.  Bit-identical to the
+    in-place clipped step given the same squared norm; against the oracle, the effective scale is
+    within one fp32 ulp of the oracle's own and the oracle stepped with the HIP path's scale
+    reproduces the outputs bit for bit.  An overflowing block raises the flag and leaves the
+    inputs untouched."""
+    from gpu_util import assert_scale_within_one_ulp
+    wl = synth.Workload(name=f"n{n}", n=n, step=100, loss_scale=S, zero_moments=False)
+    hy = wl.hyper()
+    base = synth.make_block(wl, seed=300 + n % 89, device=DEV)
+    blk = TwoSets({k: t.clone() for k, t in base.items()})
+    inplace = DeviceBlock({k: t.clone() for k, t in base.items()})
+    host = blk.host()
+    sqnorm = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = lohan.new_workspace(DEV)
+
+    def clipped_step(b):
+        a, o = b.sets[b.cur], b.sets[1 - b.cur]
+        lohan.lohan_grad_sqnorm(b.g, n, S, sqnorm, None, ws)
+        lohan.lohan_adam_block_step_out_of_place_clipped(
+            a["p"], a["m"], a["v"], b.g, o["p"], o["m"], o["v"], o["p16"], n, hy["lr"],
+            hy["beta1"], hy["beta2"], hy["eps"], hy["weight_decay"], hy["step"], S, sqnorm,
+            max_norm, b.flag, 0, ws)
+        torch.cuda.synchronize()
+        return int(b.flag.cpu().item())
+
+    assert clipped_step(blk) == 0
+    got = blk.host(which=1)
+    inputs_after = blk.host(which=0)
+    for k in ("p", "m", "v"):
+        assert np.array_equal(inputs_after[k].view(np.uint8), host[k].view(np.uint8)), k
+
+    inplace.norm(S)
+    lohan.lohan_adam_block_step_clipped(inplace.p, inplace.m, inplace.v, inplace.g, inplace.p16,
+                                        n, hy["lr"], hy["beta1"], hy["beta2"], hy["eps"],
+                                        hy["weight_decay"], hy["step"], S, inplace.sqnorm,
+                                        max_norm, inplace.flag, 0, inplace.ws)
+    torch.cuda.synchronize()
+    assert float(inplace.sqnorm.cpu().item()) == float(sqnorm.cpu().item())
+    same = inplace.host()
+    for k in ("p", "m", "v", "p16"):
+        assert np.array_equal(got[k].view(np.uint8), same[k].view(np.uint8)), k
+
+    sq_gpu = float(sqnorm.cpu().item())
+    sq_orc = oracle.grad_sqnorm(host["g"], S)
+    assert abs(sq_gpu - sq_orc) <= 1e-5 * sq_orc
+    s_eff_gpu = lohan.lohan_clip_loss_scale(sq_gpu, S, max_norm)
+    assert_scale_within_one_ulp(s_eff_gpu, float(oracle.clip_loss_scale(sq_orc, S, max_norm)))
+    assert (s_eff_gpu == S) == (max_norm >= 100.0)
+    oracle_steps(oracle, host, dict(hy, loss_scale=s_eff_gpu), 1, nthreads=4)
+    worst = assert_state_parity(got, host, what="clipped out-of-place step")
+    assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}, worst
+
+    bad = TwoSets({k: t.clone() for k, t in base.items()})
+    bad.g.view(torch.int16)[n // 2] = 0x7E00
+    before = bad.host(which=0)
+    assert clipped_step(bad) == 1
+    after = bad.host(which=0)
+    for k in ("p", "m", "v", "p16"):
+        assert np.array_equal(after[k].view(np.uint8), before[k].view(np.uint8)), k

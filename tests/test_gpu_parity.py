@@ -9,7 +9,7 @@ import torch
 import paper_2403_06504_amd as lohan
 from paper_2403_06504_amd import synthetic_inputs as synth
 
-from gpu_util import (RTOL_SQNORM, DeviceBlock, assert_parity_given_scales, assert_state_parity,
+from gpu_util import (RTOL_SQNORM, DeviceBlock, assert_scale_within_one_ulp, assert_state_parity,
                       gpu_steps, oracle_steps)
 
 pytestmark = pytest.mark.gpu
@@ -427,9 +427,10 @@ def test_prechecked_flag_is_honoured(oracle):
                                           (257, 1.0, 1e-3)])
 def test_device_side_clipping(oracle, n, S, max_norm):
     """lohan_adam_block_step_clipped resolves the clip coefficient on the device.  It must be
-    bit-identical to the host route through lohan_clip_loss_scale (same formula, same norm), and
-    match the oracle, which clips with its own norm: bit-exact when both effective scales round
-    to the same fp32 value, within the 2-ulp bar otherwise."""
+    bit-identical to the host route through lohan_clip_loss_scale (same formula, same norm).
+    Against the oracle the bar has two halves: the effective loss scale each side derives from
+    its own squared norm agrees to one fp32 ulp, and the oracle stepped with the HIP path's
+    effective scale gives the HIP path's state bit for bit (0 ulp)."""
     wl = small_workload(n, S=S)
     hy = wl.hyper()
     base = synth.make_block(wl, seed=11, device=DEV)
@@ -462,10 +463,10 @@ def test_device_side_clipping(oracle, n, S, max_norm):
         assert s_eff_orc == S                                  # norm below the threshold
     else:
         assert s_eff_orc > S                                   # really clipped
-    old = {k: host[k].copy() for k in ("p", "m", "v")}
-    oracle_steps(oracle, host, dict(hy, loss_scale=s_eff_orc), 1, nthreads=4)
-    assert_parity_given_scales(a, host, old, host["g"], s_eff_gpu, s_eff_orc, hy["lr"],
-                               what="device-side clipping")
+    assert_scale_within_one_ulp(s_eff_gpu, s_eff_orc, what="device-side clipping")
+    oracle_steps(oracle, host, dict(hy, loss_scale=s_eff_gpu), 1, nthreads=4)
+    worst = assert_state_parity(a, host, what="device-side clipping")
+    assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}, worst
 
     # an overflowing block is skipped whatever the norm holds
     skip = DeviceBlock({k: t.clone() for k, t in base.items()})
