@@ -59,6 +59,8 @@ def parse_args():
     ap.add_argument("--reduce-policy", type=int, default=-1,
                     help="loads of the gradient reduction: 0 default, 1 nontemporal, -1 automatic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-producer-fused", dest="producer_fused", action="store_false",
+                    help="skip the variant whose flag/norm come from the gradient producer")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the five-stream bandwidth probe after the timed region")
     ap.add_argument("--placement", choices=["library", "allocator"], default="library",
@@ -230,6 +232,54 @@ def five_stream_ceiling(block, n, torch, lohan):
     return best
 
 
+def producer_fused_step(block, wl, n, flag, sqnorm, ws, args, torch, lohan):
+    """The step when the gradient producer computes the flag and norm in its epilogue
+    (lohan_grad_produce_fp16: fp32 accumulator -> G16): per step one producer launch, which a
+    framework runs anyway to form G16, then the 28 B/element update with LOHAN_FLAG_PRECHECKED.
+    Reported: the update alone (what is left of the step) and producer + update."""
+    dev = block["p"].device
+    acc = torch.empty(n, dtype=torch.float32, device=dev)
+    for lo in range(0, n, 1 << 26):                       # the fp16 gradients, widened
+        hi = min(n, lo + (1 << 26))
+        acc[lo:hi].copy_(block["g"][lo:hi])
+    hy = wl.hyper()
+    steps = min(args.steps, 50)
+
+    def one(t, ev=None):
+        lohan.lohan_grad_produce_fp16(acc, n, 1.0, block["g"], wl.loss_scale, sqnorm, flag, ws)
+        if ev is not None:
+            ev[0].record()
+        lohan.lohan_adam_block_step(block["p"], block["m"], block["v"], block["g"], block["p16"],
+                                    n, hy["lr"], hy["beta1"], hy["beta2"], hy["eps"],
+                                    hy["weight_decay"], t, hy["loss_scale"], flag,
+                                    lohan.LOHAN_FLAG_PRECHECKED, None)
+        if ev is not None:
+            ev[1].record()
+
+    for w in range(3):
+        one(hy["step"] + w)
+    torch.cuda.synchronize()
+    events = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for k in range(steps):
+        events[k][2].record()
+        one(hy["step"] + 3 + k, events[k])
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t0) / steps
+    assert int(flag.cpu().item()) == 0
+    produce = spread([e[2].elapsed_time(e[0]) for e in events])
+    update = spread([e[0].elapsed_time(e[1]) for e in events])
+    del acc
+    return {"note": "flag and norm from the gradient producer's epilogue; the step proper is the "
+                    "prechecked update (28 B/element), its duration taken event to event after "
+                    "the producer, launch gap included",
+            "update_ms": update, "producer_ms": produce,
+            "step_value": n / (update["median_ms"] * 1e-3),
+            "step_frac_of_peak_at_28B": 28 * n / (update["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "producer_gbps_at_6B": 6 * n / (produce["median_ms"] * 1e-3) / 1e9,
+            "producer_plus_update_ms": elapsed * 1e3}
+
+
 def measure_block(wl, args, torch, lohan, synth, with_cpu_baseline, slab=None):
     """One block through the whole hot path, `args.steps` timed steps; returns the JSON object."""
     dev = "cuda:0"
@@ -327,6 +377,9 @@ def measure_block(wl, args, torch, lohan, synth, with_cpu_baseline, slab=None):
                           "achieved_gbps": gbps(REDUCE_BYTES_PER_ELEM * n, reduce_["median_ms"])},
         "cpu_baseline": base,
     }
+    if args.producer_fused:
+        out["producer_fused"] = producer_fused_step(block, wl, n, flag, sqnorm, ws, args, torch,
+                                                    lohan)
     if allocator is not None:
         a = gbps(ADAM_BYTES_PER_ELEM * n, allocator["median_ms"])
         out["allocator_placement"] = {
@@ -716,6 +769,41 @@ def bench_offload(args, torch, lohan, synth):
         finally:
             lohan.lohan_offload_destroy(h)
 
+    def link_probe():
+        """What the host link delivers for one fp32 array of the block (n floats, pinned host
+        memory, plain asynchronous copies): each direction alone and both at once, timed with
+        events on the copying streams."""
+        hp, _, hv = host[0]
+        dev_in = torch.empty(n, dtype=torch.float32, device=dev)
+        dev_out = torch.empty(n, dtype=torch.float32, device=dev)
+        s_in, s_out = torch.cuda.Stream(), torch.cuda.Stream()
+        nbytes = 4 * n
+
+        def timed(do_in, do_out, reps=3):
+            torch.cuda.synchronize()
+            evs = []
+            for do, st, dst, src in ((do_in, s_in, dev_in, hp), (do_out, s_out, hv, dev_out)):
+                if not do:
+                    continue
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                with torch.cuda.stream(st):
+                    e0.record()
+                    for _ in range(reps):
+                        dst.copy_(src, non_blocking=True)
+                    e1.record()
+                evs.append((e0, e1))
+            torch.cuda.synchronize()
+            return [reps * nbytes / (a.elapsed_time(b) * 1e-3) / 1e9 for a, b in evs]
+
+        saved = hv.clone()
+        timed(True, True, 1)
+        out = {"h2d_alone_gbps": timed(True, False)[0], "d2h_alone_gbps": timed(False, True)[0]}
+        both = timed(True, True)
+        out["h2d_duplex_gbps"], out["d2h_duplex_gbps"] = both
+        hv.copy_(saved)
+        return out
+
+    link = link_probe()
     steps = max(1, min(args.steps, 5))
     warm = max(1, min(args.warmup, 2))
     run(lohan.LOHAN_OFFLOAD_OVERLAPPED, warm, hy["step"])
@@ -757,6 +845,9 @@ def bench_offload(args, torch, lohan, synth):
         "zero_copy_value": total / t_zc, "zero_copy_ms_per_step": t_zc * 1e3,
         "zero_copy_pcie_gbps_each_direction": 12 * total / t_zc / 1e9,
         "pcie_gbps_each_direction": 12 * total / t_ovl / 1e9,
+        "link_probe": link,
+        "fraction_of_duplex_link": 12 * total / t_ovl / 1e9 /
+                                   min(link["h2d_duplex_gbps"], link["d2h_duplex_gbps"]),
         "roofline": {"kernel": "H2D/D2H copies around k_adam_block_step", "bound": "pcie",
                      "achieved": 12 * total / t_ovl / 1e9, "peak": 64.0, "unit": "GB/s",
                      "frac": 12 * total / t_ovl / 1e9 / 64.0, "traffic": None,

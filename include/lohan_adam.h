@@ -107,6 +107,30 @@ lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_s
                                  void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 /*
+ * A gradient producer with the block's overflow flag and squared norm computed in its epilogue,
+ * so that the block step needs no separate 2-byte pass over G16: fp32 gradients (as accumulated
+ * over micro-batches by backward, still multiplied by the loss scale) are turned into the G16
+ * tensor of Table II -- the form in which Sec. IV-C's handler receives the gradients of block i --
+ *     grad_fp16_out[i] = binary16, round to nearest even, of (grad_fp32[i] * multiplier)
+ * (one fp32 multiplication, e.g. by 1 / accumulation steps; a product too large for binary16
+ * becomes +-inf, which is how fp16 gradients overflow), and *overflow_flag and *sqnorm are those
+ * lohan_grad_sqnorm would compute from grad_fp16_out (flag bit-identical; norm accumulated in
+ * float64 in a fixed order of its own, same input -> same bits).  The step then runs with
+ * LOHAN_FLAG_PRECHECKED (or lohan_adam_block_step_clipped): 28 bytes per element in place.
+ *   grad_fp32      device, in : n floats
+ *   grad_fp16_out  device, out: n binary16 values (must not overlap grad_fp32)
+ *   multiplier     finite, else LOHAN_ERR_ARG
+ *   loss_scale     finite and > 0 (only scales the norm), else LOHAN_ERR_ARG
+ *   sqnorm         device, out: one double or NULL
+ *   overflow_flag  device, out: one uint32, always written
+ * Moves 6 bytes per element (4 read, 2 written).  Errors as lohan_grad_sqnorm.
+ */
+lohan_status_t lohan_grad_produce_fp16(const float *grad_fp32, uint64_t n, float multiplier,
+                                       void *grad_fp16_out, float loss_scale, double *sqnorm,
+                                       uint32_t *overflow_flag, void *workspace,
+                                       size_t workspace_bytes, hipStream_t stream);
+
+/*
  * lohan_grad_sqnorm for callers that cannot allocate device memory or carry a workspace around:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, results and kernels as lohan_grad_sqnorm, minus the workspace: the partial results

@@ -124,6 +124,22 @@ double lohan_oracle_grad_sqnorm(const uint16_t *grad_fp16, uint64_t n, float los
     return acc;
 }
 
+/* ---- gradient producer ------------------------------------------------------------------- */
+
+/* G16 (Table II) as it leaves backward when the gradients were accumulated in fp32: one fp32
+ * multiplication (e.g. by 1 / accumulation steps), then rounding to binary16 (nearest even,
+ * overflow to infinity, gradual underflow).  The paper only names the tensor; producing it from an
+ * fp32 accumulator by a scaled cast is a reading.  The flag and norm of the result are those of
+ * the functions above applied to the output. */
+void lohan_oracle_grad_produce(const float *grad_fp32, uint64_t n, float multiplier,
+                               uint16_t *grad_fp16_out)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        float scaled = grad_fp32[i] * multiplier;
+        grad_fp16_out[i] = float_to_half_bits_rne(scaled);
+    }
+}
+
 /* ---- the step ------------------------------------------------------------------------------ */
 
 typedef struct {

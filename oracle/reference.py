@@ -26,6 +26,8 @@ def _lib():
         lib.lohan_oracle_grad_overflow_check.restype = ctypes.c_int
         lib.lohan_oracle_grad_sqnorm.argtypes = [u16p, ctypes.c_uint64, ctypes.c_float]
         lib.lohan_oracle_grad_sqnorm.restype = ctypes.c_double
+        lib.lohan_oracle_grad_produce.argtypes = [f32p, ctypes.c_uint64, ctypes.c_float, u16p]
+        lib.lohan_oracle_grad_produce.restype = None
         lib.lohan_oracle_step_scalars.argtypes = [ctypes.c_float] * 4 + [ctypes.c_int64,
                                                                          ctypes.c_float, f32p]
         lib.lohan_oracle_step_scalars.restype = None
@@ -63,6 +65,14 @@ def grad_sqnorm(grad_fp16_bits: np.ndarray, loss_scale: float) -> float:
     """sum_i (g16_i / loss_scale)^2 in float64, index order."""
     g = _ptr(grad_fp16_bits, np.uint16, ctypes.c_uint16)
     return float(_lib().lohan_oracle_grad_sqnorm(g, grad_fp16_bits.size, loss_scale))
+
+
+def grad_produce(grad_fp32: np.ndarray, multiplier: float) -> np.ndarray:
+    """binary16 bit patterns of fl(grad_fp32 * multiplier), round to nearest even."""
+    out = np.empty(grad_fp32.size, dtype=np.uint16)
+    _lib().lohan_oracle_grad_produce(_ptr(grad_fp32, np.float32, ctypes.c_float), grad_fp32.size,
+                                     float(multiplier), _ptr(out, np.uint16, ctypes.c_uint16))
+    return out
 
 
 def step_scalars(lr, beta1, beta2, weight_decay, step, loss_scale) -> dict:

@@ -21,7 +21,8 @@ LOHAN_FLAG_P16_FP16 = 4
 
 EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
-    "lohan_grad_sqnorm", "lohan_grad_sqnorm_static", "lohan_adam_block_step", "lohan_adam_block_step_clipped",
+    "lohan_grad_sqnorm", "lohan_grad_sqnorm_static", "lohan_grad_produce_fp16",
+    "lohan_adam_block_step", "lohan_adam_block_step_clipped",
     "lohan_adam_block_step_out_of_place", "lohan_adam_block_step_out_of_place_clipped",
     "lohan_adam_multi_block_step", "lohan_model_placement", "lohan_tensor_placement",
     "lohan_ring_bytes", "lohan_ring_init", "lohan_ring_adam_block_step",
@@ -110,6 +111,8 @@ def load_library():
     lib.lohan_grad_sqnorm.restype = ctypes.c_int
     lib.lohan_grad_sqnorm_static.argtypes = [vp, u64, f32, vp, vp, vp]
     lib.lohan_grad_sqnorm_static.restype = ctypes.c_int
+    lib.lohan_grad_produce_fp16.argtypes = [vp, u64, f32, vp, f32, vp, vp, vp, sz, vp]
+    lib.lohan_grad_produce_fp16.restype = ctypes.c_int
     lib.lohan_adam_block_step.argtypes = [vp, vp, vp, vp, vp, u64, f32, f32, f32, f32, f32,
                                           ctypes.c_int64, f32, vp, ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_block_step.restype = ctypes.c_int
@@ -285,6 +288,16 @@ def lohan_grad_sqnorm(grad_fp16, n, loss_scale, sqnorm, overflow_flag, workspace
     ws, ws_bytes = _workspace(workspace, workspace_bytes)
     _check(load_library().lohan_grad_sqnorm(
         _addr(grad_fp16, n, _F16, "grad_fp16"), int(n), float(loss_scale),
+        _addr(sqnorm, 1, _F64, "sqnorm"), _addr(overflow_flag, 1, _U32, "overflow_flag"),
+        ws, ws_bytes, _stream(stream)))
+
+
+def lohan_grad_produce_fp16(grad_fp32, n, multiplier, grad_fp16_out, loss_scale, sqnorm,
+                            overflow_flag, workspace, workspace_bytes=None, stream=None):
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_grad_produce_fp16(
+        _addr(grad_fp32, n, _F32, "grad_fp32"), int(n), float(multiplier),
+        _addr(grad_fp16_out, n, _F16, "grad_fp16_out"), float(loss_scale),
         _addr(sqnorm, 1, _F64, "sqnorm"), _addr(overflow_flag, 1, _U32, "overflow_flag"),
         ws, ws_bytes, _stream(stream)))
 

@@ -164,6 +164,28 @@ lohan_status_t lohan_grad_sqnorm(const void *grad_fp16, uint64_t n, float loss_s
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
+lohan_status_t lohan_grad_produce_fp16(const float *grad_fp32, uint64_t n, float multiplier,
+                                       void *grad_fp16_out, float loss_scale, double *sqnorm,
+                                       uint32_t *overflow_flag, void *workspace,
+                                       size_t workspace_bytes, hipStream_t stream)
+{
+    if (overflow_flag == nullptr || (n != 0 && (grad_fp32 == nullptr || grad_fp16_out == nullptr)))
+        return LOHAN_ERR_NULL;
+    if (misaligned(grad_fp32, 16) || misaligned(grad_fp16_out, 16) || misaligned(sqnorm, 8) ||
+        misaligned(overflow_flag, 4))
+        return LOHAN_ERR_ALIGN;
+    if (!std::isfinite(multiplier) || !finite_pos(loss_scale)) return LOHAN_ERR_ARG;
+    lohan_status_t ws = check_workspace(workspace, workspace_bytes);
+    if (ws != LOHAN_OK) return ws;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
+    const double inv = 1.0 / (double)loss_scale;
+    hipError_t e = lohan::launch_grad_produce(grad_fp32, n, multiplier, grad_fp16_out, inv * inv,
+                                              sqnorm, overflow_flag, workspace,
+                                              reduce_workgroups(dev), reduce_streams(n), stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
 namespace {
 
 lohan_status_t validate_step_args(const float *param_fp32, const float *exp_avg,

@@ -111,6 +111,13 @@ hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm,
                               double *sqnorm, uint32_t *flag, void *workspace, uint32_t max_wgs,
                               bool stream_past_caches, hipStream_t stream);
 
+// Gradient producer with the flag / norm in its epilogue: out[i] = binary16(grad_fp32[i] *
+// multiplier); sqnorm (may be NULL) and flag describe the values written.
+hipError_t launch_grad_produce(const float *grad_fp32, uint64_t n, float multiplier,
+                               void *grad_fp16_out, double inv2, double *sqnorm, uint32_t *flag,
+                               void *workspace, uint32_t max_wgs, bool stream_past_caches,
+                               hipStream_t stream);
+
 // Launch shape of the Adam kernel.
 struct AdamLaunch {
     int variant;         // see adam_variant_valid

@@ -41,6 +41,34 @@ __device__ __forceinline__ void st(T *ptr, T val)
     else *ptr = val;
 }
 
+// 16-bit output formats.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// fp32 -> bfloat16, round to nearest even; gfx950 converts a pair in one instruction
+// (v_cvt_pk_bf16_f32).  lo goes to bits [15:0], hi to bits [31:16].  A NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi)
+{
+    f32x2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
+
+// fp32 -> IEEE binary16, round to nearest even (v_cvt_f16_f32 under the default rounding mode),
+// overflow to infinity, gradual underflow.  Same packing as bf16_pack_rne.
+__device__ __forceinline__ uint32_t half_pack_rne(float lo, float hi)
+{
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    f32x2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
+}
+
+template <bool HALF_OUT>
+__device__ __forceinline__ uint32_t pack16(float lo, float hi)
+{
+    if constexpr (HALF_OUT) return half_pack_rne(lo, hi);
+    else return bf16_pack_rne(lo, hi);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Gradient reduction: overflow flag (integer test on the raw fp16 bits) and, optionally, the sum
 // of squares, in ONE launch.  Every workgroup publishes one partial and takes a ticket from a
@@ -157,52 +185,20 @@ __device__ __forceinline__ void workgroup_combine(uint32_t tid, double &acc, uin
     }
 }
 
-// Workgroup `wg` of `nwg` reduces its interleaved share of g[0, n), publishes partial
-// `slot_base + wg`, and -- if it is the last of the nwg to do so -- combines the nwg partials
-// into sqnorm_out / flag_out (either may be NULL).  NT: stream the gradients past the caches
-// (blocks far larger than the memory-side cache) or leave them cached for the update that
-// follows (blocks that fit it).  inv2 = (1/loss_scale)^2 in float64 turns the raw sum of squares
-// into the squared norm of the unscaled gradients.
-template <bool WITH_NORM, int UNROLL, bool NT>
-__device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g, uint64_t n,
-                                                 uint32_t wg, uint32_t nwg, uint32_t slot_base,
-                                                 double *partial_sum, uint32_t *partial_flag,
-                                                 uint32_t *counter, double inv2,
-                                                 double *__restrict__ sqnorm_out,
-                                                 uint32_t *__restrict__ flag_out)
+// Tail of every reducing kernel: combine the workgroup's lanes, publish the workgroup's partial
+// as slot `slot_base + wg`, take a ticket, and -- in the workgroup that draws the last of the nwg
+// tickets -- combine all partials into sqnorm_out / flag_out (either may be NULL) and put the
+// counter back to zero.  All threads of the workgroup must call it.
+template <bool WITH_NORM>
+__device__ __forceinline__ void reduce_publish_and_finish(uint32_t tid, double acc, uint32_t ovf,
+                                                          uint32_t wg, uint32_t nwg,
+                                                          uint32_t slot_base, double *partial_sum,
+                                                          uint32_t *partial_flag,
+                                                          uint32_t *counter, double inv2,
+                                                          double *__restrict__ sqnorm_out,
+                                                          uint32_t *__restrict__ flag_out)
 {
     constexpr int kThreads = kReduceThreads;
-    constexpr uint64_t kVec = 8;                               // halves per 128-bit load
-    constexpr uint64_t kTile = (uint64_t)kThreads * kVec * UNROLL;
-    const uint32_t tid = threadIdx.x;
-    const uint64_t ntiles = n / kTile;
-
-    uint32_t ovf = 0;
-    double acc = 0.0;
-
-    for (uint64_t tile = wg; tile < ntiles; tile += nwg) {
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(g + tile * kTile) + tid;
-        u32x4 q[UNROLL];
-#pragma unroll
-        for (int j = 0; j < UNROLL; ++j) q[j] = ld<NT>(src + j * kThreads);
-#pragma unroll
-        for (int j = 0; j < UNROLL; ++j) reduce_vec<WITH_NORM>(q[j], ovf, acc);
-    }
-
-    // Ragged end: whole 8-element vectors first, then up to 7 single elements.
-    const uint64_t rem_start = ntiles * kTile;
-    const uint64_t rem_vecs = (n - rem_start) / kVec;
-    for (uint64_t i = (uint64_t)wg * kThreads + tid; i < rem_vecs; i += (uint64_t)nwg * kThreads) {
-        u32x4 q = *(reinterpret_cast<const u32x4 *>(g + rem_start) + i);
-        reduce_vec<WITH_NORM>(q, ovf, acc);
-    }
-    const uint64_t tail_start = rem_start + rem_vecs * kVec;
-    if (wg == 0 && tail_start + tid < n) {
-        uint32_t h = g[tail_start + tid];
-        ovf = overflow_bits(h, ovf);
-        if constexpr (WITH_NORM) acc += (double)square_pair(h, 0.0f);
-    }
-
     workgroup_combine<WITH_NORM>(tid, acc, ovf);
 
     // Publish this workgroup's partial, then take a ticket.  The ticket's increment consumes what
@@ -260,6 +256,56 @@ __device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g,
     }
 }
 
+// Workgroup `wg` of `nwg` reduces its interleaved share of g[0, n), publishes partial
+// `slot_base + wg`, and -- if it is the last of the nwg to do so -- combines the nwg partials
+// into sqnorm_out / flag_out (either may be NULL).  NT: stream the gradients past the caches
+// (blocks far larger than the memory-side cache) or leave them cached for the update that
+// follows (blocks that fit it).  inv2 = (1/loss_scale)^2 in float64 turns the raw sum of squares
+// into the squared norm of the unscaled gradients.
+template <bool WITH_NORM, int UNROLL, bool NT>
+__device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g, uint64_t n,
+                                                 uint32_t wg, uint32_t nwg, uint32_t slot_base,
+                                                 double *partial_sum, uint32_t *partial_flag,
+                                                 uint32_t *counter, double inv2,
+                                                 double *__restrict__ sqnorm_out,
+                                                 uint32_t *__restrict__ flag_out)
+{
+    constexpr int kThreads = kReduceThreads;
+    constexpr uint64_t kVec = 8;                               // halves per 128-bit load
+    constexpr uint64_t kTile = (uint64_t)kThreads * kVec * UNROLL;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t ntiles = n / kTile;
+
+    uint32_t ovf = 0;
+    double acc = 0.0;
+
+    for (uint64_t tile = wg; tile < ntiles; tile += nwg) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(g + tile * kTile) + tid;
+        u32x4 q[UNROLL];
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) q[j] = ld<NT>(src + j * kThreads);
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) reduce_vec<WITH_NORM>(q[j], ovf, acc);
+    }
+
+    // Ragged end: whole 8-element vectors first, then up to 7 single elements.
+    const uint64_t rem_start = ntiles * kTile;
+    const uint64_t rem_vecs = (n - rem_start) / kVec;
+    for (uint64_t i = (uint64_t)wg * kThreads + tid; i < rem_vecs; i += (uint64_t)nwg * kThreads) {
+        u32x4 q = *(reinterpret_cast<const u32x4 *>(g + rem_start) + i);
+        reduce_vec<WITH_NORM>(q, ovf, acc);
+    }
+    const uint64_t tail_start = rem_start + rem_vecs * kVec;
+    if (wg == 0 && tail_start + tid < n) {
+        uint32_t h = g[tail_start + tid];
+        ovf = overflow_bits(h, ovf);
+        if constexpr (WITH_NORM) acc += (double)square_pair(h, 0.0f);
+    }
+
+    reduce_publish_and_finish<WITH_NORM>(tid, acc, ovf, wg, nwg, slot_base, partial_sum,
+                                         partial_flag, counter, inv2, sqnorm_out, flag_out);
+}
+
 template <bool WITH_NORM, int UNROLL, bool NT>
 __global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *__restrict__ g,
                                                                 uint64_t n, double *partial_sum,
@@ -287,6 +333,66 @@ __global__ __launch_bounds__(kReduceThreads) void k_multi_grad_reduce(
                                             flags != nullptr ? flags + b : nullptr);
 }
 
+// A gradient producer with the block's flag and norm computed in its epilogue: fp32 gradients
+// (accumulated over micro-batches, still multiplied by the loss scale) are scaled by `mul`,
+// rounded to binary16 -- the G16 tensor that the block step consumes -- and the overflow flag and
+// squared norm of exactly the values written are reduced on the way, so that the step needs no
+// separate 2 B/element pass over G16.  A value too large for binary16 becomes +-inf here, which
+// is how fp16 gradients overflow in the first place.  Persistent over interleaved tiles of
+// 64 lanes x 4 elements x UNROLL rows; the finish is the reduction's.
+template <bool WITH_NORM, int UNROLL, bool NT>
+__global__ __launch_bounds__(kReduceThreads) void k_grad_produce(
+    const float *__restrict__ src, uint64_t n, float mul, uint16_t *__restrict__ out,
+    double *partial_sum, uint32_t *partial_flag, uint32_t *counter, double inv2,
+    double *__restrict__ sqnorm_out, uint32_t *__restrict__ flag_out)
+{
+    constexpr uint64_t kVec = 4;
+    constexpr uint64_t kRow = (uint64_t)kReduceThreads * kVec;
+    constexpr uint64_t kTile = kRow * UNROLL;
+    const uint32_t tid = threadIdx.x, wg = blockIdx.x, nwg = gridDim.x;
+    const uint64_t ntiles = n / kTile;
+    uint32_t ovf = 0;
+    double acc = 0.0;
+
+    auto emit = [&](f32x4 x) {
+        const uint32_t lo = half_pack_rne(x[0] * mul, x[1] * mul);
+        const uint32_t hi = half_pack_rne(x[2] * mul, x[3] * mul);
+        ovf = overflow_bits(lo, ovf);
+        ovf = overflow_bits(hi, ovf);
+        if constexpr (WITH_NORM) acc += (double)square_pair(hi, square_pair(lo, 0.0f));
+        return u32x2{lo, hi};
+    };
+
+    for (uint64_t tile = wg; tile < ntiles; tile += nwg) {
+        const uint64_t base = tile * kTile + (uint64_t)tid * kVec;
+        f32x4 x[UNROLL];
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j)
+            x[j] = ld<NT>(reinterpret_cast<const f32x4 *>(src + base + j * kRow));
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j)
+            st<NT>(reinterpret_cast<u32x2 *>(out + base + j * kRow), emit(x[j]));
+    }
+    // Ragged end: whole 4-element vectors spread over the grid, then up to 3 single elements.
+    const uint64_t rem_start = ntiles * kTile;
+    const uint64_t rem_vecs = (n - rem_start) / kVec;
+    for (uint64_t i = (uint64_t)wg * kReduceThreads + tid; i < rem_vecs;
+         i += (uint64_t)nwg * kReduceThreads) {
+        const uint64_t off = rem_start + i * kVec;
+        const f32x4 x = *reinterpret_cast<const f32x4 *>(src + off);
+        *reinterpret_cast<u32x2 *>(out + off) = emit(x);
+    }
+    const uint64_t tail = rem_start + rem_vecs * kVec + tid;
+    if (wg == 0 && tail < n) {
+        const uint32_t h = half_pack_rne(src[tail] * mul, 0.0f) & 0xFFFFu;
+        out[tail] = (uint16_t)h;
+        ovf = overflow_bits(h, ovf);
+        if constexpr (WITH_NORM) acc += (double)square_pair(h, 0.0f);
+    }
+    reduce_publish_and_finish<WITH_NORM>(tid, acc, ovf, wg, nwg, 0u, partial_sum, partial_flag,
+                                         counter, inv2, sqnorm_out, flag_out);
+}
+
 // Ticket counters start at zero; afterwards every reduction leaves them at zero.
 __global__ void k_workspace_init(uint32_t *counters, uint32_t count)
 {
@@ -306,33 +412,6 @@ __global__ void k_grad_empty(double *sqnorm, uint32_t *flag)
 // ------------------------------------------------------------------------------------------------
 // The 28 B/element stream.
 // ------------------------------------------------------------------------------------------------
-
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-// fp32 -> bfloat16, round to nearest even; gfx950 converts a pair in one instruction
-// (v_cvt_pk_bf16_f32).  lo goes to bits [15:0], hi to bits [31:16].  A NaN stays a quiet NaN.
-__device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi)
-{
-    f32x2 x = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
-}
-
-// fp32 -> IEEE binary16, round to nearest even (v_cvt_f16_f32 under the default rounding mode),
-// overflow to infinity, gradual underflow.  Same packing as bf16_pack_rne.
-__device__ __forceinline__ uint32_t half_pack_rne(float lo, float hi)
-{
-    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-    f32x2 x = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
-}
-
-template <bool HALF_OUT>
-__device__ __forceinline__ uint32_t pack16(float lo, float hi)
-{
-    if constexpr (HALF_OUT) return half_pack_rne(lo, hi);
-    else return bf16_pack_rne(lo, hi);
-}
 
 template <bool L2>
 __device__ __forceinline__ void adam_elem(float &p, float &m, float &v, float g_scaled,
@@ -759,6 +838,46 @@ hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm,
     else
         launch_reduce_policy<false>(stream_past_caches, grid, stream, g, n, ws, inv2, sqnorm,
                                     flag);
+    return hipGetLastError();
+}
+
+template <bool WITH_NORM>
+static void launch_produce_policy(bool stream_past_caches, uint32_t grid, hipStream_t stream,
+                                  const float *src, uint64_t n, float mul, uint16_t *out,
+                                  const WorkspaceView &ws, double inv2, double *sqnorm,
+                                  uint32_t *flag)
+{
+    constexpr int kUnroll = kReduceUnroll;
+    if (stream_past_caches)
+        hipLaunchKernelGGL((k_grad_produce<WITH_NORM, kUnroll, true>), dim3(grid),
+                           dim3(kReduceThreads), 0, stream, src, n, mul, out, ws.partial_sum,
+                           ws.partial_flag, ws.counters, inv2, sqnorm, flag);
+    else
+        hipLaunchKernelGGL((k_grad_produce<WITH_NORM, kUnroll, false>), dim3(grid),
+                           dim3(kReduceThreads), 0, stream, src, n, mul, out, ws.partial_sum,
+                           ws.partial_flag, ws.counters, inv2, sqnorm, flag);
+}
+
+hipError_t launch_grad_produce(const float *grad_fp32, uint64_t n, float multiplier,
+                               void *grad_fp16_out, double inv2, double *sqnorm, uint32_t *flag,
+                               void *workspace, uint32_t max_wgs, bool stream_past_caches,
+                               hipStream_t stream)
+{
+    if (n == 0) {
+        hipLaunchKernelGGL(k_grad_empty, dim3(1), dim3(64), 0, stream, sqnorm, flag);
+        return hipGetLastError();
+    }
+    if (max_wgs > kMaxPartials) max_wgs = kMaxPartials;
+    const uint32_t grid =
+        reduce_grid(n, (uint64_t)kReduceThreads * 4 * kReduceUnroll, max_wgs);
+    const WorkspaceView ws = workspace_view(workspace);
+    uint16_t *out = reinterpret_cast<uint16_t *>(grad_fp16_out);
+    if (sqnorm != nullptr)
+        launch_produce_policy<true>(stream_past_caches, grid, stream, grad_fp32, n, multiplier,
+                                    out, ws, inv2, sqnorm, flag);
+    else
+        launch_produce_policy<false>(stream_past_caches, grid, stream, grad_fp32, n, multiplier,
+                                     out, ws, inv2, sqnorm, flag);
     return hipGetLastError();
 }
 

@@ -113,6 +113,24 @@ def test_reduction_validation_returns_before_any_launch(lib):
     assert lib.lohan_grad_sqnorm(A, 8, f(1.0), A * 4, None, A * 2, 8, None) == 4
 
 
+def test_grad_produce_validation_returns_before_any_launch(lib):
+    ws_bytes = lib.lohan_workspace_bytes()
+    f = ctypes.c_float
+
+    def status(src=A, out=A * 2, mul=1.0, S=1024.0, sq=A * 3, flag=A * 4, ws=A * 5, wsb=ws_bytes):
+        return lib.lohan_grad_produce_fp16(src, 64, f(mul), out, f(S), sq, flag, ws, wsb, None)
+
+    assert status(src=None) == 1 and status(out=None) == 1 and status(flag=None) == 1
+    assert status(ws=None) == 1
+    assert status(src=A + 4) == 2 and status(out=A * 2 + 8) == 2 and status(sq=A * 3 + 4) == 2
+    assert status(flag=A * 4 + 2) == 2 and status(ws=A * 5 + 8) == 2
+    for bad in (math.inf, math.nan):
+        assert status(mul=bad) == 3
+    for bad in (0.0, -1.0, math.inf, math.nan):
+        assert status(S=bad) == 3
+    assert status(wsb=ws_bytes - 1) == 4
+
+
 def test_static_sqnorm_validation_returns_before_any_launch(lib):
     f = ctypes.c_float
     assert lib.lohan_grad_sqnorm_static(A, 8, f(1.0), None, A * 3, None) == 1

@@ -54,6 +54,12 @@ MUTANTS = [
      "if (0) h += 1u;"),
     ("fp16 copy overflow threshold wrong", "if (a >= 0x47800000u) return (uint16_t)(sign | 0x7C00u);",
      "if (a >= 0x47000000u) return (uint16_t)(sign | 0x7C00u);"),
+    ("producer forgets the multiplier", "float scaled = grad_fp32[i] * multiplier;",
+     "float scaled = grad_fp32[i];"),
+    ("producer divides instead of multiplying", "float scaled = grad_fp32[i] * multiplier;",
+     "float scaled = grad_fp32[i] / multiplier;"),
+    ("producer flushes subnormal results", "float scaled = grad_fp32[i] * multiplier;",
+     "float scaled = grad_fp32[i] * multiplier; if (fabsf(scaled) < 6.1035156e-05f) scaled = 0.0f;"),
 ]
 
 # The pins that take the `oracle` fixture, with the parameter sets they are collected with.
@@ -76,6 +82,7 @@ PIN_CALLS = [
     (pins.test_fp16_decode_all_patterns, [dict()]),
     (pins.test_bf16_encode_against_library, [dict()]),
     (pins.test_fp16_encode_against_library, [dict()]),
+    (pins.test_grad_produce_against_library, [dict()]),
     (pins.test_fp16_copy_option_only_changes_the_copy, [dict()]),
     (pins.test_overflow_flag_brute_force_all_patterns, [dict()]),
     (pins.test_overflow_skips_and_leaves_state_untouched,

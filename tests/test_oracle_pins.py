@@ -358,6 +358,33 @@ def test_fp16_encode_against_library(oracle):
     assert (oracle.float_to_half_bits(np.float32(np.nan)) & 0x7FFF) > 0x7C00
 
 
+def test_grad_produce_against_library(oracle):
+    """The gradient producer (fp32 accumulator -> G16): one fp32 multiplication, then the
+    binary16 rounding, against numpy doing the same two operations; the flag and norm of the
+    produced tensor are the pinned functions applied to it.  Includes products that overflow
+    binary16 (they must become infinities and raise the flag), ties, subnormal results, and a
+    multiplier that is not a power of two (so that the product's own rounding matters)."""
+    rng = np.random.default_rng(17)
+    halves = np.arange(1, 0x7C00, 3, dtype=np.uint32).astype(np.uint16).view(np.float16).astype(np.float32)
+    ties = (halves.view(np.uint32) | 0x1000).view(np.float32)
+    for mul in (1.0, 0.125, 1.0 / 3.0, 0.7, 3.0):
+        m32 = np.float32(mul)
+        x = np.concatenate([(rng.standard_normal(50000) * 65.5).astype(np.float32),
+                            (rng.standard_normal(5000) * 3e-7).astype(np.float32),
+                            ties / m32, -ties / m32, halves / m32,
+                            np.array([0.0, -0.0, 65504.0, 65520.0, -65520.0, 70000.0, 2.0 ** -25,
+                                      1e30, -1e30], np.float32) / m32])
+        with np.errstate(over="ignore"):
+            want = (x * m32).astype(np.float16).view(np.uint16)
+        got = oracle.grad_produce(x, mul)
+        assert np.array_equal(got, want), mul
+        assert oracle.grad_overflow_check(got) == int(np.any(~np.isfinite(want.view(np.float16))))
+    clean = (rng.standard_normal(4096) * 65.5).astype(np.float32)
+    assert oracle.grad_overflow_check(oracle.grad_produce(clean, 0.5)) == 0
+    assert np.array_equal(oracle.grad_produce(np.array([np.nan], np.float32), 1.0) & 0x7C00,
+                          np.array([0x7C00], np.uint16))
+
+
 def test_fp16_copy_option_only_changes_the_copy(oracle):
     n = 5000
     p, m, v, g = rand_block(n, 41)
