@@ -437,7 +437,7 @@ def bench_ceiling(args, torch, lohan, synth):
     rows = {}
     reps = max(5, min(args.steps, 20))
     for name, pattern, width in patterns:
-        sweep = (0,) if pattern == lohan.LOHAN_PROBE_MEMCPY else (0, 8, 11, 16, 24)
+        sweep = (0,) if pattern == lohan.LOHAN_PROBE_MEMCPY else (0, 2, 3, 4, 6, 8, 11, 16, 24)
         per = {}
         for waves in sweep:
             ms = probe_ms(pattern, views, n, waves, torch, lohan, reps)
@@ -752,6 +752,8 @@ def bench_offload(args, torch, lohan, synth):
     slots = 3
     slab = torch.empty(lohan.lohan_offload_slab_bytes(n, slots), dtype=torch.uint8, device=dev)
 
+    stage_times = {}
+
     def run(mode, passes, first_step):
         h = lohan.lohan_offload_create(slab, n, slots, mode)
         try:
@@ -765,7 +767,10 @@ def bench_offload(args, torch, lohan, synth):
                                                hy["eps"], hy["weight_decay"], first_step + k,
                                                hy["loss_scale"], 0.0, 0)
             lohan.lohan_offload_drain(h)
-            return (time.perf_counter() - t0) / passes
+            elapsed = (time.perf_counter() - t0) / passes
+            stage_times[mode] = [lohan.lohan_tuning_offload_slot_times(h, s_)
+                                 for s_ in range(min(slots, nblocks))]
+            return elapsed
         finally:
             lohan.lohan_offload_destroy(h)
 
@@ -846,6 +851,17 @@ def bench_offload(args, torch, lohan, synth):
         "zero_copy_pcie_gbps_each_direction": 12 * total / t_zc / 1e9,
         "pcie_gbps_each_direction": 12 * total / t_ovl / 1e9,
         "link_probe": link,
+        "stage_ms_last_blocks": {
+            "note": "per staging slot, the block that used it last: host-to-device copies, "
+                    "flag/norm + step, device-to-host copies, event to event on their streams",
+            "overlapped": [dict(zip(("h2d", "step", "d2h"), t))
+                           for t in stage_times[lohan.LOHAN_OFFLOAD_OVERLAPPED]],
+            "serialized": [dict(zip(("h2d", "step", "d2h"), t))
+                           for t in stage_times[lohan.LOHAN_OFFLOAD_SERIALIZED]],
+            "gbps_of_12B_per_element": {
+                k: [12 * n / (t[i] * 1e-3) / 1e9
+                    for t in stage_times[lohan.LOHAN_OFFLOAD_OVERLAPPED]]
+                for i, k in ((0, "h2d"), (2, "d2h"))}},
         "fraction_of_duplex_link": 12 * total / t_ovl / 1e9 /
                                    min(link["h2d_duplex_gbps"], link["d2h_duplex_gbps"]),
         "roofline": {"kernel": "H2D/D2H copies around k_adam_block_step", "bound": "pcie",

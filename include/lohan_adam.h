@@ -455,7 +455,7 @@ float lohan_clip_loss_scale(double sqnorm, float loss_scale, float max_norm);
  * (PCIe is full duplex); LOHAN_OFFLOAD_SERIALIZED reproduces the naive schedule for comparison.
  * A skipped (overflowing) block is copied back bit-identical.
  *
- * The handle owns three streams and 4 events per slot, nothing else: the staging memory
+ * The handle owns three streams and 7 events per slot, nothing else: the staging memory
  * (`device_slab`, lohan_offload_slab_bytes() bytes, 256-byte aligned) is the caller's and must
  * outlive the handle.  A handle is bound to the device that was current at creation and is not
  * thread-safe.  Host state arrays must be pinned (hipHostMalloc or equivalent), otherwise the

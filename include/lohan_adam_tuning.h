@@ -45,9 +45,10 @@ lohan_status_t lohan_tuning_device_info(int *compute_units, size_t *lds_bytes_pe
 
 /*
  * Bandwidth probes: the access patterns of the step with trivial arithmetic, to measure the
- * ceiling the machine sustains for each (one tile per workgroup, 64-lane workgroups, 128-bit
- * accesses per lane, nontemporal loads and write-through streaming stores, the launch shape of
- * the update kernel).  Each call enqueues ONE kernel on `stream` (LOHAN_PROBE_MEMCPY: one
+ * ceiling the machine sustains for each (64-lane workgroups handed out in address order, 128-bit
+ * accesses per lane, nontemporal loads and write-through streaming stores; the five-stream probe
+ * has the update kernel's exact launch shape, one 256-element tile per workgroup, the
+ * single-stream probes take eight such rows per workgroup).  Each call enqueues ONE kernel on `stream` (LOHAN_PROBE_MEMCPY: one
  * hipMemcpyAsync device-to-device) and returns.
  *   LOHAN_PROBE_READ         reads n floats from a                       4 n bytes
  *   LOHAN_PROBE_WRITE        writes n floats to b                        4 n bytes
@@ -57,8 +58,8 @@ lohan_status_t lohan_tuning_device_info(int *compute_units, size_t *lds_bytes_pe
  *                            few multiply-adds in between                28 n bytes
  *   LOHAN_PROBE_MEMCPY       hipMemcpyAsync(b, a, 4 n, DeviceToDevice)   8 n bytes
  * a, b, c, g16, h16: device, 16-byte aligned, n elements each, not overlapping; pointers a
- * pattern does not use may be NULL.  Only whole tiles of 256 elements are touched (n is rounded
- * down).  waves_per_cu: occupancy throttle as above (0 = none).  The contents of written arrays
+ * pattern does not use may be NULL.  Only whole tiles are touched: n is rounded down to a
+ * multiple of 256 elements (five-stream, memcpy) or of 2048 elements (read, write, copy).  waves_per_cu: occupancy throttle as above (0 = none).  The contents of written arrays
  * are unspecified afterwards.  Errors: LOHAN_ERR_NULL / _ALIGN / _ARG, LOHAN_ERR_HIP.
  */
 enum {
@@ -78,6 +79,16 @@ lohan_status_t lohan_tuning_probe(int pattern, float *a, float *b, float *c, con
  * the handle is poisoned exactly as after a real runtime failure.  LOHAN_ERR_NULL / _ARG.
  */
 lohan_status_t lohan_tuning_offload_inject_failure(lohan_offload_t *handle, int after_calls);
+
+/*
+ * Durations of the three stages of the block that last went through staging slot `slot` of an
+ * offload pipeline: its host-to-device copies, its flag/norm pass + step, its device-to-host
+ * copies, each from event to event on the stream that ran it (milliseconds; outputs may be
+ * NULL).  Waits for that block's copy-out to finish.  LOHAN_ERR_ARG for a slot that has not been
+ * used, LOHAN_ERR_HIP if the events cannot be read.
+ */
+lohan_status_t lohan_tuning_offload_slot_times(lohan_offload_t *handle, int slot, float *h2d_ms,
+                                               float *step_ms, float *d2h_ms);
 
 #ifdef __cplusplus
 }

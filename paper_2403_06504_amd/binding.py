@@ -30,6 +30,7 @@ EXPORTS = (
     "lohan_clip_loss_scale", "lohan_workspace_init",
     "lohan_tuning_set_launch_config", "lohan_tuning_get_launch_config",
     "lohan_tuning_device_info", "lohan_tuning_probe", "lohan_tuning_offload_inject_failure",
+    "lohan_tuning_offload_slot_times",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
     "lohan_offload_wait_last_step", "lohan_offload_drain", "lohan_offload_destroy",
     "lohan_swap_iter_time", "lohan_swap_recompute_flops", "lohan_plan_activation_swapping",
@@ -169,6 +170,9 @@ def load_library():
     lib.lohan_tuning_probe.restype = ctypes.c_int
     lib.lohan_tuning_offload_inject_failure.argtypes = [vp, ctypes.c_int]
     lib.lohan_tuning_offload_inject_failure.restype = ctypes.c_int
+    fp = ctypes.POINTER(ctypes.c_float)
+    lib.lohan_tuning_offload_slot_times.argtypes = [vp, ctypes.c_int, fp, fp, fp]
+    lib.lohan_tuning_offload_slot_times.restype = ctypes.c_int
     lib.lohan_offload_slab_bytes.argtypes = [u64, ctypes.c_int]
     lib.lohan_offload_slab_bytes.restype = sz
     lib.lohan_offload_create.argtypes = [ctypes.POINTER(vp), vp, sz, u64, ctypes.c_int,
@@ -568,6 +572,14 @@ def lohan_offload_destroy(handle):
 
 def lohan_tuning_offload_inject_failure(handle, after_calls):
     _check(load_library().lohan_tuning_offload_inject_failure(handle, int(after_calls)))
+
+
+def lohan_tuning_offload_slot_times(handle, slot):
+    """(h2d_ms, step_ms, d2h_ms) of the block that last used staging slot `slot`."""
+    a, b, c = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
+    _check(load_library().lohan_tuning_offload_slot_times(handle, int(slot), ctypes.byref(a),
+                                                          ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
 
 
 def _swap_hw(hw: dict) -> LohanSwapHw:

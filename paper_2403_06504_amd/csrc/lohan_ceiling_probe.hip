@@ -2,9 +2,10 @@
 // step of Sec. IV-C with trivial arithmetic, to measure what the machine sustains for pure
 // reads, pure writes, a copy, and the step's own five-stream 14-bytes-in / 14-bytes-out pattern
 // (Table II's tensor widths: G16 2, P32 4, OS32 8 in; P32 4, OS32 8, P16 2 out).  They use the
-// launch design of the update kernel -- one 256-element tile per 64-lane workgroup, 128-bit
-// accesses per lane, nontemporal loads, write-through streaming stores, occupancy bounded by an
-// unused dynamic LDS request -- so that the only difference to k_adam_block_step is the arithmetic.
+// launch design of the update kernel -- 64-lane workgroups in address order, 128-bit accesses per
+// lane, nontemporal loads, write-through streaming stores, occupancy bounded by an unused dynamic
+// LDS request -- and the five-stream probe its exact tile (256 elements per workgroup), so that
+// the only difference to k_adam_block_step is the arithmetic.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -32,27 +33,44 @@ __device__ __forceinline__ void st_through(u32x2 *ptr, u32x2 val)
                  : "memory");
 }
 
+// The single-stream probes give every workgroup kRows rows of 64 x 128 bits (with one row per
+// workgroup they would measure the rate at which workgroups can be dispatched, about 4.7 per
+// nanosecond, rather than the memory); the host launches whole groups of kRows rows only.
+constexpr int kRows = 8;
+
 __global__ __launch_bounds__(kLanes) void k_probe_read(const float *a, float *sink)
 {
-    const uint64_t off = (uint64_t)blockIdx.x * kTile + (uint64_t)threadIdx.x * 4;
-    const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a + off));
-    // Never true for finite data, but keeps the load alive.
-    if (x.x + x.y + x.z + x.w == 1.2345678e30f) *sink = x.x;
+    const float *base = a + (uint64_t)blockIdx.x * kRows * kTile + (uint64_t)threadIdx.x * 4;
+    f32x4 x[kRows];
+#pragma unroll
+    for (int j = 0; j < kRows; ++j)
+        x[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(base + j * kTile));
+    f32x4 acc = x[0];
+#pragma unroll
+    for (int j = 1; j < kRows; ++j) acc += x[j];
+    // Never true for finite data, but keeps the loads alive.
+    if (acc.x + acc.y + acc.z + acc.w == 1.2345678e30f) *sink = acc.x;
 }
 
 __global__ __launch_bounds__(kLanes) void k_probe_write(float *__restrict__ b)
 {
-    const uint64_t off = (uint64_t)blockIdx.x * kTile + (uint64_t)threadIdx.x * 4;
+    float *base = b + (uint64_t)blockIdx.x * kRows * kTile + (uint64_t)threadIdx.x * 4;
     const f32x4 x = {1.0f, 2.0f, 3.0f, (float)threadIdx.x};
-    st_through(reinterpret_cast<f32x4 *>(b + off), x);
+#pragma unroll
+    for (int j = 0; j < kRows; ++j) st_through(reinterpret_cast<f32x4 *>(base + j * kTile), x);
 }
 
 __global__ __launch_bounds__(kLanes) void k_probe_copy(const float *__restrict__ a,
                                                        float *__restrict__ b)
 {
-    const uint64_t off = (uint64_t)blockIdx.x * kTile + (uint64_t)threadIdx.x * 4;
-    const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a + off));
-    st_through(reinterpret_cast<f32x4 *>(b + off), x);
+    const uint64_t off = (uint64_t)blockIdx.x * kRows * kTile + (uint64_t)threadIdx.x * 4;
+    f32x4 x[kRows];
+#pragma unroll
+    for (int j = 0; j < kRows; ++j)
+        x[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a + off + j * kTile));
+#pragma unroll
+    for (int j = 0; j < kRows; ++j)
+        st_through(reinterpret_cast<f32x4 *>(b + off + j * kTile), x[j]);
 }
 
 __global__ __launch_bounds__(kLanes) void k_probe_five_stream(float *__restrict__ a,
@@ -114,6 +132,8 @@ extern "C" lohan_status_t lohan_tuning_probe(int pattern, float *a, float *b, fl
     size_t lds = 0;
     if (waves_per_cu > 0 && waves_per_cu < 32) lds = lds_per_cu / (size_t)waves_per_cu / 256 * 256;
     const dim3 grid((uint32_t)tiles), wg(kLanes);
+    const dim3 grid_rows((uint32_t)(tiles / kRows));        // whole groups of rows only
+    if (pattern != LOHAN_PROBE_FIVE_STREAM && grid_rows.x == 0) return LOHAN_OK;
     const void *kernel = pattern == LOHAN_PROBE_READ    ? reinterpret_cast<const void *>(k_probe_read)
                          : pattern == LOHAN_PROBE_WRITE ? reinterpret_cast<const void *>(k_probe_write)
                          : pattern == LOHAN_PROBE_COPY  ? reinterpret_cast<const void *>(k_probe_copy)
@@ -126,13 +146,13 @@ extern "C" lohan_status_t lohan_tuning_probe(int pattern, float *a, float *b, fl
     case LOHAN_PROBE_READ:
         // The sink is written only if four loaded values sum to one particular number; it is a
         // itself, so the pattern needs no second array.
-        hipLaunchKernelGGL(k_probe_read, grid, wg, lds, stream, a, a);
+        hipLaunchKernelGGL(k_probe_read, grid_rows, wg, lds, stream, a, a);
         break;
     case LOHAN_PROBE_WRITE:
-        hipLaunchKernelGGL(k_probe_write, grid, wg, lds, stream, b);
+        hipLaunchKernelGGL(k_probe_write, grid_rows, wg, lds, stream, b);
         break;
     case LOHAN_PROBE_COPY:
-        hipLaunchKernelGGL(k_probe_copy, grid, wg, lds, stream, a, b);
+        hipLaunchKernelGGL(k_probe_copy, grid_rows, wg, lds, stream, a, b);
         break;
     default:
         hipLaunchKernelGGL(k_probe_five_stream, grid, wg, lds, stream, a, b, c,

@@ -33,6 +33,9 @@ struct lohan_offload {
     size_t array_bytes = 0;      // one fp32 array of max_elems, padded to 256 B
     hipStream_t s_in = nullptr, s_compute = nullptr, s_out = nullptr;
     std::vector<hipEvent_t> ev_grad, ev_h2d, ev_step, ev_d2h;
+    // Begin markers of the three stages of a slot's latest occupant, for the bench-only timing
+    // query (lohan_tuning_offload_slot_times); the end markers are the events above.
+    std::vector<hipEvent_t> ev_h2d_begin, ev_step_begin, ev_d2h_begin;
     std::vector<bool> used;
     uint64_t submitted = 0;
     int last_slot = -1;
@@ -65,7 +68,7 @@ bool create_events(std::vector<hipEvent_t> &v, int count)
 {
     v.assign((size_t)count, nullptr);
     for (int i = 0; i < count; ++i)
-        if (hipEventCreateWithFlags(&v[(size_t)i], hipEventDisableTiming) != hipSuccess) return false;
+        if (hipEventCreateWithFlags(&v[(size_t)i], hipEventDefault) != hipSuccess) return false;
     return true;
 }
 
@@ -76,6 +79,9 @@ void release(lohan_offload *h)
     destroy_events(h->ev_h2d);
     destroy_events(h->ev_step);
     destroy_events(h->ev_d2h);
+    destroy_events(h->ev_h2d_begin);
+    destroy_events(h->ev_step_begin);
+    destroy_events(h->ev_d2h_begin);
     if (h->s_in) (void)hipStreamDestroy(h->s_in);
     if (h->s_compute) (void)hipStreamDestroy(h->s_compute);
     if (h->s_out) (void)hipStreamDestroy(h->s_out);
@@ -137,7 +143,10 @@ lohan_status_t lohan_offload_create(lohan_offload_t **handle, void *device_slab,
               hipStreamCreateWithFlags(&h->s_compute, hipStreamNonBlocking) == hipSuccess &&
               hipStreamCreateWithFlags(&h->s_out, hipStreamNonBlocking) == hipSuccess &&
               create_events(h->ev_grad, num_slots) && create_events(h->ev_h2d, num_slots) &&
-              create_events(h->ev_step, num_slots) && create_events(h->ev_d2h, num_slots);
+              create_events(h->ev_step, num_slots) && create_events(h->ev_d2h, num_slots) &&
+              create_events(h->ev_h2d_begin, num_slots) &&
+              create_events(h->ev_step_begin, num_slots) &&
+              create_events(h->ev_d2h_begin, num_slots);
     // Every slot's workspace starts with its ticket counters at zero.
     for (int i = 0; ok && i < num_slots; ++i)
         ok = lohan_workspace_init(h->slab + h->slot_bytes * (size_t)i + 3 * h->array_bytes,
@@ -191,6 +200,7 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
     if (h->used[s]) LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_in, h->ev_d2h[s], 0));
     if (h->mode == LOHAN_OFFLOAD_SERIALIZED && h->last_slot >= 0)
         LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_in, h->ev_d2h[(size_t)h->last_slot], 0));
+    LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_h2d_begin[s], h->s_in));
     LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dp, blk->host_param_fp32, bytes, hipMemcpyHostToDevice, h->s_in));
     LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dm, blk->host_exp_avg, bytes, hipMemcpyHostToDevice, h->s_in));
     LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dv, blk->host_exp_avg_sq, bytes, hipMemcpyHostToDevice, h->s_in));
@@ -200,6 +210,7 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
     LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_grad[s], producer_stream));
     LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_compute, h->ev_grad[s], 0));
     LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_compute, h->ev_h2d[s], 0));
+    LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_step_begin[s], h->s_compute));
     if (blk->sqnorm != nullptr)
         st = lohan_grad_sqnorm(blk->grad_fp16, blk->n, loss_scale, blk->sqnorm,
                                blk->overflow_flag, ws, lohan::kWorkspaceBytes, h->s_compute);
@@ -228,6 +239,7 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
 
     // Stage out.  A skipped step left the slot untouched, so the copy writes back the same bits.
     LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_out, h->ev_step[s], 0));
+    LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_d2h_begin[s], h->s_out));
     LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_param_fp32, dp, bytes, hipMemcpyDeviceToHost, h->s_out));
     LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_exp_avg, dm, bytes, hipMemcpyDeviceToHost, h->s_out));
     LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_exp_avg_sq, dv, bytes, hipMemcpyDeviceToHost, h->s_out));
@@ -262,6 +274,23 @@ lohan_status_t lohan_tuning_offload_inject_failure(lohan_offload_t *h, int after
     if (h == nullptr) return LOHAN_ERR_NULL;
     if (after_calls < 0) return LOHAN_ERR_ARG;
     h->fail_countdown = after_calls + 1;
+    return LOHAN_OK;
+}
+
+lohan_status_t lohan_tuning_offload_slot_times(lohan_offload_t *h, int slot, float *h2d_ms,
+                                               float *step_ms, float *d2h_ms)
+{
+    if (h == nullptr) return LOHAN_ERR_NULL;
+    if (slot < 0 || slot >= h->nslots || !h->used[(size_t)slot]) return LOHAN_ERR_ARG;
+    const size_t s = (size_t)slot;
+    float a = 0.0f, b = 0.0f, c = 0.0f;
+    LOHAN_HIP_TRY(hipEventSynchronize(h->ev_d2h[s]));
+    LOHAN_HIP_TRY(hipEventElapsedTime(&a, h->ev_h2d_begin[s], h->ev_h2d[s]));
+    LOHAN_HIP_TRY(hipEventElapsedTime(&b, h->ev_step_begin[s], h->ev_step[s]));
+    LOHAN_HIP_TRY(hipEventElapsedTime(&c, h->ev_d2h_begin[s], h->ev_d2h[s]));
+    if (h2d_ms) *h2d_ms = a;
+    if (step_ms) *step_ms = b;
+    if (d2h_ms) *d2h_ms = c;
     return LOHAN_OK;
 }
 

@@ -153,7 +153,7 @@ def test_pipeline_rejects_bad_arguments():
         lohan.lohan_offload_destroy(h)
 
 
-@pytest.mark.parametrize("after_calls", [0, 3, 6, 8, 10, 12])   # a submit makes 13 runtime calls
+@pytest.mark.parametrize("after_calls", [0, 3, 6, 8, 10, 12])   # a submit makes 16 runtime calls
 def test_failed_submit_poisons_the_handle(oracle, after_calls):
     """A runtime failure in the middle of a submit (injected from the host: the chosen HIP call
     is not issued and reports failure; nothing faults on the device) leaves the handle poisoned:
