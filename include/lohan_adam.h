@@ -413,6 +413,20 @@ lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
                                      size_t *slab_alignment, uint32_t *blocks_per_group);
 
 /*
+ * The compact alternative: most of lohan_model_placement's gain for almost none of its space.
+ * Blocks are packed one after the other (p, m, v, g, p16), every array rounded up to 2 MiB, and
+ * the three fp32 arrays of a block start an ODD number of MiB apart (each is followed by 1 MiB
+ * of padding).  In an interleaved comparison on one fresh slab (update kernel, of the 8 TB/s
+ * peak): 13B-shaped block 0.853 this way, 0.857 in the lanes of lohan_model_placement, 0.840
+ * packed with the arrays an even number of MiB apart; 175B-shaped block 0.848 / 0.860 / 0.847.
+ * Overhead: 4 MiB per block plus the rounding (0.1 % for a 13B-shaped block) instead of 4-17 %.
+ * Arguments and errors as lohan_model_placement (no blocks_per_group).
+ */
+lohan_status_t lohan_model_placement_compact(uint64_t n, uint32_t num_blocks,
+                                             lohan_block_offsets_t *offsets, size_t *slab_bytes,
+                                             size_t *slab_alignment);
+
+/*
  * The same placement for units of UNEQUAL length -- the gradient tensors of Sec. IV-C's handler
  * (per layer: the attention and MLP matrices of 3h^2, h^2, 4h^2, 4h^2 elements and the h-sized
  * bias / LayerNorm vectors), or the slots of a ring with its spares.  lengths[i] is the element

@@ -24,7 +24,8 @@ EXPORTS = (
     "lohan_grad_sqnorm", "lohan_grad_sqnorm_static", "lohan_grad_produce_fp16",
     "lohan_adam_block_step", "lohan_adam_block_step_clipped",
     "lohan_adam_block_step_out_of_place", "lohan_adam_block_step_out_of_place_clipped",
-    "lohan_adam_multi_block_step", "lohan_model_placement", "lohan_tensor_placement",
+    "lohan_adam_multi_block_step", "lohan_model_placement", "lohan_model_placement_compact",
+    "lohan_tensor_placement",
     "lohan_ring_bytes", "lohan_ring_init", "lohan_ring_adam_block_step",
     "lohan_ring_adam_block_step_clipped", "lohan_ring_read",
     "lohan_clip_loss_scale", "lohan_workspace_init",
@@ -148,6 +149,9 @@ def load_library():
     lib.lohan_ring_read.argtypes = [vp, u32, u32, ctypes.POINTER(u32), ctypes.POINTER(u32),
                                     ctypes.POINTER(u32), vp]
     lib.lohan_ring_read.restype = ctypes.c_int
+    lib.lohan_model_placement_compact.argtypes = [u64, u32, ctypes.POINTER(LohanBlockOffsets),
+                                                  ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.lohan_model_placement_compact.restype = ctypes.c_int
     lib.lohan_tensor_placement.argtypes = [ctypes.POINTER(u64), u32,
                                            ctypes.POINTER(LohanBlockOffsets), ctypes.POINTER(sz),
                                            ctypes.POINTER(sz)]
@@ -455,6 +459,17 @@ def lohan_ring_read(ring, num_blocks, num_spares=1, stream=None):
                                           int(num_spares), slot_of, spares, last,
                                           _stream(stream)))
     return list(slot_of), list(spares), list(last)
+
+
+def lohan_model_placement_compact(n, num_blocks=1):
+    """Returns (offsets, slab_bytes, slab_alignment); offsets as lohan_model_placement's."""
+    arr = (LohanBlockOffsets * max(1, num_blocks))()
+    total, align = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load_library().lohan_model_placement_compact(int(n), int(num_blocks), arr,
+                                                        ctypes.byref(total), ctypes.byref(align)))
+    fields = [f for f, _ in LohanBlockOffsets._fields_]
+    return ([{f: getattr(arr[b], f) for f in fields} for b in range(num_blocks)], total.value,
+            align.value)
 
 
 def lohan_tensor_placement(lengths):

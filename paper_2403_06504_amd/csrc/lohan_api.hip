@@ -694,6 +694,35 @@ lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
     return LOHAN_OK;
 }
 
+lohan_status_t lohan_model_placement_compact(uint64_t n, uint32_t num_blocks,
+                                             lohan_block_offsets_t *offsets, size_t *slab_bytes,
+                                             size_t *slab_alignment)
+{
+    constexpr size_t kGranule = 2ull << 20;
+    constexpr size_t kSkew = 1ull << 20;
+    if (slab_bytes == nullptr || slab_alignment == nullptr ||
+        (offsets == nullptr && num_blocks != 0))
+        return LOHAN_ERR_NULL;
+    if (n > (1ull << 40)) return LOHAN_ERR_ARG;
+    auto round_up = [](size_t x, size_t a) { return (x + a - 1) / a * a; };
+    const size_t wide = round_up((size_t)n * 4, kGranule);
+    const size_t narrow = round_up((size_t)n * 2, kGranule);
+    // p, m, v an odd number of MiB apart; the block as a whole a multiple of 2 MiB long.
+    const size_t block_bytes = 3 * (wide + kSkew) + 2 * narrow + kSkew;
+    for (uint32_t b = 0; b < num_blocks; ++b) {
+        const size_t base = (size_t)b * block_bytes;
+        lohan_block_offsets_t &o = offsets[b];
+        o.param_fp32 = base;
+        o.exp_avg = base + wide + kSkew;
+        o.exp_avg_sq = base + 2 * (wide + kSkew);
+        o.grad_fp16 = base + 3 * (wide + kSkew);
+        o.param_bf16 = o.grad_fp16 + narrow;
+    }
+    *slab_bytes = (size_t)num_blocks * block_bytes;
+    *slab_alignment = kGranule;
+    return LOHAN_OK;
+}
+
 lohan_status_t lohan_tensor_placement(const uint64_t *lengths, uint32_t count,
                                       lohan_block_offsets_t *offsets, size_t *slab_bytes,
                                       size_t *slab_alignment)

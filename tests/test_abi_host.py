@@ -352,6 +352,33 @@ def test_out_of_place_clipped_validation(lib):
     assert status(wsb=16) == 4
 
 
+def test_compact_placement_properties(lib):
+    mib = 1 << 20
+    for n, blocks in ((12 * 5120 ** 2, 5), (12 * 12288 ** 2, 2), (12 * 768 ** 2, 12), (1000, 3),
+                      (0, 2)):
+        offsets, total, align = lohan.lohan_model_placement_compact(n, blocks)
+        assert align == 2 * mib
+        spans = []
+        for o in offsets:
+            assert (o["exp_avg"] - o["param_fp32"]) % (2 * mib) == mib      # odd MiB apart
+            assert (o["exp_avg_sq"] - o["exp_avg"]) % (2 * mib) == mib
+            for field, width in (("param_fp32", 4), ("exp_avg", 4), ("exp_avg_sq", 4),
+                                 ("grad_fp16", 2), ("param_bf16", 2)):
+                assert o[field] % mib == 0 and o[field] + n * width <= total
+                spans.append((o[field], o[field] + n * width))
+        spans = sorted(s for s in spans if s[1] > s[0])
+        assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
+        assert total <= 16 * n * blocks + blocks * 14 * mib
+    _, total, _ = lohan.lohan_model_placement_compact(12 * 5120 ** 2, 40)
+    assert total <= 1.002 * 16 * 12 * 5120 ** 2 * 40
+    total_c, align_c = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.lohan_model_placement_compact(8, 1, None, ctypes.byref(total_c),
+                                             ctypes.byref(align_c)) == 1
+    one = (binding.LohanBlockOffsets * 1)()
+    assert lib.lohan_model_placement_compact((1 << 40) + 1, 1, one, ctypes.byref(total_c),
+                                             ctypes.byref(align_c)) == 3
+
+
 def test_tensor_placement_properties(lib):
     """Per-tensor placement: inside the slab, aligned, disjoint, p/m/v of one tensor at the same
     offset within lanes one period + 1 MiB apart, and equal to the equal-block placement when the
