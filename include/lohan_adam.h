@@ -50,7 +50,7 @@ typedef enum {
     LOHAN_ERR_ARG = 3,        /* a scalar argument is out of its domain (see each call) */
     LOHAN_ERR_WORKSPACE = 4,  /* workspace_bytes < lohan_workspace_bytes() */
     LOHAN_ERR_HIP = 5,        /* the HIP runtime reported an error at launch */
-    LOHAN_ERR_TOO_LARGE = 6   /* n exceeds LOHAN_GRAD_SQNORM_STATIC_MAX_N (lohan_grad_sqnorm_static) */
+    LOHAN_ERR_TOO_LARGE = 6   /* n exceeds the maximum of lohan_grad_sqnorm_static */
 } lohan_status_t;
 
 enum {
@@ -511,8 +511,9 @@ lohan_status_t lohan_offload_create(lohan_offload_t **handle, void *device_slab,
  * the call.  Validation errors enqueue nothing.  If the HIP runtime fails after part of the
  * block's work has been enqueued, LOHAN_ERR_HIP is returned and the handle is POISONED: its slot
  * bookkeeping no longer describes what is in flight, so every later lohan_offload_submit and
- * lohan_offload_wait_last_step returns LOHAN_ERR_HIP without enqueueing anything; lohan_offload_drain
- * and lohan_offload_destroy still work.  The failed block's host arrays are unspecified.
+ * lohan_offload_wait_last_step returns LOHAN_ERR_HIP without enqueueing anything;
+ * lohan_offload_drain and lohan_offload_destroy still work.  The failed block's host arrays are
+ * unspecified.
  */
 lohan_status_t lohan_offload_submit(lohan_offload_t *handle, const lohan_offload_block_t *blk,
                                     float lr, float beta1, float beta2, float eps,

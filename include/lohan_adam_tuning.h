@@ -48,8 +48,8 @@ lohan_status_t lohan_tuning_device_info(int *compute_units, size_t *lds_bytes_pe
  * ceiling the machine sustains for each (64-lane workgroups handed out in address order, 128-bit
  * accesses per lane, nontemporal loads and write-through streaming stores; the five-stream probe
  * has the update kernel's exact launch shape, one 256-element tile per workgroup, the
- * single-stream probes take eight such rows per workgroup).  Each call enqueues ONE kernel on `stream` (LOHAN_PROBE_MEMCPY: one
- * hipMemcpyAsync device-to-device) and returns.
+ * single-stream probes take eight such rows per workgroup).  Each call enqueues ONE kernel on
+ * `stream` (LOHAN_PROBE_MEMCPY: one hipMemcpyAsync device-to-device) and returns.
  *   LOHAN_PROBE_READ         reads n floats from a                       4 n bytes
  *   LOHAN_PROBE_WRITE        writes n floats to b                        4 n bytes
  *   LOHAN_PROBE_COPY         b[i] = a[i]                                 8 n bytes
@@ -59,8 +59,9 @@ lohan_status_t lohan_tuning_device_info(int *compute_units, size_t *lds_bytes_pe
  *   LOHAN_PROBE_MEMCPY       hipMemcpyAsync(b, a, 4 n, DeviceToDevice)   8 n bytes
  * a, b, c, g16, h16: device, 16-byte aligned, n elements each, not overlapping; pointers a
  * pattern does not use may be NULL.  Only whole tiles are touched: n is rounded down to a
- * multiple of 256 elements (five-stream, memcpy) or of 2048 elements (read, write, copy).  waves_per_cu: occupancy throttle as above (0 = none).  The contents of written arrays
- * are unspecified afterwards.  Errors: LOHAN_ERR_NULL / _ALIGN / _ARG, LOHAN_ERR_HIP.
+ * multiple of 256 elements (five-stream, memcpy) or of 2048 elements (read, write, copy).
+ * waves_per_cu: occupancy throttle as above (0 = none).  The contents of written arrays are
+ * unspecified afterwards.  Errors: LOHAN_ERR_NULL / _ALIGN / _ARG, LOHAN_ERR_HIP.
  */
 enum {
     LOHAN_PROBE_READ = 0,

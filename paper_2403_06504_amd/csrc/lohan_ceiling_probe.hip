@@ -134,10 +134,10 @@ extern "C" lohan_status_t lohan_tuning_probe(int pattern, float *a, float *b, fl
     const dim3 grid((uint32_t)tiles), wg(kLanes);
     const dim3 grid_rows((uint32_t)(tiles / kRows));        // whole groups of rows only
     if (pattern != LOHAN_PROBE_FIVE_STREAM && grid_rows.x == 0) return LOHAN_OK;
-    const void *kernel = pattern == LOHAN_PROBE_READ    ? reinterpret_cast<const void *>(k_probe_read)
-                         : pattern == LOHAN_PROBE_WRITE ? reinterpret_cast<const void *>(k_probe_write)
-                         : pattern == LOHAN_PROBE_COPY  ? reinterpret_cast<const void *>(k_probe_copy)
-                                                        : reinterpret_cast<const void *>(k_probe_five_stream);
+    const void *kernel = reinterpret_cast<const void *>(k_probe_five_stream);
+    if (pattern == LOHAN_PROBE_READ) kernel = reinterpret_cast<const void *>(k_probe_read);
+    if (pattern == LOHAN_PROBE_WRITE) kernel = reinterpret_cast<const void *>(k_probe_write);
+    if (pattern == LOHAN_PROBE_COPY) kernel = reinterpret_cast<const void *>(k_probe_copy);
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
             hipSuccess)

@@ -201,9 +201,12 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
     if (h->mode == LOHAN_OFFLOAD_SERIALIZED && h->last_slot >= 0)
         LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_in, h->ev_d2h[(size_t)h->last_slot], 0));
     LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_h2d_begin[s], h->s_in));
-    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dp, blk->host_param_fp32, bytes, hipMemcpyHostToDevice, h->s_in));
-    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dm, blk->host_exp_avg, bytes, hipMemcpyHostToDevice, h->s_in));
-    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dv, blk->host_exp_avg_sq, bytes, hipMemcpyHostToDevice, h->s_in));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dp, blk->host_param_fp32, bytes, hipMemcpyHostToDevice,
+                                        h->s_in));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dm, blk->host_exp_avg, bytes, hipMemcpyHostToDevice,
+                                        h->s_in));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(dv, blk->host_exp_avg_sq, bytes, hipMemcpyHostToDevice,
+                                        h->s_in));
     LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_h2d[s], h->s_in));
 
     // Step: needs the staged states and the gradients the producer stream has enqueued so far.
@@ -240,9 +243,12 @@ lohan_status_t lohan_offload_submit(lohan_offload_t *h, const lohan_offload_bloc
     // Stage out.  A skipped step left the slot untouched, so the copy writes back the same bits.
     LOHAN_SUBMIT_TRY(h, hipStreamWaitEvent(h->s_out, h->ev_step[s], 0));
     LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_d2h_begin[s], h->s_out));
-    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_param_fp32, dp, bytes, hipMemcpyDeviceToHost, h->s_out));
-    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_exp_avg, dm, bytes, hipMemcpyDeviceToHost, h->s_out));
-    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_exp_avg_sq, dv, bytes, hipMemcpyDeviceToHost, h->s_out));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_param_fp32, dp, bytes, hipMemcpyDeviceToHost,
+                                        h->s_out));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_exp_avg, dm, bytes, hipMemcpyDeviceToHost,
+                                        h->s_out));
+    LOHAN_SUBMIT_TRY(h, hipMemcpyAsync(blk->host_exp_avg_sq, dv, bytes, hipMemcpyDeviceToHost,
+                                        h->s_out));
     LOHAN_SUBMIT_TRY(h, hipEventRecord(h->ev_d2h[s], h->s_out));
 
     h->used[s] = true;

@@ -101,3 +101,22 @@ def test_step_after_the_producer_needs_no_check_pass(oracle):
         else:
             worst = assert_state_parity(got, host, what="step after the producer")
             assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}, worst
+
+
+def test_producer_on_the_13b_block_shape(oracle):
+    """The bench's block shape in the bench's launch configuration: whole-array flag and norm,
+    output bits on sampled ranges (first, last, seeded interior)."""
+    wl = synth.WORKLOADS["gpt13b"]
+    n, S = wl.n, wl.loss_scale
+    src = accumulator(n, 3, S)
+    out, flag, sq = produce(src, 0.5, S)
+    assert flag == 0
+    span = 1 << 21
+    rng = np.random.default_rng(5)
+    for lo in [0, n - span] + [int(x) for x in rng.integers(span, n - 2 * span, size=3)]:
+        want = oracle.grad_produce(src[lo:lo + span].cpu().numpy(), 0.5)
+        assert np.array_equal(synth.to_numpy_bits(out[lo:lo + span]), want), lo
+    ref = oracle.grad_sqnorm(synth.to_numpy_bits(out), S)
+    assert abs(sq - ref) <= RTOL_SQNORM * ref, (sq, ref)
+    src[n - 3] = 1e9
+    assert produce(src, 0.5, S)[1] == 1
