@@ -23,8 +23,8 @@
  *   - `workspace` is device scratch of at least lohan_workspace_bytes() bytes, 16-byte aligned,
  *     private to the call until its kernels complete (calls that may run concurrently on different
  *     streams need different workspaces).  It must have been prepared ONCE with
- *     lohan_workspace_init (or be zero-filled) before its first use; every call leaves it ready
- *     for the next one, so nothing needs clearing between calls.
+ *     lohan_workspace_init before its first use; every call leaves it ready for the next one, so
+ *     nothing needs clearing between calls.
  *   - n is the element count of the flat block; any n >= 0 is accepted (n == 0: flag = 0,
  *     squared norm = 0, nothing else is touched).
  *   - Errors are reported by return code only.  For codes LOHAN_ERR_NULL .. LOHAN_ERR_WORKSPACE no
@@ -72,9 +72,12 @@ size_t lohan_workspace_bytes(void);
  * (the workgroup that publishes the last partial result combines them all), which needs a few
  * ticket counters in the workspace to read zero when a call starts.  This enqueues a small fill
  * kernel on `stream` that zeroes them; every later call puts them back to zero itself.  Call it
- * once per workspace (and again after an LOHAN_ERR_HIP, when the contents are unspecified).  A
- * workspace whose counters are not zero makes the calls that use it leave their outputs
- * unwritten.  Errors: LOHAN_ERR_NULL / _ALIGN / _WORKSPACE as for any workspace argument.
+ * once per workspace (and again after an LOHAN_ERR_HIP, when the contents are unspecified).  It
+ * also writes a marker by which the kernels recognise a prepared workspace: a call that is
+ * handed one without the marker reduces nothing and reports the block as overflowing
+ * (*overflow_flag = 1, *sqnorm = NaN), so the step that follows is skipped -- wrong use fails
+ * visibly and on the safe side.  Errors: LOHAN_ERR_NULL / _ALIGN / _WORKSPACE as for any
+ * workspace argument.
  */
 lohan_status_t lohan_workspace_init(void *workspace, size_t workspace_bytes, hipStream_t stream);
 

@@ -87,13 +87,17 @@ inline RingView ring_view(void *ring, uint32_t num_blocks, uint32_t num_spares)
 // scalars: kMultiMaxBlocks unscale factors (float; a single-block clipped step uses the first),
 // then kMultiMaxBlocks squared norms (double) for multi-block calls whose caller wants none,
 // then kMultiMaxBlocks uint32 ticket counters of the gradient reduction (a single-block call uses
-// the first).  The counters are the only part with an invariant: zero between calls
-// (launch_workspace_init sets it up, every reduction restores it).
+// the first), then a 64-bit word that holds kWorkspaceMagic once the workspace has been prepared.
+// The counters are the only part with an invariant: zero between calls (launch_workspace_init
+// sets it up, every reduction restores it); the magic word lets the kernels tell a workspace that
+// was never prepared, whose counters may hold anything.
 constexpr uint32_t kMaxPartials = 4096;
 constexpr size_t kScalarsOffset = (size_t)kMaxPartials * (sizeof(double) + sizeof(uint32_t));
 constexpr size_t kNormsOffset = kScalarsOffset + 256;
 constexpr size_t kCountersOffset = kNormsOffset + kMultiMaxBlocks * sizeof(double);
-constexpr size_t kWorkspaceBytes = kCountersOffset + kMultiMaxBlocks * sizeof(uint32_t);
+constexpr size_t kMagicOffset = kCountersOffset + kMultiMaxBlocks * sizeof(uint32_t);
+constexpr size_t kWorkspaceBytes = kMagicOffset + 16;
+constexpr uint64_t kWorkspaceMagic = 0x4C6F48616E57531Full;
 static_assert(kMultiMaxBlocks * sizeof(float) <= 256, "unscale factors must fit their area");
 
 // What the launchers need to know about the device the stream belongs to.
@@ -102,7 +106,7 @@ struct DeviceInfo {
     size_t lds_per_cu;   // bytes of LDS per compute unit (sizes the occupancy throttle)
 };
 
-// Zero the ticket counters of a workspace (a one-workgroup fill kernel).
+// Zero the ticket counters of a workspace and set its magic word (a one-workgroup fill kernel).
 hipError_t launch_workspace_init(void *workspace, hipStream_t stream);
 
 // stream_past_caches: nontemporal loads (blocks far larger than the memory-side cache) instead

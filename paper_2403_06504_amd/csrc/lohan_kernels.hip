@@ -306,14 +306,34 @@ __device__ __forceinline__ void grad_reduce_body(const uint16_t *__restrict__ g,
                                          partial_flag, counter, inv2, sqnorm_out, flag_out);
 }
 
+// A workspace that was never prepared (lohan_workspace_init) may hold anything in its ticket
+// counters, and then no workgroup would ever recognise itself as the last one.  Every reducing
+// kernel therefore looks at the workspace's magic word first; without it, it reduces nothing
+// and reports the block as overflowing (flag 1, norm NaN), which makes the step skip: wrong use
+// fails on the safe side and visibly, not with a stale flag.
+__device__ __forceinline__ bool workspace_unprepared(const uint64_t *__restrict__ magic,
+                                                     double *__restrict__ sqnorm_out,
+                                                     uint32_t *__restrict__ flag_out)
+{
+    if (*magic == kWorkspaceMagic) return false;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (sqnorm_out != nullptr) *sqnorm_out = __builtin_nan("");
+        if (flag_out != nullptr) *flag_out = 1u;
+    }
+    return true;
+}
+
 template <bool WITH_NORM, int UNROLL, bool NT>
 __global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *__restrict__ g,
                                                                 uint64_t n, double *partial_sum,
                                                                 uint32_t *partial_flag,
-                                                                uint32_t *counter, double inv2,
+                                                                uint32_t *counter,
+                                                                const uint64_t *__restrict__ magic,
+                                                                double inv2,
                                                                 double *__restrict__ sqnorm,
                                                                 uint32_t *__restrict__ flag)
 {
+    if (workspace_unprepared(magic, sqnorm, flag)) return;
     grad_reduce_body<WITH_NORM, UNROLL, NT>(g, n, blockIdx.x, gridDim.x, 0u, partial_sum,
                                             partial_flag, counter, inv2, sqnorm, flag);
 }
@@ -323,10 +343,14 @@ __global__ __launch_bounds__(kReduceThreads) void k_grad_reduce(const uint16_t *
 // to sqnorms[b] and flags[b].
 template <bool WITH_NORM, int UNROLL, bool NT>
 __global__ __launch_bounds__(kReduceThreads) void k_multi_grad_reduce(
-    MultiArgs args, double *partial_sum, uint32_t *partial_flag, uint32_t *counters, double inv2,
-    double *__restrict__ sqnorms, uint32_t *__restrict__ flags)
+    MultiArgs args, double *partial_sum, uint32_t *partial_flag, uint32_t *counters,
+    const uint64_t *__restrict__ magic, double inv2, double *__restrict__ sqnorms,
+    uint32_t *__restrict__ flags)
 {
     const uint32_t b = blockIdx.y;
+    if (workspace_unprepared(magic, sqnorms != nullptr ? sqnorms + b : nullptr,
+                             flags != nullptr ? flags + b : nullptr))
+        return;
     grad_reduce_body<WITH_NORM, UNROLL, NT>(args.d[b].g, args.d[b].n, blockIdx.x, gridDim.x,
                                             b * gridDim.x, partial_sum, partial_flag, counters + b,
                                             inv2, sqnorms != nullptr ? sqnorms + b : nullptr,
@@ -343,9 +367,11 @@ __global__ __launch_bounds__(kReduceThreads) void k_multi_grad_reduce(
 template <bool WITH_NORM, int UNROLL, bool NT>
 __global__ __launch_bounds__(kReduceThreads) void k_grad_produce(
     const float *__restrict__ src, uint64_t n, float mul, uint16_t *__restrict__ out,
-    double *partial_sum, uint32_t *partial_flag, uint32_t *counter, double inv2,
-    double *__restrict__ sqnorm_out, uint32_t *__restrict__ flag_out)
+    double *partial_sum, uint32_t *partial_flag, uint32_t *counter,
+    const uint64_t *__restrict__ magic, double inv2, double *__restrict__ sqnorm_out,
+    uint32_t *__restrict__ flag_out)
 {
+    if (workspace_unprepared(magic, sqnorm_out, flag_out)) return;
     constexpr uint64_t kVec = 4;
     constexpr uint64_t kRow = (uint64_t)kReduceThreads * kVec;
     constexpr uint64_t kTile = kRow * UNROLL;
@@ -393,11 +419,13 @@ __global__ __launch_bounds__(kReduceThreads) void k_grad_produce(
                                          counter, inv2, sqnorm_out, flag_out);
 }
 
-// Ticket counters start at zero; afterwards every reduction leaves them at zero.
-__global__ void k_workspace_init(uint32_t *counters, uint32_t count)
+// Ticket counters start at zero; afterwards every reduction leaves them at zero.  The magic word
+// marks the workspace as prepared.
+__global__ void k_workspace_init(uint32_t *counters, uint32_t count, uint64_t *magic)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) counters[i] = 0u;
+    if (i == 0) *magic = kWorkspaceMagic;
 }
 
 // n == 0: nothing to reduce, but the outputs are still defined.
@@ -787,6 +815,7 @@ struct WorkspaceView {
     double *partial_sum;
     uint32_t *partial_flag;
     uint32_t *counters;
+    uint64_t *magic;
 };
 
 static WorkspaceView workspace_view(void *workspace)
@@ -794,13 +823,15 @@ static WorkspaceView workspace_view(void *workspace)
     char *base = reinterpret_cast<char *>(workspace);
     return WorkspaceView{reinterpret_cast<double *>(base),
                          reinterpret_cast<uint32_t *>(base + sizeof(double) * kMaxPartials),
-                         reinterpret_cast<uint32_t *>(base + kCountersOffset)};
+                         reinterpret_cast<uint32_t *>(base + kCountersOffset),
+                         reinterpret_cast<uint64_t *>(base + kMagicOffset)};
 }
 
 hipError_t launch_workspace_init(void *workspace, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_workspace_init, dim3(1), dim3(64), 0, stream,
-                       workspace_view(workspace).counters, kMultiMaxBlocks);
+    const WorkspaceView ws = workspace_view(workspace);
+    hipLaunchKernelGGL(k_workspace_init, dim3(1), dim3(64), 0, stream, ws.counters,
+                       kMultiMaxBlocks, ws.magic);
     return hipGetLastError();
 }
 
@@ -813,11 +844,11 @@ static void launch_reduce_policy(bool stream_past_caches, uint32_t grid, hipStre
     if (stream_past_caches)
         hipLaunchKernelGGL((k_grad_reduce<WITH_NORM, kUnroll, true>), dim3(grid),
                            dim3(kReduceThreads), 0, stream, g, n, ws.partial_sum, ws.partial_flag,
-                           ws.counters, inv2, sqnorm, flag);
+                           ws.counters, ws.magic, inv2, sqnorm, flag);
     else
         hipLaunchKernelGGL((k_grad_reduce<WITH_NORM, kUnroll, false>), dim3(grid),
                            dim3(kReduceThreads), 0, stream, g, n, ws.partial_sum, ws.partial_flag,
-                           ws.counters, inv2, sqnorm, flag);
+                           ws.counters, ws.magic, inv2, sqnorm, flag);
 }
 
 hipError_t launch_grad_reduce(const void *grad_fp16, uint64_t n, bool with_norm, double inv2,
@@ -851,11 +882,11 @@ static void launch_produce_policy(bool stream_past_caches, uint32_t grid, hipStr
     if (stream_past_caches)
         hipLaunchKernelGGL((k_grad_produce<WITH_NORM, kUnroll, true>), dim3(grid),
                            dim3(kReduceThreads), 0, stream, src, n, mul, out, ws.partial_sum,
-                           ws.partial_flag, ws.counters, inv2, sqnorm, flag);
+                           ws.partial_flag, ws.counters, ws.magic, inv2, sqnorm, flag);
     else
         hipLaunchKernelGGL((k_grad_produce<WITH_NORM, kUnroll, false>), dim3(grid),
                            dim3(kReduceThreads), 0, stream, src, n, mul, out, ws.partial_sum,
-                           ws.partial_flag, ws.counters, inv2, sqnorm, flag);
+                           ws.partial_flag, ws.counters, ws.magic, inv2, sqnorm, flag);
 }
 
 hipError_t launch_grad_produce(const float *grad_fp32, uint64_t n, float multiplier,
@@ -898,11 +929,11 @@ static void launch_multi_reduce_policy(bool stream_past_caches, dim3 grid, hipSt
     if (stream_past_caches)
         hipLaunchKernelGGL((k_multi_grad_reduce<WITH_NORM, kUnroll, true>), grid,
                            dim3(kReduceThreads), 0, stream, args, ws.partial_sum, ws.partial_flag,
-                           ws.counters, inv2, sqnorms, flags);
+                           ws.counters, ws.magic, inv2, sqnorms, flags);
     else
         hipLaunchKernelGGL((k_multi_grad_reduce<WITH_NORM, kUnroll, false>), grid,
                            dim3(kReduceThreads), 0, stream, args, ws.partial_sum, ws.partial_flag,
-                           ws.counters, inv2, sqnorms, flags);
+                           ws.counters, ws.magic, inv2, sqnorms, flags);
 }
 
 hipError_t launch_multi_grad_reduce(const MultiArgs &args, uint32_t num_blocks, bool with_norm,

@@ -786,3 +786,44 @@ def test_random_bit_patterns_and_hyperparameters(oracle):
         assert nan_aware_equal(got["p16"], host["p16"], nan16), (case, "second step", "p16", hy)
         say(f"[random] case {case}: {int(np.isnan(host['p']).sum())} NaN, "
             f"{int(np.isinf(host['p']).sum())} inf of {n} parameters after two steps")
+
+
+def test_unprepared_workspace_fails_on_the_safe_side(oracle):
+    """A workspace that lohan_workspace_init never saw (here: filled with a byte pattern, so its
+    ticket counters hold garbage) must not leave a stale flag behind: the reducing calls report
+    flag 1 and a NaN norm, and the self-checking step writes nothing.  Once prepared, the same
+    memory works."""
+    n = 300_007
+    wl = small_workload(n)
+    hy = wl.hyper()
+    blk = DeviceBlock(synth.make_block(wl, seed=3, device=DEV))
+    before = blk.host()
+    for fill in (0xA5, 0x00, 0xFF):
+        raw = torch.full((lohan.lohan_workspace_bytes(),), fill, dtype=torch.uint8, device=DEV)
+        blk.flag.fill_(0)
+        blk.sqnorm.fill_(0.0)
+        lohan.lohan_grad_sqnorm(blk.g, n, wl.loss_scale, blk.sqnorm, blk.flag, raw)
+        torch.cuda.synchronize()
+        assert blk.flag_value() == 1 and np.isnan(float(blk.sqnorm.cpu().item())), fill
+        blk.flag.fill_(0)
+        lohan.lohan_grad_overflow_check(blk.g, n, blk.flag, raw)
+        torch.cuda.synchronize()
+        assert blk.flag_value() == 1, fill
+        blk.flag.fill_(0)
+        lohan.lohan_adam_block_step(blk.p, blk.m, blk.v, blk.g, blk.p16, n, hy["lr"], hy["beta1"],
+                                    hy["beta2"], hy["eps"], hy["weight_decay"], hy["step"],
+                                    hy["loss_scale"], blk.flag, 0, raw)
+        torch.cuda.synchronize()
+        assert blk.flag_value() == 1
+        after = blk.host()
+        for k in ("p", "m", "v", "p16"):
+            assert np.array_equal(after[k].view(np.uint8), before[k].view(np.uint8)), (fill, k)
+    lohan.lohan_workspace_init(raw)
+    lohan.lohan_adam_block_step(blk.p, blk.m, blk.v, blk.g, blk.p16, n, hy["lr"], hy["beta1"],
+                                hy["beta2"], hy["eps"], hy["weight_decay"], hy["step"],
+                                hy["loss_scale"], blk.flag, 0, raw)
+    torch.cuda.synchronize()
+    assert blk.flag_value() == 0
+    assert oracle_steps(oracle, before, hy, 1, nthreads=4) == [0]
+    worst = assert_state_parity(blk.host(), before, what="after preparing the workspace")
+    assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
