@@ -280,6 +280,54 @@ def producer_fused_step(block, wl, n, flag, sqnorm, ws, args, torch, lohan):
             "producer_plus_update_ms": elapsed * 1e3}
 
 
+def back_to_back_steps(one_step, first_t, steps, torch):
+    """Seconds per step of `steps` steps issued with nothing between them (no event records),
+    bracketed by synchronisations: what a framework's own loop would see."""
+    one_step(first_t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        one_step(first_t + 1 + k)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def small_block_figure(block, wl, n, flag, sqnorm, ws, args, torch, lohan):
+    """lohan_adam_small_block_step on the same block: flag, norm and update in one launch with
+    the block held in registers (only for blocks the device's registers hold)."""
+    hy = wl.hyper()
+
+    def one(t):
+        lohan.lohan_adam_small_block_step(block["p"], block["m"], block["v"], block["g"],
+                                          block["p16"], n, hy["lr"], hy["beta1"], hy["beta2"],
+                                          hy["eps"], hy["weight_decay"], t, hy["loss_scale"],
+                                          sqnorm, flag, 0, ws)
+
+    for w in range(3):
+        one(hy["step"] + w)
+    torch.cuda.synchronize()
+    steps = args.steps
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(steps)]
+    for k in range(steps):
+        events[k][0].record()
+        one(hy["step"] + 3 + k)
+        events[k][1].record()
+    torch.cuda.synchronize()
+    assert int(flag.cpu().item()) == 0
+    launch = spread([a.elapsed_time(b) for a, b in events])
+    b2b = back_to_back_steps(one, hy["step"] + 3 + steps, steps, torch)
+    assert int(flag.cpu().item()) == 0
+    return {"note": "one launch per step: flag, norm, grid-wide barrier and update, 28 B/element "
+                    "moved; launch_ms is event to event around the one kernel",
+            "max_n": lohan.lohan_adam_small_block_max_n(),
+            "launch_ms": launch,
+            "gbps_at_28B": 28 * n / (launch["median_ms"] * 1e-3) / 1e9,
+            "frac_of_peak_at_28B": 28 * n / (launch["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "back_to_back_us_per_step": b2b * 1e6,
+            "back_to_back_elements_per_s": n / b2b}
+
+
 def compact_placement_figure(slab, wl, args, torch, lohan):
     """The update kernel on the same arena laid out by lohan_model_placement_compact (arrays
     packed, the fp32 arrays an odd number of MiB apart): refills the arena, so it runs after the
@@ -405,6 +453,15 @@ def measure_block(wl, args, torch, lohan, synth, with_cpu_baseline, slab=None):
                           "achieved_gbps": gbps(REDUCE_BYTES_PER_ELEM * n, reduce_["median_ms"])},
         "cpu_baseline": base,
     }
+    out["back_to_back"] = {
+        "note": "the same two-call step issued with no event records in between (the timed "
+                "region above carries three per step for the per-kernel durations)",
+        "us_per_step": back_to_back_steps(lambda t: one_step(t), hy["step"] + args.warmup
+                                          + args.steps, args.steps, torch) * 1e6}
+    out["back_to_back"]["elements_per_s"] = n / (out["back_to_back"]["us_per_step"] * 1e-6)
+    if n <= lohan.lohan_adam_small_block_max_n():
+        out["small_block_step"] = small_block_figure(block, wl, n, flag, sqnorm, ws, args, torch,
+                                                     lohan)
     if args.producer_fused:
         out["producer_fused"] = producer_fused_step(block, wl, n, flag, sqnorm, ws, args, torch,
                                                     lohan)

@@ -50,7 +50,7 @@ typedef enum {
     LOHAN_ERR_ARG = 3,        /* a scalar argument is out of its domain (see each call) */
     LOHAN_ERR_WORKSPACE = 4,  /* workspace_bytes < lohan_workspace_bytes() */
     LOHAN_ERR_HIP = 5,        /* the HIP runtime reported an error at launch */
-    LOHAN_ERR_TOO_LARGE = 6   /* n exceeds the maximum of lohan_grad_sqnorm_static */
+    LOHAN_ERR_TOO_LARGE = 6   /* n exceeds the maximum of an entry point that has one */
 } lohan_status_t;
 
 enum {
@@ -212,6 +212,45 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
                                              float max_norm, const uint32_t *overflow_flag,
                                              uint32_t flags, void *workspace,
                                              size_t workspace_bytes, hipStream_t stream);
+
+/*
+ * The whole step of a SMALL block in one launch (Sec. IV-C: flag, then the update of block i's
+ * model states; tensors of Table II): *overflow_flag and *sqnorm as lohan_grad_sqnorm computes
+ * them, and the update of lohan_adam_block_step under the same skip rule, without the separate
+ * 2-byte pass and without a second launch.  The grid is sized so that all of it is resident on
+ * the device at once; every workgroup loads its share of the block into registers, the
+ * workgroups meet at a grid-wide barrier whose counter carries the flag, and the update is
+ * computed from registers: 28 bytes per element moved, reads and writes in two separate phases.
+ * For a block of a few million elements this takes about two thirds of the time of
+ * lohan_grad_sqnorm + lohan_adam_block_step, which there is a chain of launch and memory
+ * latencies; blocks that do not fit the device's registers cannot use it.
+ *   n              at most the value lohan_adam_small_block_max_n reports for the device (about
+ *                  7.8 million elements on MI355X), else LOHAN_ERR_TOO_LARGE
+ *   sqnorm         device, out: one double or NULL; unspecified when the flag is set
+ *   overflow_flag  device, out: always written: 0 (step taken), 1 (overflow: state bit-identical)
+ *   flags          LOHAN_FLAG_L2_MODE and/or LOHAN_FLAG_P16_FP16; LOHAN_FLAG_PRECHECKED ->
+ *                  LOHAN_ERR_ARG (with a known flag lohan_adam_block_step is the one to call)
+ *   workspace      required, prepared by lohan_workspace_init
+ * State after the call is bit-identical to the two-call sequence; *sqnorm is accumulated in
+ * float64 in a fixed order of its own (same input -> same bits; within 1e-5 relative of
+ * lohan_grad_sqnorm).
+ * The barrier's wait is bounded, so every wavefront exits whatever else runs on the device: the
+ * workgroups can only all be resident if the compute units are not held by other kernels for
+ * good.  Kernels of other streams that finish by themselves merely delay it.  If a workgroup
+ * does give up waiting (about a second), *overflow_flag has LOHAN_OVERFLOW_INCOMPLETE set and the
+ * block's state is unspecified (some workgroups may have written, others not): treat it as a
+ * failed step and restore the block from a checkpoint.  Everything else as lohan_adam_block_step.
+ */
+#define LOHAN_OVERFLOW_INCOMPLETE 0x80000000u
+lohan_status_t lohan_adam_small_block_max_n(uint64_t *max_n);
+lohan_status_t lohan_adam_small_block_step(float *param_fp32, float *exp_avg, float *exp_avg_sq,
+                                           const void *grad_fp16, void *param_bf16_out,
+                                           uint64_t n, float lr, float beta1, float beta2,
+                                           float eps, float weight_decay, int64_t step,
+                                           float loss_scale, double *sqnorm,
+                                           uint32_t *overflow_flag, uint32_t flags,
+                                           void *workspace, size_t workspace_bytes,
+                                           hipStream_t stream);
 
 /*
  * Out-of-place block step with the overflow test fused into the update: ONE pass of 28 bytes per

@@ -23,6 +23,7 @@ EXPORTS = (
     "lohan_workspace_bytes", "lohan_status_string", "lohan_grad_overflow_check",
     "lohan_grad_sqnorm", "lohan_grad_sqnorm_static", "lohan_grad_produce_fp16",
     "lohan_adam_block_step", "lohan_adam_block_step_clipped",
+    "lohan_adam_small_block_max_n", "lohan_adam_small_block_step",
     "lohan_adam_block_step_out_of_place", "lohan_adam_block_step_out_of_place_clipped",
     "lohan_adam_multi_block_step", "lohan_model_placement", "lohan_model_placement_compact",
     "lohan_tensor_placement",
@@ -30,6 +31,7 @@ EXPORTS = (
     "lohan_ring_adam_block_step_clipped", "lohan_ring_read",
     "lohan_clip_loss_scale", "lohan_workspace_init",
     "lohan_tuning_set_launch_config", "lohan_tuning_get_launch_config",
+    "lohan_tuning_set_wait_limit",
     "lohan_tuning_device_info", "lohan_tuning_probe", "lohan_tuning_offload_inject_failure",
     "lohan_tuning_offload_slot_times",
     "lohan_offload_slab_bytes", "lohan_offload_create", "lohan_offload_submit",
@@ -122,6 +124,14 @@ def load_library():
                                                   f32, ctypes.c_int64, f32, vp, f32, vp,
                                                   ctypes.c_uint32, vp, sz, vp]
     lib.lohan_adam_block_step_clipped.restype = ctypes.c_int
+    lib.lohan_adam_small_block_max_n.argtypes = [ctypes.POINTER(u64)]
+    lib.lohan_adam_small_block_max_n.restype = ctypes.c_int
+    lib.lohan_adam_small_block_step.argtypes = [vp, vp, vp, vp, vp, u64, f32, f32, f32, f32, f32,
+                                                ctypes.c_int64, f32, vp, vp, ctypes.c_uint32, vp,
+                                                sz, vp]
+    lib.lohan_adam_small_block_step.restype = ctypes.c_int
+    lib.lohan_tuning_set_wait_limit.argtypes = [ctypes.c_int64]
+    lib.lohan_tuning_set_wait_limit.restype = ctypes.c_int
     lib.lohan_adam_block_step_out_of_place.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u64, f32,
                                                        f32, f32, f32, f32, ctypes.c_int64, f32,
                                                        vp, ctypes.c_uint32, vp]
@@ -345,6 +355,30 @@ def lohan_adam_block_step_clipped(param_fp32, exp_avg, exp_avg_sq, grad_fp16, pa
         _stream(stream)))
 
 
+LOHAN_OVERFLOW_INCOMPLETE = 0x80000000
+
+
+def lohan_adam_small_block_max_n() -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lohan_adam_small_block_max_n(ctypes.byref(out)))
+    return out.value
+
+
+def lohan_adam_small_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n,
+                                lr, beta1, beta2, eps, weight_decay, step, loss_scale, sqnorm,
+                                overflow_flag, flags, workspace, workspace_bytes=None,
+                                stream=None):
+    ws, ws_bytes = _workspace(workspace, workspace_bytes)
+    _check(load_library().lohan_adam_small_block_step(
+        _addr(param_fp32, n, _F32, "param_fp32"), _addr(exp_avg, n, _F32, "exp_avg"),
+        _addr(exp_avg_sq, n, _F32, "exp_avg_sq"), _addr(grad_fp16, n, _F16, "grad_fp16"),
+        _addr(param_bf16_out, n, _BF16, "param_bf16_out"), int(n),
+        float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
+        float(loss_scale), None if sqnorm is None else _addr(sqnorm, 1, _F64, "sqnorm"),
+        _addr(overflow_flag, 1, _U32, "overflow_flag"), int(flags), ws, ws_bytes,
+        _stream(stream)))
+
+
 def lohan_adam_block_step_out_of_place(param_fp32_in, exp_avg_in, exp_avg_sq_in, grad_fp16,
                                        param_fp32_out, exp_avg_out, exp_avg_sq_out,
                                        param_bf16_out, n, lr, beta1, beta2, eps, weight_decay,
@@ -517,6 +551,12 @@ def lohan_tuning_set_launch_config(adam_variant=-1, adam_workgroups_per_cu=-1,
     _check(load_library().lohan_tuning_set_launch_config(
         int(adam_variant), int(adam_workgroups_per_cu), int(adam_waves_per_cu),
         int(reduce_workgroups_per_cu), int(reduce_policy)))
+
+
+def lohan_tuning_set_wait_limit(polls=-1):
+    """Bench/test-only: bound of the grid-wide wait of lohan_adam_small_block_step, in polls, for
+    the calling thread's later calls; negative = the built-in bound."""
+    _check(load_library().lohan_tuning_set_wait_limit(int(polls)))
 
 
 def lohan_tuning_get_launch_config():

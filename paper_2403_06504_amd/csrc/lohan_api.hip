@@ -21,6 +21,7 @@ constexpr int kMaxDevices = 64;
 struct DeviceSlot {
     std::atomic<int> cus{0};
     std::atomic<size_t> lds_per_cu{0};
+    std::atomic<int> small_wgs_per_cu[lohan::kSmallVariants];
 };
 DeviceSlot g_device[kMaxDevices];
 
@@ -39,6 +40,8 @@ constexpr int kDefaultAdamWgsPerCu = 0;                       // one tile per wo
 constexpr int kDefaultAdamWavesPerCu = 11;                    // occupancy throttle
 constexpr int kDefaultReduceWgsPerCu = 4;
 constexpr int kAutoReducePolicy = -1;
+// Polls of the grid-wide wait in the one-launch step before a workgroup gives up (about a second).
+constexpr uint32_t kDefaultWaitLimit = 1u << 20;
 
 // Tuning override (lohan_adam_tuning.h): per calling thread, so that a sweep on one thread never
 // changes the launch shape under calls made by another.
@@ -48,19 +51,23 @@ struct LaunchOverride {
     int adam_waves_per_cu = kDefaultAdamWavesPerCu;
     int reduce_wgs_per_cu = kDefaultReduceWgsPerCu;
     int reduce_policy = kAutoReducePolicy;
+    uint32_t wait_limit = kDefaultWaitLimit;
 };
 thread_local LaunchOverride t_launch;
 
 // Facts about the current device (the device `stream` must belong to).  cus == 0 on error.
 lohan::DeviceInfo current_device()
 {
-    lohan::DeviceInfo info{0, 0};
+    lohan::DeviceInfo info{};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return info;
     const bool cacheable = dev >= 0 && dev < kMaxDevices;
     if (cacheable) {
         info.cus = g_device[dev].cus.load(std::memory_order_acquire);
         info.lds_per_cu = g_device[dev].lds_per_cu.load(std::memory_order_relaxed);
+        for (int i = 0; i < lohan::kSmallVariants; ++i)
+            info.small_wgs_per_cu[i] =
+                g_device[dev].small_wgs_per_cu[i].load(std::memory_order_relaxed);
         if (info.cus > 0 && info.lds_per_cu > 0) return info;
     }
     int cus = 0, lds = 0;
@@ -69,10 +76,16 @@ lohan::DeviceInfo current_device()
         hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) !=
             hipSuccess ||
         lds <= 0)
-        return lohan::DeviceInfo{0, 0};
+        return lohan::DeviceInfo{};
     info.cus = cus;
     info.lds_per_cu = (size_t)lds;
+    // A device whose occupancy cannot be read simply has no one-launch step (capacity 0).
+    if (lohan::small_block_occupancy(info.small_wgs_per_cu) != hipSuccess)
+        for (int i = 0; i < lohan::kSmallVariants; ++i) info.small_wgs_per_cu[i] = 0;
     if (cacheable) {
+        for (int i = 0; i < lohan::kSmallVariants; ++i)
+            g_device[dev].small_wgs_per_cu[i].store(info.small_wgs_per_cu[i],
+                                                    std::memory_order_relaxed);
         g_device[dev].lds_per_cu.store(info.lds_per_cu, std::memory_order_relaxed);
         g_device[dev].cus.store(info.cus, std::memory_order_release);
     }
@@ -124,7 +137,7 @@ const char *lohan_status_string(lohan_status_t status)
     case LOHAN_ERR_WORKSPACE: return "workspace is smaller than lohan_workspace_bytes()";
     case LOHAN_ERR_HIP: return "the HIP runtime reported an error at launch";
     case LOHAN_ERR_TOO_LARGE:
-        return "n exceeds the maximum of the entry point that allocates nothing";
+        return "n exceeds the maximum this entry point takes";
     default: return "unknown status";
     }
 }
@@ -310,6 +323,44 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
     e = lohan::launch_adam_block_step(param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out,
                                       n, s, kernel_mode(flags), overflow_flag, inv_dev,
                                       adam_launch_for(n), dev, stream);
+    return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
+}
+
+lohan_status_t lohan_adam_small_block_max_n(uint64_t *max_n)
+{
+    if (max_n == nullptr) return LOHAN_ERR_NULL;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
+    *max_n = lohan::small_block_max_n(dev);
+    return LOHAN_OK;
+}
+
+lohan_status_t lohan_adam_small_block_step(float *param_fp32, float *exp_avg, float *exp_avg_sq,
+                                           const void *grad_fp16, void *param_bf16_out,
+                                           uint64_t n, float lr, float beta1, float beta2,
+                                           float eps, float weight_decay, int64_t step,
+                                           float loss_scale, double *sqnorm,
+                                           uint32_t *overflow_flag, uint32_t flags,
+                                           void *workspace, size_t workspace_bytes,
+                                           hipStream_t stream)
+{
+    lohan_status_t st = validate_step_args(param_fp32, exp_avg, exp_avg_sq, grad_fp16,
+                                           param_bf16_out, n, lr, beta1, beta2, eps, weight_decay,
+                                           step, loss_scale, overflow_flag, flags);
+    if (st != LOHAN_OK) return st;
+    if ((flags & LOHAN_FLAG_PRECHECKED) != 0) return LOHAN_ERR_ARG;
+    if (misaligned(sqnorm, 8)) return LOHAN_ERR_ALIGN;
+    st = check_workspace(workspace, workspace_bytes);
+    if (st != LOHAN_OK) return st;
+    const lohan::DeviceInfo dev = current_device();
+    if (dev.cus <= 0) return LOHAN_ERR_HIP;
+    if (n > lohan::small_block_max_n(dev)) return LOHAN_ERR_TOO_LARGE;
+    const lohan::StepScalars s =
+        make_step_scalars(lr, beta1, beta2, eps, weight_decay, step, loss_scale);
+    const double inv = 1.0 / (double)loss_scale;
+    hipError_t e = lohan::launch_adam_small_block_step(
+        param_fp32, exp_avg, exp_avg_sq, grad_fp16, param_bf16_out, n, s, kernel_mode(flags),
+        inv * inv, sqnorm, overflow_flag, workspace, t_launch.wait_limit, dev, stream);
     return e == hipSuccess ? LOHAN_OK : LOHAN_ERR_HIP;
 }
 
@@ -922,6 +973,13 @@ lohan_status_t lohan_tuning_set_launch_config(int adam_variant, int adam_workgro
     t_launch.reduce_wgs_per_cu = reduce_workgroups_per_cu <= 0 ? kDefaultReduceWgsPerCu
                                                                : reduce_workgroups_per_cu;
     t_launch.reduce_policy = reduce_policy < 0 ? kAutoReducePolicy : reduce_policy;
+    return LOHAN_OK;
+}
+
+lohan_status_t lohan_tuning_set_wait_limit(int64_t polls)
+{
+    if (polls > (int64_t)0xFFFFFFFFll) return LOHAN_ERR_ARG;
+    t_launch.wait_limit = polls < 0 ? kDefaultWaitLimit : (uint32_t)polls;
     return LOHAN_OK;
 }
 

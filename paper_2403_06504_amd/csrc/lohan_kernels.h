@@ -87,24 +87,55 @@ inline RingView ring_view(void *ring, uint32_t num_blocks, uint32_t num_spares)
 // scalars: kMultiMaxBlocks unscale factors (float; a single-block clipped step uses the first),
 // then kMultiMaxBlocks squared norms (double) for multi-block calls whose caller wants none,
 // then kMultiMaxBlocks uint32 ticket counters of the gradient reduction (a single-block call uses
-// the first), then a 64-bit word that holds kWorkspaceMagic once the workspace has been prepared.
-// The counters are the only part with an invariant: zero between calls (launch_workspace_init
-// sets it up, every reduction restores it); the magic word lets the kernels tell a workspace that
-// was never prepared, whose counters may hold anything.
+// the first), then a 64-bit word that holds kWorkspaceMagic once the workspace has been prepared,
+// then kGroupLines lines of kLineBytes each: word 0 of a line is the ticket counter of one group
+// of kGroupSize workgroups (the first level of the two-level ticket), word kVerdictWord of a line
+// receives the verdict of the one-launch step's grid-wide barrier for that group, and the last
+// line holds that step's call counter (word 0) and its "somebody gave up waiting" mark (word 1).
+// Invariants: all ticket counters are zero between calls (launch_workspace_init sets them up,
+// every call restores them); the magic word lets the kernels tell a workspace that was never
+// prepared, whose counters may hold anything.
 constexpr uint32_t kMaxPartials = 4096;
 constexpr size_t kScalarsOffset = (size_t)kMaxPartials * (sizeof(double) + sizeof(uint32_t));
 constexpr size_t kNormsOffset = kScalarsOffset + 256;
 constexpr size_t kCountersOffset = kNormsOffset + kMultiMaxBlocks * sizeof(double);
 constexpr size_t kMagicOffset = kCountersOffset + kMultiMaxBlocks * sizeof(uint32_t);
-constexpr size_t kWorkspaceBytes = kMagicOffset + 16;
+constexpr uint32_t kGroupSize = 32;
+constexpr uint32_t kLineBytes = 128;
+constexpr uint32_t kLineWords = kLineBytes / sizeof(uint32_t);
+constexpr uint32_t kVerdictWord = 16;
+constexpr uint32_t kGroupLines = 256;
+constexpr uint32_t kCallLine = kGroupLines - 1;
+constexpr size_t kLinesOffset = (kMagicOffset + 16 + kLineBytes - 1) / kLineBytes * kLineBytes;
+constexpr size_t kWorkspaceBytes = kLinesOffset + (size_t)kGroupLines * kLineBytes;
 constexpr uint64_t kWorkspaceMagic = 0x4C6F48616E57531Full;
+// A single-block call has at most kMaxPartials / kGroupSize groups; a multi-block call at most
+// that plus one partly filled group per block; the last line is not a group's.
+static_assert(kMaxPartials / kGroupSize + kMultiMaxBlocks < kCallLine, "group lines");
 static_assert(kMultiMaxBlocks * sizeof(float) <= 256, "unscale factors must fit their area");
+
+// The one-launch step for small blocks holds the block in registers: kSmallDepths[i] tiles of
+// kSmallTile elements per workgroup, one kernel instantiation per depth (deeper = more registers
+// per lane, fewer workgroups resident per compute unit).
+constexpr int kSmallVariants = 3;
+constexpr int kSmallDepths[kSmallVariants] = {3, 7, 15};
+constexpr uint64_t kSmallTile = 1024;
+// Bit of the overflow flag that reports a grid-wide wait that was given up (state unspecified).
+constexpr uint32_t kFlagIncomplete = 0x80000000u;
 
 // What the launchers need to know about the device the stream belongs to.
 struct DeviceInfo {
     int cus;             // compute units
     size_t lds_per_cu;   // bytes of LDS per compute unit (sizes the occupancy throttle)
+    int small_wgs_per_cu[kSmallVariants];  // resident workgroups per CU of each small-block depth
 };
+
+// Fills small_wgs_per_cu from the occupancy the runtime reports for the kernels (the lowest over
+// the modes of a depth).
+hipError_t small_block_occupancy(int wgs_per_cu[kSmallVariants]);
+
+// Largest n the one-launch step takes on this device (0 if none of the kernels fits).
+uint64_t small_block_max_n(const DeviceInfo &dev);
 
 // Zero the ticket counters of a workspace and set its magic word (a one-workgroup fill kernel).
 hipError_t launch_workspace_init(void *workspace, hipStream_t stream);
@@ -151,6 +182,15 @@ hipError_t launch_adam_ring_step(const RingView &ring, uint32_t block, const voi
                                  uint64_t n, const StepScalars &s, int mode,
                                  const float *inv_override, const AdamLaunch &cfg,
                                  const DeviceInfo &dev, hipStream_t stream);
+
+// One-launch step for a block of at most small_block_max_n(dev) elements (hipErrorInvalidValue
+// beyond): flag, squared norm (sqnorm may be NULL) and update.  spin_limit bounds the grid-wide
+// wait in polls.
+hipError_t launch_adam_small_block_step(float *p, float *m, float *v, const void *grad_fp16,
+                                        void *p16, uint64_t n, const StepScalars &s, int mode,
+                                        double inv2, double *sqnorm, uint32_t *flag,
+                                        void *workspace, uint32_t spin_limit,
+                                        const DeviceInfo &dev, hipStream_t stream);
 
 // sqnorm[0..count) -> inv_out[0..count)
 hipError_t launch_clip_scale(const double *sqnorm, float loss_scale, float max_norm,

@@ -153,6 +153,34 @@ __device__ __forceinline__ uint32_t zero_after(uint32_t a, uint32_t b)
     return z;
 }
 
+// Tickets in two levels.  Atomics on one address are performed one after the other, some 12 ns
+// apiece, so a thousand workgroups drawing from one counter spend 12 us queueing -- most of what
+// a reduction over a small block costs.  Instead, workgroup wg draws from the counter of its
+// group of kGroupSize consecutive workgroups (one 128-byte line per group, so that groups do not
+// queue behind each other), and only the workgroup that draws a group's last ticket draws from
+// the call's top counter.  Returns true in exactly one workgroup of the nwg: the one after which
+// nobody else arrives.  dep: a value the first increment must wait for (pass zero_after(...)).
+// base: the workspace; line_base: first group line of this block; top: this block's counter.
+__device__ __forceinline__ bool take_ticket(uint32_t wg, uint32_t nwg, void *base,
+                                            uint32_t line_base, uint32_t *top, uint32_t dep)
+{
+    if (nwg <= kGroupSize)                                   // one group: the top counter will do
+        return __hip_atomic_fetch_add(top, 1u + dep, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT) == nwg - 1;
+    const uint32_t group = wg / kGroupSize;
+    const uint32_t ngroups = (nwg + kGroupSize - 1) / kGroupSize;
+    const uint32_t rest = nwg - group * kGroupSize;
+    const uint32_t members = rest < kGroupSize ? rest : kGroupSize;
+    uint32_t *line = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(base) + kLinesOffset) +
+                     (size_t)(line_base + group) * kLineWords;
+    if (__hip_atomic_fetch_add(line, 1u + dep, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) !=
+        members - 1)
+        return false;
+    st_device_scope(line, 0u);                               // nobody else comes to this group
+    return __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+           ngroups - 1;
+}
+
 // Sum / OR over the workgroup: wavefront butterfly over the 64 lanes (fixed pairing), then LDS
 // across the wavefronts in index order.  The totals are valid in thread 0.
 template <bool WITH_NORM>
@@ -203,7 +231,7 @@ __device__ __forceinline__ void reduce_publish_and_finish(uint32_t tid, double a
 
     // Publish this workgroup's partial, then take a ticket.  The ticket's increment consumes what
     // the publishing exchanges returned, so it is issued only once the partial is in place: whoever
-    // draws a later ticket finds it.
+    // draws a later ticket (of the group, and then of the call) finds it.
     __shared__ uint32_t s_is_last;
     if (tid == 0) {
         uint32_t seen = 0;
@@ -212,10 +240,12 @@ __device__ __forceinline__ void reduce_publish_and_finish(uint32_t tid, double a
             seen = (uint32_t)__builtin_bit_cast(uint64_t, old);
         }
         const uint32_t old_flag = publish_device_scope(partial_flag + slot_base + wg, ovf);
-        const uint32_t ticket =
-            __hip_atomic_fetch_add(counter, 1u + zero_after(seen, old_flag), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-        s_is_last = ticket == nwg - 1 ? 1u : 0u;
+        // partial_sum is the workspace's first byte; block b of a multi-block launch (slot_base =
+        // b * nwg) has the b-th run of group lines.
+        const uint32_t groups_per_block = (nwg + kGroupSize - 1) / kGroupSize;
+        const bool last = take_ticket(wg, nwg, partial_sum, slot_base / nwg * groups_per_block,
+                                      counter, zero_after(seen, old_flag));
+        s_is_last = last ? 1u : 0u;
     }
     __syncthreads();
     if (s_is_last == 0u) return;
@@ -419,12 +449,14 @@ __global__ __launch_bounds__(kReduceThreads) void k_grad_produce(
                                          counter, inv2, sqnorm_out, flag_out);
 }
 
-// Ticket counters start at zero; afterwards every reduction leaves them at zero.  The magic word
-// marks the workspace as prepared.
-__global__ void k_workspace_init(uint32_t *counters, uint32_t count, uint64_t *magic)
+// Ticket counters (per block and per group) start at zero; afterwards every call leaves them at
+// zero.  The magic word marks the workspace as prepared.
+__global__ void k_workspace_init(uint32_t *counters, uint32_t count, uint32_t *lines,
+                                 uint32_t line_words, uint64_t *magic)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) counters[i] = 0u;
+    if (i < line_words) lines[i] = 0u;
     if (i == 0) *magic = kWorkspaceMagic;
 }
 
@@ -800,6 +832,331 @@ __global__ void k_clip_scale(const double *__restrict__ sqnorm, float loss_scale
 }
 
 // ------------------------------------------------------------------------------------------------
+// Small blocks: flag, norm and update in ONE launch, the block's state held in registers.
+//
+// For a block of a few million elements the two-launch step is a chain of latencies (a reduction
+// of dependent round trips, a launch gap, then 27 thousand one-tile workgroups).  Here the whole
+// grid is resident at once.  Every workgroup loads its share of the gradients (K tiles), reduces
+// them and arrives at a grid-wide barrier; then it loads its share of p, m, v into registers --
+// every load issued before anything is consumed -- and computes the update in registers while
+// the barrier completes; then it learns the verdict and stores.  Bytes moved: the 28 per element
+// of the update alone, and the chip's reads and writes separate into two phases.
+//
+// The barrier is the two-level ticket above with the overflow flag folded in: the low half of a
+// counter counts arrivals, the high half counts arrivals that saw an overflow, so the one atomic
+// a workgroup issues to arrive is also its contribution to the flag.  The workgroup that arrives
+// last writes the verdict into every group's line, tagged with the number of this call; the
+// others poll their own group's line (32 pollers per address instead of a thousand).  Tags make
+// resetting unnecessary: a line left over from an earlier call never matches.
+//
+// The wait is bounded: a workgroup that does not see the verdict within spin_limit polls marks
+// the call as incomplete, looks once more, and otherwise ends without writing; the workgroup
+// that arrives last reads that mark after publishing the verdict and reports it in the flag
+// (kFlagIncomplete).  Mark-then-look on one side and publish-then-read on the other mean that a
+// workgroup which ends without writing is always reported.  Every wavefront exits whatever
+// happens.  The host sizes the grid to what the device holds at once, so the wait is over before
+// the update has been computed unless other kernels occupy the compute units; those finish by
+// themselves.
+// ------------------------------------------------------------------------------------------------
+
+constexpr int kFusedThreads = 256;
+constexpr int kFusedWaves = kFusedThreads / 64;
+constexpr uint64_t kFusedTile = (uint64_t)kFusedThreads * 4;
+constexpr uint32_t kArrivedMask = 0xFFFFu;
+constexpr uint32_t kOverflowUnit = 0x10000u;
+constexpr uint32_t kLastTag = 0x7FFFFFFEu;
+static_assert(kMaxPartials <= kArrivedMask, "the arrival count must fit the counter's low half");
+
+// Workgroup barrier that orders LDS traffic only: the global loads in flight stay in flight.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Sum over the workgroup in a fixed order (butterfly within each wavefront, then the wavefronts
+// in index order); every lane gets the total.  area: kFusedWaves doubles of LDS, not reused
+// before the next barrier.
+__device__ __forceinline__ double fused_workgroup_sum(uint32_t tid, double acc, double *area)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if ((tid & 63u) == 0u) area[tid >> 6] = acc;
+    lds_barrier();
+    double total = 0.0;
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) total += area[w];
+    return total;
+}
+
+// The elements past the last whole tile (fewer than kFusedTile): lane `tid` takes elements
+// tail_start + tid, + kFusedThreads, ... one at a time.
+__device__ __forceinline__ void fused_tail_reduce(const uint16_t *__restrict__ g,
+                                                  uint64_t tail_start, uint64_t n, uint32_t tid,
+                                                  uint32_t &ovf, double &acc)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint64_t i = tail_start + (uint64_t)j * kFusedThreads + tid;
+        if (i < n) {
+            const uint32_t h = g[i];
+            ovf = overflow_bits(h, ovf);
+            acc += (double)square_pair(h, 0.0f);
+        }
+    }
+}
+
+template <bool L2, bool HALF_OUT>
+__device__ __forceinline__ void fused_tail_update(float *__restrict__ p, float *__restrict__ m,
+                                                  float *__restrict__ v,
+                                                  const uint16_t *__restrict__ g,
+                                                  uint16_t *__restrict__ p16, uint64_t tail_start,
+                                                  uint64_t n, uint32_t tid, const StepScalars &s)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint64_t i = tail_start + (uint64_t)j * kFusedThreads + tid;
+        if (i < n) {
+            const _Float16 gh = __builtin_bit_cast(_Float16, g[i]);
+            float pe = p[i], me = m[i], ve = v[i];
+            adam_elem<L2>(pe, me, ve, (float)gh, s);
+            p[i] = pe;
+            m[i] = me;
+            v[i] = ve;
+            p16[i] = (uint16_t)pack16<HALF_OUT>(pe, 0.0f);
+        }
+    }
+}
+
+// What lane 0 of a workgroup knows after arriving.
+constexpr uint32_t kOverflowed = 1u, kGaveUp = 2u, kArrivedLast = 4u, kVerdictKnown = 8u;
+
+// Lane 0 of wavefront 0: publish the partial sum, arrive (two levels), and report what is known.
+// counters[0] is the call's top counter; lines: the group lines.  any: this workgroup saw an
+// overflow; tag: this call's.  Returns kArrivedLast (| kOverflowed) in the workgroup after which nobody arrives.
+__device__ __forceinline__ uint32_t fused_arrive(uint32_t wg, uint32_t nwg, double part, bool any,
+                                                 double *partial_sum, uint32_t *counters,
+                                                 uint32_t *lines, uint32_t tag)
+{
+    // The arrival waits for the partial sum to be in place and for the call's tag to have been
+    // read: after the last arrival the call counter moves on.
+    const uint64_t old = __builtin_bit_cast(uint64_t, publish_device_scope(partial_sum + wg, part));
+    const uint32_t add = 1u + (any ? kOverflowUnit : 0u) +
+                         zero_after((uint32_t)old, (uint32_t)(old >> 32)) + zero_after(tag, tag);
+    uint32_t now;
+    if (nwg <= kGroupSize) {
+        now = __hip_atomic_fetch_add(counters, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) +
+              add;
+        if ((now & kArrivedMask) != nwg) return 0u;
+    } else {
+        const uint32_t group = wg / kGroupSize;
+        const uint32_t ngroups = (nwg + kGroupSize - 1) / kGroupSize;
+        const uint32_t rest = nwg - group * kGroupSize;
+        const uint32_t members = rest < kGroupSize ? rest : kGroupSize;
+        uint32_t *line = lines + (size_t)group * kLineWords;
+        now = __hip_atomic_fetch_add(line, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+        if ((now & kArrivedMask) != members) return 0u;
+        st_device_scope(line, 0u);
+        const uint32_t add2 = 1u + ((now >> 16) != 0u ? kOverflowUnit : 0u);
+        now = __hip_atomic_fetch_add(counters, add2, __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT) + add2;
+        if ((now & kArrivedMask) != ngroups) return 0u;
+    }
+    st_device_scope(counters, 0u);
+    return kArrivedLast | kVerdictKnown | ((now >> 16) != 0u ? kOverflowed : 0u);
+}
+
+template <int K, int MODE>
+__global__ __launch_bounds__(kFusedThreads) void k_adam_small_block_step(
+    float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
+    const uint16_t *__restrict__ g, uint16_t *__restrict__ p16, uint64_t n, StepScalars s,
+    double *partial_sum, uint32_t *counters, uint32_t *lines,
+    const uint64_t *__restrict__ magic, double inv2, double *__restrict__ sqnorm, uint32_t *flag,
+    uint32_t spin_limit)
+{
+    if (workspace_unprepared(magic, sqnorm, flag)) return;
+    constexpr bool L2 = (MODE & 1) != 0, HALF_OUT = (MODE & 2) != 0;
+    __shared__ double s_sum[2][kFusedWaves];
+    __shared__ uint32_t s_ovf[kFusedWaves];
+    __shared__ uint32_t s_verdict;
+
+    const uint32_t tid = threadIdx.x, wg = blockIdx.x, nwg = gridDim.x;
+    const uint64_t ntiles = n / kFusedTile;                 // whole tiles; the rest is the tail
+    const uint64_t tail_start = ntiles * kFusedTile;
+    const uint64_t lane_off = (uint64_t)tid * 4;
+
+    if (ntiles == 0) {
+        // Less than one tile: one workgroup does it all and there is nobody to wait for.
+        if (wg != 0) return;
+        uint32_t ovf = 0;
+        double acc = 0.0;
+        fused_tail_reduce(g, 0, n, tid, ovf, acc);
+        const bool wave_ovf = __builtin_amdgcn_ballot_w64(ovf != 0u) != 0;
+        if ((tid & 63u) == 0u) s_ovf[tid >> 6] = wave_ovf ? 1u : 0u;
+        const double total = fused_workgroup_sum(tid, acc, s_sum[0]);
+        uint32_t any = 0;
+#pragma unroll
+        for (int w = 0; w < kFusedWaves; ++w) any |= s_ovf[w];
+        if (any == 0u) fused_tail_update<L2, HALF_OUT>(p, m, v, g, p16, 0, n, tid, s);
+        if (tid == 0) {
+            if (sqnorm != nullptr) *sqnorm = total * inv2;
+            *flag = any;
+        }
+        return;
+    }
+
+    // The call's tag: one more than the call counter that the previous call left behind.
+    uint32_t *call_line = lines + (size_t)kCallLine * kLineWords;
+    uint32_t tag = ld_device_scope(call_line) + 1u;
+    if (tag > kLastTag) tag = 1u;
+    const uint32_t nlines = (nwg + kGroupSize - 1) / kGroupSize;
+    uint32_t *my_verdict = lines + (size_t)(wg / kGroupSize) * kLineWords + kVerdictWord;
+
+    // Gradients: tile k of this workgroup is tile k * nwg + wg of the block (so that the grid
+    // reads each of the K rounds as one contiguous span).  A tile index past the end is clamped
+    // to the last tile: the load is then redundant but in bounds and unconditional, and its
+    // values are never used.
+    u32x2 gv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        uint64_t tile = (uint64_t)k * nwg + wg;
+        if (tile >= ntiles) tile = ntiles - 1;
+        gv[k] = *reinterpret_cast<const u32x2 *>(g + tile * kFusedTile + lane_off);
+    }
+    uint32_t ovf = 0;
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const bool valid = (uint64_t)k * nwg + wg < ntiles;
+        const uint32_t x = valid ? gv[k].x : 0u, y = valid ? gv[k].y : 0u;
+        ovf = overflow_bits(x, ovf);
+        ovf = overflow_bits(y, ovf);
+        float sq = square_pair(x, 0.0f);
+        sq = square_pair(y, sq);
+        acc += (double)sq;
+    }
+    if (wg == 0) fused_tail_reduce(g, tail_start, n, tid, ovf, acc);
+    const bool wave_ovf = __builtin_amdgcn_ballot_w64(ovf != 0u) != 0;
+    if ((tid & 63u) == 0u) s_ovf[tid >> 6] = wave_ovf ? 1u : 0u;
+    const double part = fused_workgroup_sum(tid, acc, s_sum[0]);
+
+    // Wavefront 0 arrives before it issues its share of the big loads (the results of its atomics
+    // would otherwise queue behind them); the other wavefronts go straight on.  In the workgroup
+    // that arrives last the wavefront also publishes the verdict, one lane per group line, and
+    // only then looks for the mark of a workgroup that gave up: see the header comment.
+    uint32_t state = 0;
+    if (tid < 64u) {
+        if (tid == 0) {
+            uint32_t any = 0;
+#pragma unroll
+            for (int w = 0; w < kFusedWaves; ++w) any |= s_ovf[w];
+            state = fused_arrive(wg, nwg, part, any != 0u, partial_sum, counters, lines, tag);
+        }
+        state = __builtin_amdgcn_readfirstlane(state);
+        if ((state & kArrivedLast) != 0u) {
+            const uint32_t word = (tag << 1) | (state & kOverflowed);
+            uint32_t seen = 0;
+            for (uint32_t l = tid; l < nlines; l += 64u)
+                seen |= publish_device_scope(lines + (size_t)l * kLineWords + kVerdictWord, word);
+            if (tid == 0) {
+                const uint32_t mark = ld_device_scope(call_line + 1 + zero_after(seen, seen));
+                *flag = (state & kOverflowed) | (mark == tag ? kFlagIncomplete : 0u);
+                st_device_scope(call_line, tag);
+            }
+        } else if (tid == 0 && spin_limit == 0u) {
+            // No waiting allowed at all (a test of the give-up path): decide here, before the
+            // update is computed, while the verdict is most likely still out.
+            const uint32_t old = publish_device_scope(call_line + 1, tag);
+            const uint32_t word = ld_device_scope(my_verdict + zero_after(old, old));
+            state = (word >> 1) == tag ? (kVerdictKnown | (word & kOverflowed)) : kGaveUp;
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // The state, every load issued before anything below consumes one.
+    f32x4 pv[K], mv[K], vv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        uint64_t tile = (uint64_t)k * nwg + wg;
+        if (tile >= ntiles) tile = ntiles - 1;
+        const uint64_t off = tile * kFusedTile + lane_off;
+        pv[k] = *reinterpret_cast<const f32x4 *>(p + off);
+        mv[k] = *reinterpret_cast<const f32x4 *>(m + off);
+        vv[k] = *reinterpret_cast<const f32x4 *>(v + off);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // The update, in registers (wasted if the verdict turns out to be an overflow, which is
+    // rare), tile by tile in the order the loads were issued.  The empty asm makes the results
+    // exist HERE, ahead of the wait: left alone, the compiler sinks the whole computation into
+    // the branch that stores them, behind the verdict.
+    u32x2 hv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        adam_vec4<L2, HALF_OUT>(pv[k], mv[k], vv[k], __builtin_bit_cast(f16x4, gv[k]), s, hv[k]);
+        asm volatile("" : "+v"(pv[k]), "+v"(mv[k]), "+v"(vv[k]), "+v"(hv[k]));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    asm volatile("" ::: "memory");
+
+    // The verdict: by now it is normally there.
+    if (tid == 0) {
+        if ((state & (kVerdictKnown | kGaveUp)) == 0u) {
+            uint32_t word = 0;
+            bool there = false;
+            for (uint32_t poll = 0; poll < spin_limit && !there; ++poll) {
+                word = ld_device_scope(my_verdict);
+                there = (word >> 1) == tag;
+                if (!there) __builtin_amdgcn_s_sleep(8);
+            }
+            if (!there) {
+                const uint32_t old = publish_device_scope(call_line + 1, tag);
+                word = ld_device_scope(my_verdict + zero_after(old, old));
+                there = (word >> 1) == tag;
+            }
+            state |= there ? (kVerdictKnown | (word & kOverflowed)) : kGaveUp;
+        }
+        s_verdict = state;
+    }
+    lds_barrier();
+    const uint32_t verdict = s_verdict;
+
+    // Skip rule: with the flag set nothing is written.
+    if ((verdict & (kOverflowed | kGaveUp)) == 0u) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint64_t tile = (uint64_t)k * nwg + wg;
+            if (tile < ntiles) {
+                const uint64_t off = tile * kFusedTile + lane_off;
+                *reinterpret_cast<f32x4 *>(p + off) = pv[k];
+                *reinterpret_cast<f32x4 *>(m + off) = mv[k];
+                *reinterpret_cast<f32x4 *>(v + off) = vv[k];
+                *reinterpret_cast<u32x2 *>(p16 + off) = hv[k];
+            }
+        }
+        if (wg == 0) fused_tail_update<L2, HALF_OUT>(p, m, v, g, p16, tail_start, n, tid, s);
+    }
+
+    // The workgroup that arrived last combines the partial sums in a fixed order, with its stores
+    // already under way.
+    if ((verdict & kArrivedLast) != 0u && sqnorm != nullptr) {
+        constexpr uint32_t kRounds = kMaxPartials / kFusedThreads;
+        double mine[kRounds];
+#pragma unroll
+        for (uint32_t j = 0; j < kRounds; ++j) {
+            const uint32_t i = j * kFusedThreads + tid;
+            mine[j] = i < nwg ? ld_device_scope(partial_sum + i) : 0.0;
+        }
+        double total = 0.0;
+#pragma unroll
+        for (uint32_t j = 0; j < kRounds; ++j) total += mine[j];
+        total = fused_workgroup_sum(tid, total, s_sum[1]);
+        if (tid == 0) *sqnorm = total * inv2;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Host-side launchers (no validation here: the C ABI layer has done it).
 // ------------------------------------------------------------------------------------------------
 
@@ -816,6 +1173,7 @@ struct WorkspaceView {
     uint32_t *partial_flag;
     uint32_t *counters;
     uint64_t *magic;
+    uint32_t *lines;
 };
 
 static WorkspaceView workspace_view(void *workspace)
@@ -824,14 +1182,17 @@ static WorkspaceView workspace_view(void *workspace)
     return WorkspaceView{reinterpret_cast<double *>(base),
                          reinterpret_cast<uint32_t *>(base + sizeof(double) * kMaxPartials),
                          reinterpret_cast<uint32_t *>(base + kCountersOffset),
-                         reinterpret_cast<uint64_t *>(base + kMagicOffset)};
+                         reinterpret_cast<uint64_t *>(base + kMagicOffset),
+                         reinterpret_cast<uint32_t *>(base + kLinesOffset)};
 }
 
 hipError_t launch_workspace_init(void *workspace, hipStream_t stream)
 {
     const WorkspaceView ws = workspace_view(workspace);
-    hipLaunchKernelGGL(k_workspace_init, dim3(1), dim3(64), 0, stream, ws.counters,
-                       kMultiMaxBlocks, ws.magic);
+    constexpr uint32_t kWords = kGroupLines * kLineWords;
+    static_assert(kWords >= kMultiMaxBlocks, "one thread per word covers the counters too");
+    hipLaunchKernelGGL(k_workspace_init, dim3(kWords / 256), dim3(256), 0, stream, ws.counters,
+                       kMultiMaxBlocks, ws.lines, kWords, ws.magic);
     return hipGetLastError();
 }
 
@@ -1110,6 +1471,99 @@ hipError_t launch_adam_block_step(float *p, float *m, float *v, const void *grad
                        reinterpret_cast<const uint16_t *>(grad_fp16),
                        reinterpret_cast<uint16_t *>(p16), n, s, flag, inv_override);
     return hipGetLastError();
+}
+
+typedef void (*adam_small_kernel_t)(float *, float *, float *, const uint16_t *, uint16_t *,
+                                    uint64_t, StepScalars, double *, uint32_t *, uint32_t *,
+                                    const uint64_t *, double, double *, uint32_t *, uint32_t);
+
+template <int K>
+static adam_small_kernel_t small_kernel_of_depth(int mode)
+{
+    switch (mode & 3) {
+    case 0: return k_adam_small_block_step<K, 0>;
+    case 1: return k_adam_small_block_step<K, 1>;
+    case 2: return k_adam_small_block_step<K, 2>;
+    default: return k_adam_small_block_step<K, 3>;
+    }
+}
+
+static adam_small_kernel_t small_kernel(int depth_index, int mode)
+{
+    static_assert(kSmallTile == kFusedTile, "the header's tile is the kernel's");
+    switch (depth_index) {
+    case 0: return small_kernel_of_depth<kSmallDepths[0]>(mode);
+    case 1: return small_kernel_of_depth<kSmallDepths[1]>(mode);
+    default: return small_kernel_of_depth<kSmallDepths[2]>(mode);
+    }
+}
+
+constexpr int kSmallMaxWgsPerCu = 7;
+
+hipError_t small_block_occupancy(int wgs_per_cu[kSmallVariants])
+{
+    for (int i = 0; i < kSmallVariants; ++i) {
+        int lowest = 0;
+        for (int mode = 0; mode < 4; ++mode) {
+            int resident = 0;
+            hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                &resident, reinterpret_cast<const void *>(small_kernel(i, mode)), kFusedThreads, 0);
+            if (e != hipSuccess) return e;
+            if (mode == 0 || resident < lowest) lowest = resident;
+        }
+        // Measured: a grid that needs every wavefront slot of every compute unit (8 workgroups
+        // of 4 wavefronts) is NOT resident all at once although the runtime reports it as
+        // fitting; 7 workgroups per compute unit are.  Never count on the last slot.
+        if (lowest > kSmallMaxWgsPerCu) lowest = kSmallMaxWgsPerCu;
+        wgs_per_cu[i] = lowest;
+    }
+    return hipSuccess;
+}
+
+// Workgroups of depth i that are resident together on the whole device.
+static uint64_t small_block_grid_limit(const DeviceInfo &dev, int i)
+{
+    uint64_t resident = (uint64_t)dev.cus * (uint64_t)(dev.small_wgs_per_cu[i] > 0 ? dev.small_wgs_per_cu[i] : 0);
+    return resident < kMaxPartials ? resident : kMaxPartials;
+}
+
+uint64_t small_block_max_n(const DeviceInfo &dev)
+{
+    uint64_t best = 0;
+    for (int i = 0; i < kSmallVariants; ++i) {
+        const uint64_t tiles = small_block_grid_limit(dev, i) * (uint64_t)kSmallDepths[i];
+        if (tiles > best) best = tiles;
+    }
+    return best == 0 ? 0 : best * kSmallTile + (kSmallTile - 1);
+}
+
+hipError_t launch_adam_small_block_step(float *p, float *m, float *v, const void *grad_fp16,
+                                        void *p16, uint64_t n, const StepScalars &s, int mode,
+                                        double inv2, double *sqnorm, uint32_t *flag,
+                                        void *workspace, uint32_t spin_limit,
+                                        const DeviceInfo &dev, hipStream_t stream)
+{
+    if (n == 0) {
+        hipLaunchKernelGGL(k_grad_empty, dim3(1), dim3(64), 0, stream, sqnorm, flag);
+        return hipGetLastError();
+    }
+    // The shallowest depth that holds the block: most wavefronts per CU, fewest registers.  The
+    // grid is as small as that depth allows, so that every workgroup's K slots are in use.
+    const uint64_t ntiles = n / kSmallTile;
+    for (int i = 0; i < kSmallVariants; ++i) {
+        const uint64_t limit = small_block_grid_limit(dev, i);
+        const uint64_t depth = (uint64_t)kSmallDepths[i];
+        if (limit == 0 || limit * depth < ntiles) continue;
+        uint64_t grid = (ntiles + depth - 1) / depth;
+        if (grid < 1) grid = 1;
+        const WorkspaceView ws = workspace_view(workspace);
+        hipLaunchKernelGGL(small_kernel(i, mode), dim3((uint32_t)grid), dim3(kFusedThreads), 0,
+                           stream, p, m, v, reinterpret_cast<const uint16_t *>(grad_fp16),
+                           reinterpret_cast<uint16_t *>(p16), n, s, ws.partial_sum, ws.counters,
+                           ws.lines, ws.magic, inv2, sqnorm, flag, spin_limit);
+        return hipGetLastError();
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_adam_block_step_oop(const float *p_in, const float *m_in, const float *v_in,

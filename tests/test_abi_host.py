@@ -163,6 +163,32 @@ def test_clipped_step_validation_returns_before_any_launch(lib):
     assert status(wsb=ws_bytes - 1) == 4
 
 
+def test_small_block_step_validation_returns_before_any_launch(lib):
+    ws_bytes = lib.lohan_workspace_bytes()
+
+    def status(p=A, m=A * 2, v=A * 3, g=A * 4, p16=A * 5, sqnorm=A * 8, flag=A * 6, ws=A * 7,
+               wsb=ws_bytes, flags=0, step=1, loss_scale=1024.0, **over):
+        h = dict(GOOD, **over)
+        return lib.lohan_adam_small_block_step(
+            p, m, v, g, p16, 16, h["lr"], h["beta1"], h["beta2"], h["eps"], h["weight_decay"],
+            step, loss_scale, sqnorm, flag, flags, ws, wsb, None)
+
+    for name in ("p", "m", "v", "g", "p16", "flag", "ws"):
+        assert status(**{name: None}) == 1, name
+    for name in ("p", "m", "v", "g", "p16", "ws"):
+        assert status(**{name: A * 10 + 8}) == 2, name
+    assert status(flag=A * 6 + 2) == 2 and status(sqnorm=A * 8 + 4) == 2
+    assert status(flags=2) == 3                  # a known flag belongs to the two-call step
+    assert status(flags=8) == 3 and status(step=0) == 3
+    for bad in (0.0, -1.0, math.inf, math.nan):
+        assert status(loss_scale=bad) == 3
+    assert status(beta1=1.0) == 3 and status(lr=-1.0) == 3 and status(eps=math.nan) == 3
+    assert status(wsb=ws_bytes - 1) == 4
+    assert lib.lohan_adam_small_block_max_n(None) == 1
+    assert lib.lohan_tuning_set_wait_limit(1 << 32) == 3
+    assert lib.lohan_tuning_set_wait_limit(-1) == 0
+
+
 def test_out_of_place_step_validation_returns_before_any_launch(lib):
     def status(pi=A, mi=A * 2, vi=A * 3, g=A * 4, po=A * 5, mo=A * 6, vo=A * 7, p16=A * 8, n=16,
                step=1, loss_scale=1024.0, flag=A * 9, flags=0, **over):
