@@ -64,7 +64,7 @@ enum {
     LOHAN_FLAG_P16_FP16 = 4u
 };
 
-/* Device scratch bytes one call needs (a constant of the build; a few tens of KiB). */
+/* Device scratch bytes one call needs (a constant of the build; about 81 KiB). */
 size_t lohan_workspace_bytes(void);
 
 /*
@@ -138,7 +138,7 @@ lohan_status_t lohan_grad_produce_fp16(const float *grad_fp32, uint64_t n, float
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, results and kernels as lohan_grad_sqnorm, minus the workspace: the partial results
  * and the ticket counter live in a static device array of the library (lohan_workspace_bytes()
- * = about 49 KiB, present on every GPU the library runs on until the process ends).  The call
+ * = about 81 KiB, present on every GPU the library runs on until the process ends).  The call
  * allocates nothing, frees nothing and never synchronises.  Its first call on a device resolves
  * that device's copy of the array and enqueues a small fill kernel ahead of the reduction.
  *   n   at most LOHAN_GRAD_SQNORM_STATIC_MAX_N elements, else LOHAN_ERR_TOO_LARGE
@@ -221,9 +221,10 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
  * the device at once; every workgroup loads its share of the block into registers, the
  * workgroups meet at a grid-wide barrier whose counter carries the flag, and the update is
  * computed from registers: 28 bytes per element moved, reads and writes in two separate phases.
- * For a block of a few million elements this takes about two thirds of the time of
- * lohan_grad_sqnorm + lohan_adam_block_step, which there is a chain of launch and memory
- * latencies; blocks that do not fit the device's registers cannot use it.
+ * For a block of a few million elements this takes about four fifths of the time of
+ * lohan_grad_sqnorm + lohan_adam_block_step (30 against 37 microseconds per step for 7 million
+ * elements on MI355X), which there is a chain of launch and memory latencies; blocks that do
+ * not fit the device's registers cannot use it.
  *   n              at most the value lohan_adam_small_block_max_n reports for the device (about
  *                  7.8 million elements on MI355X), else LOHAN_ERR_TOO_LARGE
  *   sqnorm         device, out: one double or NULL; unspecified when the flag is set
@@ -237,9 +238,10 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
  * The barrier's wait is bounded, so every wavefront exits whatever else runs on the device: the
  * workgroups can only all be resident if the compute units are not held by other kernels for
  * good.  Kernels of other streams that finish by themselves merely delay it.  If a workgroup
- * does give up waiting (about a second), *overflow_flag has LOHAN_OVERFLOW_INCOMPLETE set and the
- * block's state is unspecified (some workgroups may have written, others not): treat it as a
- * failed step and restore the block from a checkpoint.  Everything else as lohan_adam_block_step.
+ * does give up waiting (after a third of a second), *overflow_flag has
+ * LOHAN_OVERFLOW_INCOMPLETE set and the block's state is unspecified (some workgroups may have written, others not): treat it as a
+ * failed step and restore the block from a checkpoint; the workspace itself stays usable.
+ * Everything else as lohan_adam_block_step.
  */
 #define LOHAN_OVERFLOW_INCOMPLETE 0x80000000u
 lohan_status_t lohan_adam_small_block_max_n(uint64_t *max_n);

@@ -40,10 +40,10 @@ void lohan_tuning_get_launch_config(int *adam_variant, int *adam_workgroups_per_
 
 /*
  * Bound of the grid-wide wait inside lohan_adam_small_block_step, in polls (one poll is a trip to
- * memory, about a microsecond), for the calls made afterwards by the calling thread; negative =
- * the built-in bound (2^20).  With 0 every workgroup but the one that arrives last gives up at
- * once, which is how the tests reach the LOHAN_OVERFLOW_INCOMPLETE report without anything going
- * wrong on the device.  LOHAN_ERR_ARG above 2^32 - 1.
+ * memory and a short sleep, a third of a microsecond), for the calls made afterwards by the
+ * calling thread; negative = the built-in bound (2^20).  With 0 every workgroup but the one that
+ * arrives last gives up at once, which is how the tests reach the LOHAN_OVERFLOW_INCOMPLETE
+ * report without anything going wrong on the device.  LOHAN_ERR_ARG above 2^32 - 1.
  */
 lohan_status_t lohan_tuning_set_wait_limit(int64_t polls);
 

@@ -40,7 +40,8 @@ constexpr int kDefaultAdamWgsPerCu = 0;                       // one tile per wo
 constexpr int kDefaultAdamWavesPerCu = 11;                    // occupancy throttle
 constexpr int kDefaultReduceWgsPerCu = 4;
 constexpr int kAutoReducePolicy = -1;
-// Polls of the grid-wide wait in the one-launch step before a workgroup gives up (about a second).
+// Polls of the grid-wide wait in the one-launch step before a workgroup gives up (a third of a
+// second).
 constexpr uint32_t kDefaultWaitLimit = 1u << 20;
 
 // Tuning override (lohan_adam_tuning.h): per calling thread, so that a sweep on one thread never

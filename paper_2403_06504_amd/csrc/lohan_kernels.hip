@@ -934,7 +934,8 @@ constexpr uint32_t kOverflowed = 1u, kGaveUp = 2u, kArrivedLast = 4u, kVerdictKn
 
 // Lane 0 of wavefront 0: publish the partial sum, arrive (two levels), and report what is known.
 // counters[0] is the call's top counter; lines: the group lines.  any: this workgroup saw an
-// overflow; tag: this call's.  Returns kArrivedLast (| kOverflowed) in the workgroup after which nobody arrives.
+// overflow; tag: this call's.  Returns kArrivedLast (| kOverflowed) in the workgroup after which
+// nobody arrives.
 __device__ __forceinline__ uint32_t fused_arrive(uint32_t wg, uint32_t nwg, double part, bool any,
                                                  double *partial_sum, uint32_t *counters,
                                                  uint32_t *lines, uint32_t tag)
@@ -1523,7 +1524,8 @@ hipError_t small_block_occupancy(int wgs_per_cu[kSmallVariants])
 // Workgroups of depth i that are resident together on the whole device.
 static uint64_t small_block_grid_limit(const DeviceInfo &dev, int i)
 {
-    uint64_t resident = (uint64_t)dev.cus * (uint64_t)(dev.small_wgs_per_cu[i] > 0 ? dev.small_wgs_per_cu[i] : 0);
+    const int per_cu = dev.small_wgs_per_cu[i] > 0 ? dev.small_wgs_per_cu[i] : 0;
+    const uint64_t resident = (uint64_t)dev.cus * (uint64_t)per_cu;
     return resident < kMaxPartials ? resident : kMaxPartials;
 }
 
