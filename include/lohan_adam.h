@@ -434,9 +434,11 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
  *     (at +2P + 2 MiB) their v arrays, block j of the group at the same offset in each lane;
  *   - the 16-bit arrays (which advance at half the rate and may sit anywhere) fill what is left
  *     of lanes 0 and 1 where they fit and otherwise follow lane 2;
- *   - blocks whose fp32 arrays fit neither period (3.2e9 elements and more) or stay below
- *     256 MiB (fewer than 2^26 elements) are simply packed block by block: p, m, v, g, p16 back
- *     to back (nothing measured better for the former; under 1 % to gain for the latter).
+ *   - blocks whose fp32 arrays fit neither period (3.2e9 elements and more) are packed block by
+ *     block with 1 MiB between p, m, v and the 16-bit arrays, so that p, m and v are an odd
+ *     number of MiB apart (arrays of exactly 12 GiB would otherwise all sit at the same offset
+ *     modulo 4 GiB); blocks whose fp32 arrays stay below 256 MiB (fewer than 2^26 elements) are
+ *     simply packed p, m, v, g, p16 back to back (under 1 % to gain).
  * Every array starts on a 1 MiB boundary relative to the slab base; the base itself needs
  * *slab_alignment (2 MiB).  The price is unused space in lanes 0 and 1: per full group 3 % of the
  * slab for 6B-shaped blocks, 7 % for 13B, 12 % for 30B, 17 % for 70B, 4 % for 135B, 14 % for 175B,

@@ -702,12 +702,17 @@ lohan_status_t lohan_model_placement(uint64_t n, uint32_t num_blocks,
         for (size_t candidate : kPeriods)
             if (period == 0 && wide <= candidate - kGranule) period = candidate;
 
-    if (period == 0) {                            // plain block-major packing
-        const size_t block_bytes = 3 * wide + 2 * narrow;
+    if (period == 0) {
+        // Block-major packing.  Arrays too long for any lane still get the odd number of MiB
+        // between p, m and v (an array of exactly 12 GiB would otherwise put all three at the
+        // same offset modulo 4 GiB, the worst case measured); short ones are packed plainly.
+        const size_t skew = wide >= kSmallest ? kSkew : 0;
+        const size_t block_bytes = 3 * (wide + skew) + 2 * narrow + skew;
         for (uint32_t b = 0; b < num_blocks; ++b) {
             const size_t base = (size_t)b * block_bytes;
-            offsets[b] = lohan_block_offsets_t{base, base + wide, base + 2 * wide,
-                                               base + 3 * wide, base + 3 * wide + narrow};
+            const size_t after = base + 3 * (wide + skew);
+            offsets[b] = lohan_block_offsets_t{base, base + wide + skew, base + 2 * (wide + skew),
+                                               after, after + narrow};
         }
         *slab_bytes = (size_t)num_blocks * block_bytes;
         if (blocks_per_group != nullptr) *blocks_per_group = 1;

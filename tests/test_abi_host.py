@@ -249,7 +249,8 @@ def test_multi_block_step_validation_returns_before_any_launch(lib):
 def test_model_placement_properties(lib):
     """No two arrays overlap, every array starts on a 1 MiB boundary inside the slab, and for
     blocks whose fp32 arrays fit a 4 GiB (else a 12 GiB) period and are not below 256 MiB the
-    three fp32 arrays of a block sit at the same offset in consecutive periods, 1 MiB apart."""
+    three fp32 arrays of a block sit at the same offset in consecutive periods, 1 MiB apart;
+    longer arrays are packed an odd number of MiB apart."""
     gib, mib = 1 << 30, 1 << 20
     cases = [(12 * 5120 ** 2, 40), (12 * 5120 ** 2, 4), (12 * 4096 ** 2, 7), (12 * 7168 ** 2, 2),
              (12 * 8192 ** 2, 1), (12 * 11264 ** 2, 3), (12 * 12288 ** 2, 2), (12 * 14336 ** 2, 2),
@@ -275,17 +276,22 @@ def test_model_placement_properties(lib):
         if wide >= 256 * mib:
             period = 4 * gib if wide <= 4 * gib - 2 * mib else \
                 12 * gib if wide <= 12 * gib - 2 * mib else 0
+        # arrays too long for any lane are packed with an odd number of MiB between p, m, v;
+        # arrays below 256 MiB are packed plainly
+        skew = mib if (not period and wide >= 256 * mib) else 0
         for o in offs:
-            lane = period + mib if period else wide
+            lane = period + mib if period else wide + skew
             assert o["exp_avg"] - o["param_fp32"] == lane
             assert o["exp_avg_sq"] - o["exp_avg"] == lane
+            if skew:
+                assert (lane // mib) % 2 == 1
         if period:
             assert per_group == (period - 2 * mib) // wide >= 1
             first = offs[0]["param_fp32"]
             for j, o in enumerate(offs[:per_group]):          # block j at j arrays into lane 0
                 assert o["param_fp32"] - first == j * wide
         else:
-            assert per_group == 1 and total == nb * (3 * wide + 2 * narrow)
+            assert per_group == 1 and total == nb * (3 * wide + 2 * narrow + 4 * skew)
     # the documented price of full groups
     for n, worst in ((12 * 4096 ** 2, 1.04), (12 * 5120 ** 2, 1.07), (12 * 7168 ** 2, 1.13),
                      (12 * 8192 ** 2, 1.17), (12 * 11264 ** 2, 1.05), (12 * 12288 ** 2, 1.14),
