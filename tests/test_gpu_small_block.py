@@ -299,3 +299,55 @@ def test_small_step_replayed_from_a_hip_graph(oracle):
         small_step(warm, workload(4096).hyper())
         torch.cuda.synchronize()
     assert float(scratch[0].cpu()) == 3.0
+
+
+def test_small_steps_on_a_side_stream_while_gemms_run(oracle):
+    """The one-launch step needs its whole grid resident, so compute units held by another
+    stream's kernels delay it; kernels that finish by themselves (GEMMs here) must do no more
+    than that.  h=768 blocks, each step behind its GEMM's event, GEMMs kept running on the main
+    stream: every step complete (no incomplete bit) and equal to the oracle."""
+    nblocks, n = 6, synth.WORKLOADS["gpt_h768"].n
+    wl = workload(n)
+    hy = wl.hyper()
+    blocks = [DeviceBlock(synth.make_block(wl, seed=200 + i, device=DEV)) for i in range(nblocks)]
+    hosts = [b.host() for b in blocks]
+    side = torch.cuda.Stream()
+    a = torch.randn(4096, 4096, device=DEV, dtype=torch.bfloat16)
+    b = torch.randn(4096, 8192, device=DEV, dtype=torch.bfloat16)
+    main = torch.cuda.current_stream()
+    for i in reversed(range(nblocks)):
+        torch.matmul(a, b)
+        ev = torch.cuda.Event()
+        ev.record(main)
+        side.wait_event(ev)
+        small_step(blocks[i], hy, stream=side)
+        for _ in range(4):                      # GEMMs that overlap the step
+            torch.matmul(a, b)
+    side.synchronize()
+    torch.cuda.synchronize()
+    for i in range(nblocks):
+        assert blocks[i].flag_value() == 0, hex(blocks[i].flag_value() & 0xFFFFFFFF)
+        assert oracle_steps(oracle, hosts[i], hy, 1) == [0]
+        assert assert_state_parity(blocks[i].host(), hosts[i], what=f"block {i}") == ZERO_ULP
+
+
+def test_two_streams_with_grids_that_fit_together(oracle):
+    """Two one-launch steps may run at the same time when their grids fit the device together
+    (here 98 workgroups each); grids that do not fit together must be ordered by the caller."""
+    n = 300_001
+    wl = workload(n)
+    hy = wl.hyper()
+    blocks = [DeviceBlock(synth.make_block(wl, seed=300 + i, device=DEV)) for i in range(8)]
+    hosts = [b.host() for b in blocks]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for s in streams:
+        s.wait_stream(torch.cuda.current_stream())
+    for k in range(3):
+        for i, blk in enumerate(blocks):
+            small_step(blk, dict(hy, step=hy["step"] + k), stream=streams[i % 2])
+    for s in streams:
+        s.synchronize()
+    for i, blk in enumerate(blocks):
+        assert blk.flag_value() == 0
+        assert oracle_steps(oracle, hosts[i], hy, 3, nthreads=8) == [0] * 3
+        assert assert_state_parity(blk.host(), hosts[i], what=f"block {i}") == ZERO_ULP
