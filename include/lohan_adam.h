@@ -238,12 +238,13 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
  * The barrier's wait is bounded, so every wavefront exits whatever else runs on the device: the
  * workgroups can only all be resident if the compute units are not held by other kernels for
  * good.  Kernels of other streams that finish by themselves merely delay it; two calls of THIS
- * entry point that may run at the same time on one device (two streams) must have grids that fit
- * the device together (on MI355X: n1 + n2 at most 5 million), or be ordered by the caller: otherwise
- * each holds the compute units the other waits for, and both give up.  If a workgroup
+ * entry point that may run at the same time on one device (two streams) must have grids that
+ * fit the device together (on MI355X: n1 + n2 at most 5 million), or be ordered by the caller:
+ * otherwise each holds the compute units the other waits for, and both give up.  If a workgroup
  * does give up waiting (after a third of a second), *overflow_flag has
- * LOHAN_OVERFLOW_INCOMPLETE set and the block's state is unspecified (some workgroups may have written, others not): treat it as a
- * failed step and restore the block from a checkpoint; the workspace itself stays usable.
+ * LOHAN_OVERFLOW_INCOMPLETE set and the block's state is unspecified (some workgroups may have
+ * written, others not): treat it as a failed step and restore the block from a checkpoint; the
+ * workspace itself stays usable.
  * Everything else as lohan_adam_block_step.
  */
 #define LOHAN_OVERFLOW_INCOMPLETE 0x80000000u
