@@ -118,10 +118,35 @@ int main(int argc, char **argv)
     printf("flag %u state_bit_identical %d sqnorm_rel_err %.3e\n", flag, same,
            fabs(sq - want_sq) / want_sq);
 
+    /* a fourth step in ONE launch, where the block is small enough for it */
+    uint64_t small_max = 0;
+    LOHAN_OK_OR_DIE(lohan_adam_small_block_max_n(&small_max));
+    if (n <= small_max) {
+        LOHAN_OK_OR_DIE(lohan_adam_small_block_step(dp, dm, dv, dg, dh, n, lr, b1, b2, eps, wd,
+                                                    103, S, dsq, dflag, 0, ws,
+                                                    lohan_workspace_bytes(), stream));
+        HIP_OK(hipStreamSynchronize(stream));
+        HIP_OK(hipMemcpy(&flag, dflag, 4, hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(&sq, dsq, 8, hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(gp, dp, n * 4, hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(gm, dm, n * 4, hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(gv, dv, n * 4, hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(gh, dh, n * 2, hipMemcpyDeviceToHost));
+        if (lohan_oracle_adam_block_step(p, m, v, g, h, n, lr, b1, b2, eps, wd, 103, S, 0, 0,
+                                         8) != 0)
+            return 5;
+        printf("small_block flag %u state_bit_identical %d sqnorm_rel_err %.3e\n", flag,
+               memcmp(gp, p, n * 4) == 0 && memcmp(gm, m, n * 4) == 0 &&
+                   memcmp(gv, v, n * 4) == 0 && memcmp(gh, h, n * 2) == 0,
+               fabs(sq - want_sq) / want_sq);
+    } else {
+        printf("small_block skipped: n exceeds %llu\n", (unsigned long long)small_max);
+    }
+
     /* an overflowing block: flag 1, state untouched (the self-checking step this time) */
     const uint16_t inf16 = 0x7C00;
     HIP_OK(hipMemcpy((char *)dg + 2 * (n / 2), &inf16, 2, hipMemcpyHostToDevice));
-    LOHAN_OK_OR_DIE(lohan_adam_block_step(dp, dm, dv, dg, dh, n, lr, b1, b2, eps, wd, 103, S,
+    LOHAN_OK_OR_DIE(lohan_adam_block_step(dp, dm, dv, dg, dh, n, lr, b1, b2, eps, wd, 104, S,
                                           dflag, 0, ws, lohan_workspace_bytes(), stream));
     HIP_OK(hipStreamSynchronize(stream));
     HIP_OK(hipMemcpy(&flag, dflag, 4, hipMemcpyDeviceToHost));

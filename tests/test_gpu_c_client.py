@@ -21,4 +21,10 @@ def test_plain_c_program_matches_the_oracle(n):
     first = dict(zip(lines[0].split()[::2], lines[0].split()[1::2]))
     assert first["flag"] == "0" and first["state_bit_identical"] == "1", run.stdout
     assert float(first["sqnorm_rel_err"]) <= 1e-5
-    assert lines[1] == "overflow_flag 1 untouched 1", run.stdout
+    if n <= 5_000_000:                      # far below any device's limit for the one-launch step
+        small = dict(zip(lines[1].split()[1::2], lines[1].split()[2::2]))
+        assert small["flag"] == "0" and small["state_bit_identical"] == "1", run.stdout
+        assert float(small["sqnorm_rel_err"]) <= 1e-5
+    else:
+        assert lines[1].startswith("small_block skipped"), run.stdout
+    assert lines[2] == "overflow_flag 1 untouched 1", run.stdout
