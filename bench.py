@@ -730,11 +730,11 @@ def bench_stream(args, torch, lohan, synth):
 
     # A one-tile probe launch between the phases: a kernel of a distinctive name in a rocprofv3
     # kernel trace, so that the trace can be cut into the phases below.
-    mark_buf = torch.zeros(256, dtype=torch.float32, device=dev)
+    mark_buf = torch.zeros(2048, dtype=torch.float32, device=dev)   # one workgroup's worth
 
     def phase_marker():
         torch.cuda.synchronize()
-        lohan.lohan_tuning_probe(lohan.LOHAN_PROBE_READ, mark_buf, None, None, None, None, 256)
+        lohan.lohan_tuning_probe(lohan.LOHAN_PROBE_READ, mark_buf, None, None, None, None, 2048)
         torch.cuda.synchronize()
 
     for w in range(args.warmup):
