@@ -49,7 +49,7 @@ def parse_args():
     ap.add_argument("--workload", default="default",
                     choices=["default", "gpt13b", "gpt175b", "gpt_h768", "stream13b", "offload13b",
                              "shapes", "gpt13b_oop", "gpt175b_oop", "models", "ring13b",
-                             "ceiling"],
+                             "ceiling", "placement13b", "placement175b"],
                     help="default = the 175B-shaped block (headline) with the 13B-shaped block "
                          "nested under 'gpt13b'")
     ap.add_argument("--variant", type=int, default=None, help="kernel launch-shape override")
@@ -1129,6 +1129,82 @@ def bench_models(args, torch, lohan, synth):
     }
 
 
+def bench_placement_sweep(args, torch, lohan, synth):
+    """How much the relative position of p, m and v matters, and where the library's choice sits:
+    the update kernel on one block inside the default bench's arena, p at the arena's start, m at
+    one lane period + a MiB, v at two periods + b MiB, for a, b in 0..16 (the output names the
+    pair lohan_model_placement uses); every layout in turn, `--steps` rounds, median per layout."""
+    import statistics
+    dev = "cuda:0"
+    wl = synth.WORKLOADS["gpt13b" if args.workload == "placement13b" else "gpt175b"]
+    n = wl.n
+    mib = 1 << 20
+    need = max(sum(lohan.lohan_model_placement(synth.WORKLOADS[w].n)[1:3])
+               for w in ("gpt175b", "gpt13b"))
+    slab = torch.empty(need + 64 * mib, dtype=torch.uint8, device=dev)
+    offsets, _, align, _ = lohan.lohan_model_placement(n)
+    lib = offsets[0]
+    base = (-slab.data_ptr()) % align
+    gib = 1 << 30
+    period = (lib["exp_avg"] - lib["param_fp32"]) // gib * gib
+    lib_a = (lib["exp_avg"] - lib["param_fp32"] - period) // mib
+    lib_b = (lib["exp_avg_sq"] - lib["param_fp32"] - 2 * period) // mib
+    src = synth.make_block(wl, seed=0, device=dev)
+    spec = {"p": (torch.float32, 4), "m": (torch.float32, 4), "v": (torch.float32, 4),
+            "g": (torch.float16, 2), "p16": (torch.bfloat16, 2)}
+
+    def views(a, b):
+        off = {"p": 0, "m": period + a * mib, "v": 2 * period + b * mib,
+               "g": lib["grad_fp16"] + 32 * mib, "p16": lib["param_bf16"] + 32 * mib}
+        return {k: slab[base + off[k]: base + off[k] + n * spec[k][1]].view(spec[k][0])
+                for k in off}
+
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    hy = wl.hyper()
+    rounds = min(args.steps, 8)
+    skews = list(range(17))
+    records = {(a, b): [] for a in skews for b in skews}
+    for r in range(rounds):
+        for key, rec in records.items():
+            v = views(*key)
+            for k in v:
+                v[k].copy_(src[k])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for rep in range(3):
+                if rep == 1:
+                    e0.record()
+                lohan.lohan_adam_block_step(v["p"], v["m"], v["v"], v["g"], v["p16"], n,
+                                            hy["lr"], hy["beta1"], hy["beta2"], hy["eps"],
+                                            hy["weight_decay"], hy["step"] + r, hy["loss_scale"],
+                                            flag, lohan.LOHAN_FLAG_PRECHECKED, None)
+            e1.record()
+            rec.append((e0, e1))
+    torch.cuda.synchronize()
+    frac = {key: ADAM_BYTES_PER_ELEM * n /
+            (statistics.median(a.elapsed_time(b) / 2 for a, b in rec) * 1e-3) / 1e9 / HBM_PEAK_GBPS
+            for key, rec in records.items()}
+    best = max(frac, key=frac.get)
+    ranked = sorted(frac.values())
+    return {
+        "metric": "adam_kernel_fraction_of_hbm_peak_by_placement", "value": frac[(lib_a, lib_b)],
+        "unit": "fraction of 8 TB/s", "n_gpus": 1, "steps": rounds, "warmup": 1,
+        "ms_per_step": ADAM_BYTES_PER_ELEM * n / (frac[(lib_a, lib_b)] * HBM_PEAK_GBPS * 1e9) * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: update kernel on one {wl.name} block, m at one "
+                               "lane period + a MiB and v at two periods + b MiB from p, a and b "
+                               "in 0..16, inside the default bench's arena",
+                   "elements": n, "lane_period_mib": period // mib, "rounds": rounds},
+        "library_choice": {"a": lib_a, "b": lib_b, "frac": frac[(lib_a, lib_b)]},
+        "former_choice": {"a": 1, "b": 2, "frac": frac[(1, 2)]},
+        "best": {"a": best[0], "b": best[1], "frac": frac[best]},
+        "worst_frac": ranked[0], "median_frac": ranked[len(ranked) // 2],
+        "rank_of_library_choice": sum(1 for f in ranked if f > frac[(lib_a, lib_b)]) + 1,
+        "table_rows_a_columns_b": [[round(frac[(a, b)], 4) for b in skews] for a in skews],
+        "cpu_baseline": None,
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -1165,6 +1241,8 @@ def main():
         out = bench_models(args, torch, lohan, synth)
     elif args.workload == "ring13b":
         out = bench_ring(args, torch, lohan, synth)
+    elif args.workload.startswith("placement"):
+        out = bench_placement_sweep(args, torch, lohan, synth)
     elif args.workload.endswith("_oop"):
         out = bench_block_oop(args, torch, lohan, synth)
     else:

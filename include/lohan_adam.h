@@ -427,15 +427,18 @@ lohan_status_t lohan_adam_multi_block_step(const lohan_block_t *blocks, uint32_t
  * block sit relative to each other moves the update kernel by several percent on MI355X: p, m
  * and v advance at the same rate, so their relative position is fixed for a whole launch, and
  * the measured best is "same offset within consecutive periods of 4 GiB (or 12 GiB), shifted by
- * 1 MiB each" (6.80-6.90 TB/s for a 13B-shaped block); the allocator's placement is a lottery
+ * a few MiB" (6.85-6.92 TB/s for a 13B-shaped block); the allocator's placement is a lottery
  * between -4 % and 0 % of that, and all three arrays at the same offset modulo 4 GiB is the worst
  * case.  This function lays out the tensors of Table II for num_blocks equal blocks of n
  * elements inside ONE caller-allocated slab accordingly:
  *   - the period P is 4 GiB if one fp32 array fits into 4 GiB - 2 MiB, else 12 GiB if it fits
  *     into 12 GiB - 2 MiB;
  *   - groups of G = floor((P - 2 MiB) / bytes(p)) consecutive blocks share three "lanes":
- *     lane 0 holds their p arrays back to back, lane 1 (at +P + 1 MiB) their m arrays, lane 2
- *     (at +2P + 2 MiB) their v arrays, block j of the group at the same offset in each lane;
+ *     lane 0 holds their p arrays back to back, lane 1 their m arrays, lane 2 their v arrays,
+ *     block j of the group at the same offset in each lane; lanes 1 and 2 start at P + 8 MiB and
+ *     2P + 9 MiB for the 4 GiB period and at P + 1 MiB and 2P + 2 MiB for the 12 GiB period (the
+ *     best of the pairs measured: m and v an odd number of MiB apart, no two of the three at the
+ *     same offset modulo 16 MiB);
  *   - the 16-bit arrays (which advance at half the rate and may sit anywhere) fill what is left
  *     of lanes 0 and 1 where they fit and otherwise follow lane 2;
  *   - blocks whose fp32 arrays fit neither period (3.2e9 elements and more) are packed block by
@@ -483,9 +486,9 @@ lohan_status_t lohan_model_placement_compact(uint64_t n, uint32_t num_blocks,
  * count of unit i; units keep their order.  The rule is lohan_model_placement's: the period P is
  * chosen for the LONGEST fp32 array (4 GiB, else 12 GiB); maximal runs of consecutive units whose
  * fp32 arrays fit one lane together form a group; within a group all p arrays sit back to back
- * in lane 0, the m arrays at the same offsets in lane 1 (+P + 1 MiB), the v arrays in lane 2
- * (+2P + 2 MiB); the 16-bit arrays fill the room left in lanes 0 and 1, first fit, and otherwise
- * follow lane 2.  Arrays of 2 MiB and more start on 1 MiB boundaries, smaller ones on 4 KiB
+ * in lane 0, the m arrays at the same offsets in lane 1, the v arrays in lane 2 (lane starts as
+ * in lohan_model_placement); the 16-bit arrays fill the room left in lanes 0 and 1, first fit,
+ * and otherwise follow lane 2.  Arrays of 2 MiB and more start on 1 MiB boundaries, smaller ones on 4 KiB
  * boundaries (so a model's many short vectors cost little).  If the longest fp32 array is below
  * 256 MiB or fits neither period, the units are packed one after the other (p, m, v, g, p16).
  * For equal lengths of 2^26 elements and more the offsets equal lohan_model_placement's.

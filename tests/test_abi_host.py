@@ -249,8 +249,8 @@ def test_multi_block_step_validation_returns_before_any_launch(lib):
 def test_model_placement_properties(lib):
     """No two arrays overlap, every array starts on a 1 MiB boundary inside the slab, and for
     blocks whose fp32 arrays fit a 4 GiB (else a 12 GiB) period and are not below 256 MiB the
-    three fp32 arrays of a block sit at the same offset in consecutive periods, 1 MiB apart;
-    longer arrays are packed an odd number of MiB apart."""
+    three fp32 arrays of a block sit at the same offset in consecutive lanes (whose starts are
+    skewed by a few MiB against the period); longer arrays are packed an odd number of MiB apart."""
     gib, mib = 1 << 30, 1 << 20
     cases = [(12 * 5120 ** 2, 40), (12 * 5120 ** 2, 4), (12 * 4096 ** 2, 7), (12 * 7168 ** 2, 2),
              (12 * 8192 ** 2, 1), (12 * 11264 ** 2, 3), (12 * 12288 ** 2, 2), (12 * 14336 ** 2, 2),
@@ -279,12 +279,16 @@ def test_model_placement_properties(lib):
         # arrays too long for any lane are packed with an odd number of MiB between p, m, v;
         # arrays below 256 MiB are packed plainly
         skew = mib if (not period and wide >= 256 * mib) else 0
+        # lanes 1 and 2: at the period + 8 MiB and twice the period + 9 MiB for the 4 GiB period,
+        # + 1 and + 2 MiB for the 12 GiB period
+        lane1, lane2 = {4 * gib: (4 * gib + 8 * mib, 8 * gib + 9 * mib),
+                        12 * gib: (12 * gib + mib, 24 * gib + 2 * mib),
+                        0: (wide + skew, 2 * (wide + skew))}[period]
         for o in offs:
-            lane = period + mib if period else wide + skew
-            assert o["exp_avg"] - o["param_fp32"] == lane
-            assert o["exp_avg_sq"] - o["exp_avg"] == lane
-            if skew:
-                assert (lane // mib) % 2 == 1
+            assert o["exp_avg"] - o["param_fp32"] == lane1
+            assert o["exp_avg_sq"] - o["param_fp32"] == lane2
+            if period or skew:                   # m and v an odd number of MiB apart
+                assert ((lane2 - lane1) // mib) % 2 == 1
         if period:
             assert per_group == (period - 2 * mib) // wide >= 1
             first = offs[0]["param_fp32"]
@@ -413,8 +417,8 @@ def test_compact_placement_properties(lib):
 
 def test_tensor_placement_properties(lib):
     """Per-tensor placement: inside the slab, aligned, disjoint, p/m/v of one tensor at the same
-    offset within lanes one period + 1 MiB apart, and equal to the equal-block placement when the
-    lengths are equal."""
+    offset within the three lanes, and equal to the equal-block placement when the lengths are
+    equal."""
     mib, gib = 1 << 20, 1 << 30
     h = 5120
     one_layer = [3 * h * h, 3 * h, h * h, h, 4 * h * h, 4 * h, 4 * h * h, h, h, h, h, h]
@@ -436,9 +440,11 @@ def test_tensor_placement_properties(lib):
         widest = max(lengths) * 4
         if 256 * mib <= widest <= 12 * gib - 2 * mib:
             period = 4 * gib if widest <= 4 * gib - 2 * mib else 12 * gib
+            lane1, lane2 = ((period + 8 * mib, 2 * period + 9 * mib) if period == 4 * gib
+                            else (period + mib, 2 * period + 2 * mib))
             for o in offsets:
-                assert o["exp_avg"] - o["param_fp32"] == period + mib
-                assert o["exp_avg_sq"] - o["exp_avg"] == period + mib
+                assert o["exp_avg"] - o["param_fp32"] == lane1
+                assert o["exp_avg_sq"] - o["param_fp32"] == lane2
         payload = 16 * sum(lengths)
         assert total >= payload
     # equal lengths of 2^26 elements and more: the same offsets as lohan_model_placement
@@ -491,7 +497,7 @@ def test_plain_c_client_builds_and_runs(lib, tmp_path):
     assert int(lines["workspace_bytes"]) == lohan.lohan_workspace_bytes()
     assert lines["status_3"] == lohan.lohan_status_string(3)
     assert lines["clip"] == "2346.2798"
-    assert lines["placement"] == f"0 group 3 lane {(4 << 30) + (1 << 20)} align {2 << 20}"
+    assert lines["placement"] == f"0 group 3 lane {(4 << 30) + (8 << 20)} align {2 << 20}"
     assert lines["null_step"] == "1"
     assert lines["plan"] == "0 n 2 first 1 a 30.0 f 100.0 t 19.00"
     assert lines["flops"] == "0 200.0 -10.0"

@@ -662,7 +662,8 @@ def test_step_can_be_captured_in_a_hip_graph(oracle):
 
 def test_13b_blocks_in_the_library_placement(oracle):
     """The layout bench.py times: a full group of 13B-shaped blocks inside one slab at the offsets
-    lohan_model_placement gives (fp32 arrays in three lanes one 4 GiB period + 1 MiB apart).  All
+    lohan_model_placement gives (fp32 arrays in three lanes, 4 GiB + 8 MiB and 8 GiB + 9 MiB from
+    the first).  All
     blocks are stepped; block 0 is compared with the oracle over every element, the others on
     sampled ranges -- an overlap between any two arrays would corrupt one of them."""
     wl = synth.WORKLOADS["gpt13b"]
@@ -683,8 +684,8 @@ def test_13b_blocks_in_the_library_placement(oracle):
             placed[k].copy_(src[k])
         blocks.append(DeviceBlock(placed))
         del src
-    assert blocks[0].m.data_ptr() - blocks[0].p.data_ptr() == (4 << 30) + (1 << 20)
-    assert blocks[0].v.data_ptr() - blocks[0].m.data_ptr() == (4 << 30) + (1 << 20)
+    assert blocks[0].m.data_ptr() - blocks[0].p.data_ptr() == (4 << 30) + (8 << 20)
+    assert blocks[0].v.data_ptr() - blocks[0].p.data_ptr() == (8 << 30) + (9 << 20)
     span = 1 << 21
     rng = np.random.default_rng(17)
     starts = [0, n - span] + [int(x) for x in rng.integers(span, n - 2 * span, size=2)]
