@@ -486,7 +486,10 @@ def test_device_side_clipping(oracle, n, S, max_norm):
 
 @pytest.mark.parametrize("S", [65536.0, 1024.0, 3000.0, 1.0])
 def test_sqnorm_parity_and_determinism(oracle, S):
-    for n in (0, 1, 5, 8, 2047, 8192, 8193, 65537, 3_000_001, 40_000_003):
+    # 4096 elements per workgroup: 131072 / 135168 elements are 32 / 33 workgroups, the sizes at
+    # which the ticket goes from one level to two; 4_190_209 makes 1023 + a ragged last group
+    for n in (0, 1, 5, 8, 2047, 8192, 8193, 65537, 131_072, 131_073, 135_168, 262_149,
+              3_000_001, 4_190_209, 40_000_003):
         wl = small_workload(n, S=S)
         blk = DeviceBlock(synth.make_block(wl, seed=n % 97, device=DEV))
         blk.norm(S)
