@@ -221,10 +221,10 @@ lohan_status_t lohan_adam_block_step_clipped(float *param_fp32, float *exp_avg, 
  * the device at once; every workgroup loads its share of the block into registers, the
  * workgroups meet at a grid-wide barrier whose counter carries the flag, and the update is
  * computed from registers: 28 bytes per element moved, reads and writes in two separate phases.
- * For a block of a few million elements this takes about four fifths of the time of
- * lohan_grad_sqnorm + lohan_adam_block_step (30 against 37 microseconds per step for 7 million
- * elements on MI355X), which there is a chain of launch and memory latencies; blocks that do
- * not fit the device's registers cannot use it.
+ * For a block of a few million elements this takes four fifths to nineteen twentieths of the
+ * time of lohan_grad_sqnorm + lohan_adam_block_step (30-36 against 37 microseconds per step for
+ * 7 million elements on MI355X), which there is a chain of launch and memory latencies; blocks
+ * that do not fit the device's registers cannot use it.
  *   n              at most the value lohan_adam_small_block_max_n reports for the device (about
  *                  7.8 million elements on MI355X), else LOHAN_ERR_TOO_LARGE
  *   sqnorm         device, out: one double or NULL; unspecified when the flag is set
