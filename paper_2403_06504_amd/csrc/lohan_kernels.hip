@@ -968,8 +968,18 @@ __device__ __forceinline__ uint32_t fused_arrive(uint32_t wg, uint32_t nwg, doub
     return kArrivedLast | kVerdictKnown | ((now >> 16) != 0u ? kOverflowed : 0u);
 }
 
+// Scalar registers count against residency too, and the runtime's occupancy query does not see
+// it.  Measured: compiled freely the shallowest kernel used 79 SGPRs (85 with VCC and friends),
+// the runtime reported 8 workgroups per compute unit, and yet grids of 1,800 and more workgroups
+// never completed their barrier while 1,792 = 7 x 256 always did; held to 64 SGPRs, 2,048 are
+// resident.  That fits a wavefront being charged 16 more than its own (the trap handler's) in
+// granules of 16 out of 800 per SIMD: 85 + 16 -> 112, seven times; 68 + 16 -> 96, eight times.
+// The attribute takes no template argument, so the deeper kernels, which need only 4 and 2
+// wavefront slots per SIMD, are held to 64 as well; the spills go to lanes of a vector register
+// and cost nothing measurable.
 template <int K, int MODE>
-__global__ __launch_bounds__(kFusedThreads) void k_adam_small_block_step(
+__global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_num_sgpr(64)))
+void k_adam_small_block_step(
     float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
     const uint16_t *__restrict__ g, uint16_t *__restrict__ p16, uint64_t n, StepScalars s,
     double *partial_sum, uint32_t *counters, uint32_t *lines,
@@ -1499,8 +1509,6 @@ static adam_small_kernel_t small_kernel(int depth_index, int mode)
     }
 }
 
-constexpr int kSmallMaxWgsPerCu = 7;
-
 hipError_t small_block_occupancy(int wgs_per_cu[kSmallVariants])
 {
     for (int i = 0; i < kSmallVariants; ++i) {
@@ -1512,10 +1520,8 @@ hipError_t small_block_occupancy(int wgs_per_cu[kSmallVariants])
             if (e != hipSuccess) return e;
             if (mode == 0 || resident < lowest) lowest = resident;
         }
-        // Measured: a grid that needs every wavefront slot of every compute unit (8 workgroups
-        // of 4 wavefronts) is NOT resident all at once although the runtime reports it as
-        // fitting; 7 workgroups per compute unit are.  Never count on the last slot.
-        if (lowest > kSmallMaxWgsPerCu) lowest = kSmallMaxWgsPerCu;
+        // (What the runtime reports rests on vector registers, LDS and wavefront slots; the
+        // kernels' scalar registers are kept out of the way at compile time, see above.)
         wgs_per_cu[i] = lowest;
     }
     return hipSuccess;
