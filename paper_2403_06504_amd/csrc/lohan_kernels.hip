@@ -670,7 +670,7 @@ __global__ __launch_bounds__(WG) void k_adam_multi_block_step(MultiArgs args, St
 // whose gradients turn out to hold inf/NaN loses nothing: the kernel raises *flag (cleared by a
 // one-lane kernel ahead of it) and the caller discards the outputs.  Each wavefront tests the
 // gradient bits it has loaded anyway; only a wavefront that found a non-finite value touches
-// *flag, with a vector atomic OR.
+// *flag, with a plain vector store of 1.
 template <int WG, int UNROLL, int POLICY, int MODE>
 __device__ __forceinline__ void adam_oop_body(
     const float *__restrict__ pi, const float *__restrict__ mi, const float *__restrict__ vi,
@@ -759,8 +759,11 @@ __global__ __launch_bounds__(WG) void k_adam_block_step_oop(
     if (inv_override != nullptr) s.inv = *inv_override;
     uint32_t ovf = 0;
     adam_oop_body<WG, UNROLL, POLICY, MODE>(pi, mi, vi, g, po, mo, vo, p16, n, s, ovf);
-    if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0 && (threadIdx.x & 63u) == 0)
-        atomicOr(flag, 1u);
+    // Raising the flag is a plain store: the flag was cleared ahead of this launch and every
+    // writer writes the same 1, so nothing needs to be atomic -- and a block whose gradients are
+    // mostly non-finite (the usual way to overflow) would otherwise queue a million atomics on
+    // one address, 12 ns apiece (measured: 12.9 ms instead of 1.3 ms).
+    if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0 && (threadIdx.x & 63u) == 0) *flag = 1u;
 }
 
 // Ring form of the out-of-place step: the blocks (or single tensors) of a model live in slots
@@ -770,9 +773,9 @@ __global__ __launch_bounds__(WG) void k_adam_block_step_oop(
 // unless the gradients overflowed, in which case nothing changes.  Which slot holds which block
 // is a table in device memory, so no host decision (and no host synchronisation) sits between
 // the blocks of a backward pass.  Every block counts its attempts (steps enqueued so far); an
-// overflowing step records its attempt number with an atomic max, which needs no clearing and
-// tells "the latest attempt overflowed" from any older one.  A step whose n is not the length
-// the block was registered with touches nothing and is recorded like an overflow.
+// overflowing step records its attempt number (attempt numbers only grow, so the record needs no
+// clearing) and so tells "the latest attempt overflowed" from any older one.  A step whose n is
+// not the length the block was registered with touches nothing and is recorded like an overflow.
 template <int WG, int UNROLL, int POLICY, int MODE>
 __global__ __launch_bounds__(WG) void k_adam_ring_step(
     const RingSlot *__restrict__ slots, const uint32_t *__restrict__ slot_of,
@@ -793,8 +796,10 @@ __global__ __launch_bounds__(WG) void k_adam_ring_step(
     uint32_t ovf = 0;
     adam_oop_body<WG, UNROLL, POLICY, MODE>(in.p, in.m, in.v, g, out.p, out.m, out.v, out.p16, n,
                                             s, ovf);
+    // A plain store, as in k_adam_block_step_oop: every writer of this launch writes the same
+    // attempt number, and the steps of one block are ordered, so older values are smaller.
     if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0 && (threadIdx.x & 63u) == 0)
-        atomicMax(overflow_attempt + block, attempt);
+        overflow_attempt[block] = attempt;
 }
 
 __global__ void k_ring_commit(uint32_t *__restrict__ slot_of,

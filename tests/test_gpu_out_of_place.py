@@ -115,6 +115,30 @@ def test_overflow_raises_the_flag_and_the_inputs_survive(oracle, n):
                 assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
 
 
+def test_every_gradient_non_finite(oracle):
+    """The usual way to overflow: all of a block's gradients are inf or NaN, so every wavefront
+    raises the flag.  Flag 1, inputs bit-identical; a clean step afterwards is taken."""
+    n = 5_000_011
+    wl = small_workload(n)
+    hy = wl.hyper()
+    blk = TwoSets(synth.make_block(wl, seed=9, device=DEV))
+    clean_g = blk.g.clone()
+    pattern = torch.tensor([0x7C00, -0x400, 0x7E00, 0x7FFF], dtype=torch.int16, device=DEV)
+    blk.g.view(torch.int16).copy_(pattern.repeat((n + 3) // 4)[:n])
+    before = blk.host()
+    assert oracle.grad_overflow_check(before["g"]) == 1
+    assert blk.step(hy) == 1
+    after = blk.host()
+    for k in ("p", "m", "v"):
+        assert np.array_equal(after[k].view(np.uint32), before[k].view(np.uint32)), k
+    blk.g.copy_(clean_g)
+    host = blk.host()
+    assert blk.step(hy) == 0
+    assert oracle_steps(oracle, host, hy, 1, nthreads=8) == [0]
+    worst = assert_state_parity(blk.host(), host, what="clean step after an all-NaN one")
+    assert worst == {"p": 0, "m": 0, "v": 0, "p16": 0}
+
+
 def test_every_kernel_variant_out_of_place(oracle):
     n = 1_000_003
     wl = small_workload(n)

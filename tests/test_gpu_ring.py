@@ -124,6 +124,39 @@ def test_three_passes_with_an_overflow_in_the_second(oracle, n):
     r.check(slot_of3, "pass 3")
 
 
+def test_a_block_whose_every_gradient_is_non_finite_stays_put(oracle):
+    """Every wavefront of the step records the overflow (the usual way a block overflows); the
+    block keeps its slot bit for bit and the next clean pass goes through."""
+    n = 3_000_001
+    r = Ring(n, 3, seed0=30)
+    t = r.hy["step"]
+    clean = r.g[1].clone()
+    r.g[1].view(torch.int16).fill_(0x7E00)
+    before = r.host_of_slot(1, 1)
+    r.one_pass(t)
+    slot_of, _, last = r.read()
+    assert r.oracle_pass(oracle, t) == [0, 1, 0] and last == [0, 1, 0]
+    assert slot_of[1] == 1
+    after = r.host_of_slot(1, 1)
+    for k in ("p", "m", "v", "p16"):
+        assert np.array_equal(after[k].view(np.uint8), before[k].view(np.uint8)), k
+    r.check(slot_of, "pass with an all-NaN block")
+    r.g[1].copy_(clean)
+    hy = r.hy
+    for b in reversed(range(3)):
+        step = t if b == 1 else t + 1
+        lohan.lohan_ring_adam_block_step(r.ring, 3, 1, b, r.g[b], n, hy["lr"], hy["beta1"],
+                                         hy["beta2"], hy["eps"], hy["weight_decay"], step,
+                                         hy["loss_scale"], 0)
+        h = r.host[b]
+        h["g"] = synth.to_numpy_bits(r.g[b])
+        assert oracle.adam_block_step(h["p"], h["m"], h["v"], h["g"], h["p16"], nthreads=4,
+                                      **dict(hy, step=step)) == 0
+    slot_of2, _, last2 = r.read()
+    assert last2 == [0, 0, 0]
+    r.check(slot_of2, "clean pass after it")
+
+
 @pytest.mark.parametrize("flags", [lohan.LOHAN_FLAG_L2_MODE, lohan.LOHAN_FLAG_P16_FP16,
                                    lohan.LOHAN_FLAG_L2_MODE | lohan.LOHAN_FLAG_P16_FP16])
 def test_ring_mode_flags(oracle, flags):
